@@ -1,0 +1,152 @@
+/* usp.h -- C ABI of the MI355X (gfx950) USP attention library.
+ *
+ * USP = unified Ulysses x Ring sequence-parallel attention (arxiv 2405.07719, Sec. 3,
+ * Algorithm 1).  This library runs one rank's share of that path on ONE GPU; the other
+ * ranks of the SP group are "virtual": their shards live in the same device buffers,
+ * the Ulysses all-to-all is a local permutation and the ring is a loop over resident
+ * K/V blocks.  No inter-GPU communication happens here.
+ *
+ * Conventions for every entry point
+ *   - returns a usp_status (0 = USP_OK); never throws, aborts or synchronises;
+ *   - all tensor pointers are DEVICE pointers owned by the caller, dense, row-major in
+ *     the stated shape; the library keeps no reference after return;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream);
+ *   - arguments are validated on the host BEFORE any launch; on error nothing is enqueued;
+ *   - no device memory is allocated: scratch comes from the caller (`workspace`), its
+ *     size from the matching *_workspace_bytes query (host only, works without a GPU).
+ *
+ * Notation (Sec. 2, notation table): L sequence length, hc head count, hs head size,
+ * bs batch.  Added: hk = KV head count (GQA), U = Ulysses degree, R = ring degree,
+ * N = U*R (Sec. 3), Lq = L/R, hq = hc/U, hkv = hk/U.
+ * Virtual rank numbering: rank = r*U + u, Ulysses fastest (Sec. 4, Tip 7 ordering).
+ *
+ * Buffer layouts
+ *   seq layout  : [N][bs][L/N][heads][hs]     one input/output shard per rank (Sec. 3)
+ *   head layout : [N][bs][L/R][heads/U][hs]   after the forward all-to-all
+ *   lse         : [N][bs][hc/U][L/R] float    rank-local head layout (Algorithm 1
+ *                                             all-to-alls only O back)
+ */
+#ifndef USP_H_
+#define USP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(USP_BUILDING)
+#pragma GCC visibility push(default)
+#endif
+
+typedef enum {
+  USP_OK = 0,
+  USP_ERR_NULL = 1,        /* a required pointer is NULL */
+  USP_ERR_SHAPE = 2,       /* non-positive size; L not divisible by N (contiguous) or 2*R*U (zigzag) */
+  USP_ERR_DEGREE = 3,      /* U<1, R<1, hc%U, hk%U (Ulysses degree cannot exceed/divide the KV heads, Sec. 3), hc%hk */
+  USP_ERR_DTYPE = 4,       /* unknown or unsupported dtype combination */
+  USP_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than the query says */
+  USP_ERR_UNSUPPORTED = 6, /* e.g. hs not in {64,128}, too many merge parts, rank range out of bounds */
+  USP_ERR_LAUNCH = 7       /* the HIP runtime reported an error when enqueuing */
+} usp_status;
+
+typedef enum { USP_BF16 = 0, USP_FP32 = 1 } usp_dtype;
+typedef enum { USP_SPLIT_CONTIG = 0, USP_SPLIT_ZIGZAG = 1 } usp_split; /* basic ring vs load-balanced ring (Sec. 3) */
+typedef enum { USP_SEQ_TO_HEAD = 0, USP_HEAD_TO_SEQ = 1 } usp_a2a_dir; /* forward / reverse AllToAll4D (Algorithm 1) */
+
+/* The problem of Algorithm 1.  scale = 0 means 1/sqrt(hs) (Eq. 1 read per head). */
+typedef struct {
+  int32_t bs;
+  int64_t L;
+  int32_t hc, hk, hs;
+  int32_t ulysses, ring;
+  int32_t causal;   /* 0 / 1 */
+  int32_t split;    /* usp_split: how ring blocks are cut from the sequence */
+  int32_t dtype;    /* usp_dtype of Q, K, V, O (and dO, dQ, dK, dV) */
+  float scale;
+} usp_problem;
+
+/* Global positions of a local index range in at most two ascending runs (Algorithm 2 gives
+ * two chunks per ring rank): local i < len0 -> start0 + i, otherwise start1 + (i - len0). */
+typedef struct {
+  int64_t start0, len0, start1, len1;
+} usp_posdesc;
+
+#define USP_MAX_MERGE_PARTS 64
+
+/* Text for a status code (static storage). */
+const char* usp_status_str(int status);
+
+/* Host only.  Checks a problem against the constraints of Sec. 3 (degrees vs head counts,
+ * divisibility of L).  Returns USP_OK or the first violated class. */
+int usp_validate(const usp_problem* p);
+
+/* Host only.  Algorithm 2 as index arithmetic for virtual rank (ring_rank, ulysses_rank):
+ *   *shard      <- positions of its [L/N] input shard (the u-th of U pieces of the ring block);
+ *   *ring_block <- positions of ring rank r's [L/R] block (zigzag: chunks r and 2R-1-r of 2R;
+ *                  contiguous: block r of R).
+ * Either output pointer may be NULL. */
+int usp_local_positions(const usp_problem* p, int ring_rank, int ulysses_rank, usp_posdesc* shard,
+                        usp_posdesc* ring_block);
+
+/* Algorithm 1 steps 2-4 (dir = USP_SEQ_TO_HEAD) and 6 (USP_HEAD_TO_SEQ): the AllToAll4D of one
+ * Ulysses group as a permutation.  `heads` is hc (Q, O) or hk (K, V); element size from p->dtype.
+ * Ranks [rank_begin, rank_end) index the HEAD-layout side:
+ *   SEQ_TO_HEAD: for each such rank (r,u) gather   dst_head[rank][b][u'*(L/N)+s][h'][e] =
+ *                src_seq[r*U+u'][b][s][u*(heads/U)+h'][e]   for all u' in [0,U);
+ *   HEAD_TO_SEQ: for each such rank scatter the inverse (it fills its head slice of the U
+ *                seq-layout shards of its Ulysses group).
+ * src and dst are whole-buffer base pointers (seq or head layout as the direction implies)
+ * and must not overlap.  Bit-exact copy; no arithmetic. */
+int usp_layout_a2a(const usp_problem* p, int heads, int dir, const void* src, void* dst, int rank_begin,
+                   int rank_end, void* stream);
+
+/* One ring step (Sec. 2, the blockwise loop of SP-Ring; Eq. 1 restricted to one K/V block).
+ *   q [bs,Lq,hq,hs]; k, v [bs,Lk,hkv,hs]  (in_dtype);  query head h reads KV head h / (hq/hkv);
+ *   o_part [bs,Lq,hq,hs] (o_dtype): softmax(scale*q k^T) v over the VISIBLE keys of this block;
+ *   lse_part [bs,hq,Lq] float: natural-log sum of exp(scale*q.k) over the visible keys.
+ * causal != 0: key j is visible to query i iff kpos(j) <= qpos(i) (global positions from the
+ * descriptors); causal == 0: every key is visible and qpos/kpos may be NULL.
+ * A row with no visible key gets o = 0 and lse = -inf.  scale = 0 means 1/sqrt(hs).
+ * bf16 inputs run on MFMA with fp32 accumulation; fp32 inputs run a plain-ALU instance. */
+int usp_block_attn_fwd(const void* q, const void* k, const void* v, void* o_part, float* lse_part, int bs,
+                       int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                       const usp_posdesc* qpos, const usp_posdesc* kpos, int in_dtype, int o_dtype,
+                       void* stream);
+
+/* Merge of the ring steps' partial results (implied by the blockwise formulation of Sec. 2):
+ *   lse_out = ln sum_i exp(lse_i);  o_out = sum_i exp(lse_i - lse_out) * o_i;
+ * parts with lse_i = -inf contribute nothing; all -inf gives (0, -inf).
+ * o_parts / lse_parts: HOST arrays of n_parts DEVICE pointers, each [bs,Lq,hq,hs] (part_dtype)
+ * and [bs,hq,Lq] float; 1 <= n_parts <= USP_MAX_MERGE_PARTS.  Outputs may alias part 0. */
+int usp_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
+                  float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
+                  void* stream);
+
+/* Algorithm 1 forward for virtual ranks [rank_begin, rank_end):
+ * all-to-all of Q,K,V -> ring loop of block attention -> LSE merge -> all-to-all of O.
+ *   q, o: seq layout with hc heads; k, v: seq layout with hk heads (ALL N shards must be
+ *   present: the ring reads the other ring ranks' K/V where hardware would receive them);
+ *   lse: [N][bs][hc/U][L/R] float, written for the ranks in range. */
+size_t usp_attn_fwd_workspace_bytes(const usp_problem* p, int n_ranks);
+int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
+                 int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Algorithm 1 backward (Sec. 3: the all-to-alls swap their scatter/gather roles).
+ *   d_o: seq layout; o, lse: as produced by usp_attn_fwd; dq, dk, dv: seq layout outputs.
+ * dq is complete for the ranks in range; dk/dv receive only those ranks' contributions, so
+ * complete dk/dv needs rank_begin = 0, rank_end = N.  dk and dv are overwritten. */
+size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks);
+int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,
+                 const float* lse, const void* d_o, void* dq, void* dk, void* dv, int rank_begin,
+                 int rank_end, void* workspace, size_t workspace_bytes, void* stream);
+
+#if defined(USP_BUILDING)
+#pragma GCC visibility pop
+#endif
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* USP_H_ */

@@ -1,0 +1,497 @@
+// One ring step of blockwise attention (Sec. 2: SP-Ring's blockwise loop; Eq. 1 restricted to
+// one K/V block): S = scale * Q K^T -> position mask -> online softmax over key tiles -> P V,
+// returning the partial O and the per-row log-sum-exp.
+//
+// gfx950 design (bf16 instance)
+//   * MFMA v_mfma_f32_32x32x16_bf16, fp32 accumulation.  The score tile is computed TRANSPOSED,
+//     S^T = K Q^T: a lane then owns one query column (lane % 32) and 16 keys per 32-key block in
+//     its accumulator registers, so the softmax row max / row sum are in-register reductions plus
+//     one exchange between lanes l and l^32.  The accumulator layout of S^T is also the B-operand
+//     layout of the second product O^T = V^T P^T (same lane <-> query, 8 keys per 16-key step), so
+//     P never leaves registers.
+//   * A workgroup owns BM = NWAVES * NQB * 32 query rows of one (batch, head); Q fragments stay in
+//     registers for the whole kernel.  K and V tiles of KT keys are staged in LDS, double
+//     buffered, fetched to registers one tile ahead while the current tile is being multiplied.
+//   * K is read from LDS as row-major 16 B fragments (A operand, rows = keys).  V stays row-major
+//     in LDS too; the V^T A-operand (rows = head dims, k = keys) is produced by the LDS transpose
+//     read ds_read_b64_tr_b16, which hands each lane 4 consecutive keys of its head dim.
+//   * exp2 with log2(e) folded into the scale; masks only on tiles that straddle the causal
+//     boundary or the ragged tail; key tiles that are invisible to the whole query tile are
+//     never loaded; the O accumulator is rescaled only when some row maximum moved.
+//   * Work order: heaviest query tiles first (descending local index under a causal mask), KV
+//     group fastest so that workgroups sharing K/V land on the same XCD's L2 when the number of
+//     groups is a multiple of the 8 XCDs.
+#include "usp_internal.h"
+
+namespace usp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Position descriptor narrowed to 32 bits (the host checks L < 2^31): fewer registers in the mask path.
+struct PosDesc32 { int start0, len0, start1, len1; };
+__device__ inline int pos_of(const PosDesc32& d, int i) { return i < d.len0 ? d.start0 + i : d.start1 + (i - d.len0); }
+__device__ inline int pos_min(const PosDesc32& d, int a, int b) {
+  int m = INT32_MAX;
+  if (a < d.len0) m = d.start0 + a;
+  if (b > d.len0) m = min(m, d.start1 + (max(a, d.len0) - d.len0));
+  return m;
+}
+__device__ inline int pos_max(const PosDesc32& d, int a, int b) {
+  int m = INT32_MIN;
+  if (a < d.len0) m = d.start0 + min(b, d.len0) - 1;
+  if (b > d.len0) m = max(m, d.start1 + (b - 1 - d.len0));
+  return m;
+}
+
+struct AttnArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* o;
+  float* lse;
+  int bs, hq, hkv, g;
+  int Lq, Lk;
+  int n_qtiles;
+  int causal;
+  float scale;        // natural-units scale (for the LSE)
+  float scale_log2;   // scale * log2(e)
+  PosDesc32 qpos, kpos;
+};
+
+// Visible key-tile ranges of a query tile: tiles [a0,a1) then [b0,b1) (b may be empty).
+struct TileRanges { int a0, a1, b0, b1; };
+
+template <int KT>
+__device__ inline TileRanges visible_tiles(const AttnArgs& a, int row_lo, int row_hi) {
+  TileRanges t;
+  if (!a.causal) {
+    t.a0 = 0; t.a1 = (a.Lk + KT - 1) / KT; t.b0 = t.b1 = t.a1;
+    return t;
+  }
+  const int64_t qmax = pos_max(a.qpos, row_lo, row_hi);
+  // keys of run 0 / run 1 with position <= qmax form a prefix of each run
+  int64_t c0 = qmax - a.kpos.start0 + 1; c0 = c0 < 0 ? 0 : (c0 > a.kpos.len0 ? a.kpos.len0 : c0);
+  int64_t c1 = qmax - a.kpos.start1 + 1; c1 = c1 < 0 ? 0 : (c1 > a.kpos.len1 ? a.kpos.len1 : c1);
+  t.a0 = 0;
+  t.a1 = (int)((c0 + KT - 1) / KT);
+  if (c1 > 0) {
+    t.b0 = (int)(a.kpos.len0 / KT);
+    t.b1 = (int)(((int64_t)a.kpos.len0 + c1 + KT - 1) / KT);
+    if (t.b0 < t.a1) t.b0 = t.a1;
+    if (t.b1 < t.b0) t.b1 = t.b0;
+  } else {
+    t.b0 = t.b1 = t.a1;
+  }
+  return t;
+}
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+  f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+// -------------------------------------------------------------------------------------------
+// bf16 MFMA kernel
+// -------------------------------------------------------------------------------------------
+template <int HS, int NQB, int NWAVES, int KT, typename OutT>
+__global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64),
+                          amdgpu_waves_per_eu((NWAVES + 3) / 4, (NWAVES + 3) / 4)))
+void block_attn_fwd_mfma(const AttnArgs a) {
+  constexpr int NT = NWAVES * 64;
+  constexpr int BM = NWAVES * NQB * 32;
+  constexpr int KSTEPS = HS / 16;          // MFMA k-steps of Q K^T
+  constexpr int DB = HS / 32;              // 32-wide head-dim blocks of O^T
+  constexpr int KB = KT / 32;              // 32-key blocks of S^T
+  constexpr int PS = KT / 16;              // MFMA k-steps of P V
+  constexpr int KSTR = HS * 2 + 16;        // LDS row stride of K in bytes (16 B pad: conflict-free b128 rows)
+  constexpr int VSTR = (HS == 128) ? 320 : 192;   // V rows: stride = odd multiple of 64 B for the transpose read
+  constexpr int KBYTES = KT * KSTR, VBYTES = KT * VSTR;
+  constexpr int CHUNKS = KT * HS / 8;      // 16 B chunks per tile (K and V alike)
+  constexpr int CPT = CHUNKS / NT;         // chunks per thread
+  static_assert(CHUNKS % NT == 0, "tile must split evenly over the workgroup");
+
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  // [buf][K | V]
+  char* const lds = smem;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hl = lane >> 5;
+
+  // ---- work item decode: KV group fastest, then head within group, then query tile (heavy first)
+  const int n_groups = a.bs * a.hkv;
+  int w = blockIdx.x;
+  const int group = w % n_groups; w /= n_groups;
+  const int hg = w % a.g;
+  const int t = w / a.g;
+  const int qtile = a.causal ? a.n_qtiles - 1 - t : t;
+  const int b = group / a.hkv, kvh = group % a.hkv;
+  const int h = kvh * a.g + hg;
+
+  const int tile_row0 = qtile * BM;
+  const int tile_row1 = min(a.Lq, tile_row0 + BM);
+  const int wave_row0 = tile_row0 + wave * (NQB * 32);
+
+  const __bf16* qg = (const __bf16*)a.q;
+  const __bf16* kg = (const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS;   // + key * hkv * HS
+  const __bf16* vg = (const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
+  const size_t kv_row_stride = (size_t)a.hkv * HS;
+
+  // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
+  bf16x8 qf[NQB][KSTEPS];
+  int qrow[NQB];
+  int qp[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    qrow[qb] = wave_row0 + qb * 32 + l32;
+    const int rr = min(qrow[qb], a.Lq - 1);
+    qp[qb] = a.causal ? pos_of(a.qpos, rr) : 0;
+    const __bf16* src = qg + (((size_t)b * a.Lq + rr) * a.hq + h) * HS + 8 * hl;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
+  }
+
+  f32x16 oacc[NQB][DB];
+  float m_run[NQB], l_run[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[qb][db][i] = 0.f;
+  }
+
+  const TileRanges tr = visible_tiles<KT>(a, tile_row0, tile_row1);
+  const int na = tr.a1 - tr.a0;
+  const int nt = na + (tr.b1 - tr.b0);
+
+  // wave-level bounds for the mask decision
+  const int wave_row1 = min(a.Lq, wave_row0 + NQB * 32);
+  const bool wave_live = wave_row0 < a.Lq;
+  const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, wave_row1) : 0;
+
+  // ---- staging: thread copies CPT 16 B chunks of K and of V per tile
+  u32x4 kreg[CPT], vreg[CPT];
+  auto fetch = [&](int it) {
+    const int jt = it < na ? tr.a0 + it : tr.b0 + (it - na);
+    const int key0 = jt * KT;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int ch = tid + c * NT;
+      const int row = ch / (HS / 8), col = ch % (HS / 8);
+      const int key = min(key0 + row, a.Lk - 1);
+      kreg[c] = *(const u32x4*)(kg + (size_t)key * kv_row_stride + col * 8);
+      vreg[c] = *(const u32x4*)(vg + (size_t)key * kv_row_stride + col * 8);
+    }
+  };
+  auto stash = [&](int buf) {
+    char* kb = lds + buf * (KBYTES + VBYTES);
+    char* vb = kb + KBYTES;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int ch = tid + c * NT;
+      const int row = ch / (HS / 8), col = ch % (HS / 8);
+      *(u32x4*)(kb + row * KSTR + col * 16) = kreg[c];
+      *(u32x4*)(vb + row * VSTR + col * 16) = vreg[c];
+    }
+  };
+
+  if (nt > 0) {
+    fetch(0);
+    stash(0);
+  }
+  __syncthreads();
+
+  for (int it = 0; it < nt; ++it) {
+    const int cur = it & 1;
+    const bool more = it + 1 < nt;
+    if (more) fetch(it + 1);
+
+    const int jt = it < na ? tr.a0 + it : tr.b0 + (it - na);
+    const int key0 = jt * KT;
+    const char* kb = lds + cur * (KBYTES + VBYTES);
+    const char* vb = kb + KBYTES;
+
+    // ---- S^T = K Q^T   (rows = keys, cols = queries)
+    f32x16 sacc[NQB][KB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int kbk = 0; kbk < KB; ++kbk)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[qb][kbk][i] = 0.f;
+#pragma unroll
+    for (int kbk = 0; kbk < KB; ++kbk) {
+      const char* krow = kb + (kbk * 32 + l32) * KSTR + hl * 16;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const bf16x8 kf = *(const bf16x8*)(krow + ks * 32);
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+          sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][kbk], 0, 0, 0);
+      }
+    }
+
+    // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave
+    const int key1 = min(a.Lk, key0 + KT);
+    bool need_mask = key0 + KT > a.Lk;
+    if (a.causal && wave_live) need_mask = need_mask || (pos_max(a.kpos, key0, key1) > wave_qmin);
+    if (need_mask) {
+#pragma unroll
+      for (int kbk = 0; kbk < KB; ++kbk)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = key0 + kbk * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
+          const bool inb = key < a.Lk;
+          const int kp = a.causal ? pos_of(a.kpos, key) : 0;
+#pragma unroll
+          for (int qb = 0; qb < NQB; ++qb) {
+            const bool vis = inb && (!a.causal || kp <= qp[qb]);
+            sacc[qb][kbk][i] = vis ? sacc[qb][kbk][i] : -INFINITY;
+          }
+        }
+    }
+
+    // ---- online softmax per query block; P^T packed to bf16 in the B-operand layout
+    bf16x8 pf[NQB][PS];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kbk = 0; kbk < KB; ++kbk)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[qb][kbk][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[qb], mx);
+      const float mc = (m_new == -INFINITY) ? 0.f : m_new * a.scale_log2;
+      const float alpha = __builtin_amdgcn_exp2f(m_run[qb] * a.scale_log2 - mc);   // m_run = -inf -> 0
+      m_run[qb] = m_new;
+      float rs = 0.f;
+#pragma unroll
+      for (int kbk = 0; kbk < KB; ++kbk) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          u32x4 pk;
+#pragma unroll
+          for (int pr = 0; pr < 4; ++pr) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][kbk][half * 8 + 2 * pr], a.scale_log2, -mc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][kbk][half * 8 + 2 * pr + 1], a.scale_log2, -mc));
+            rs += p0 + p1;
+            pk[pr] = pack_bf16(p0, p1);
+          }
+          pf[qb][kbk * 2 + half] = __builtin_bit_cast(bf16x8, pk);
+        }
+      }
+      l_run[qb] = l_run[qb] * alpha + rs;
+      if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
+      }
+    }
+
+    // ---- O^T += V^T P^T   (rows = head dims, cols = queries, k = keys)
+    // MFMA k index e of lane half hl in step s is key 16 s + 8 (e / 4) + 4 hl + (e % 4): the
+    // accumulator layout of S^T.  The transpose read returns, for a 16-lane group whose lane j
+    // points at (key base + j / 4, dim base + 4 (j % 4)), the 4 keys of dim base + j to lane j.
+    const int grp = lane >> 4, j16 = lane & 15;
+    const char* vlane = vb + (4 * hl + (j16 >> 2)) * VSTR + (16 * (grp & 1) + 4 * (j16 & 3)) * 2;
+#pragma unroll
+    for (int s = 0; s < PS; ++s) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const char* p0 = vlane + (16 * s) * VSTR + db * 64;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+          oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][s], oacc[qb][db], 0, 0, 0);
+      }
+    }
+
+    if (more) stash(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: normalise, write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    if (qrow[qb] < a.Lq) {
+      OutT* dst = (OutT*)a.o + (((size_t)b * a.Lq + qrow[qb]) * a.hq + h) * HS + 4 * hl;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          f32x4 v4 = {oacc[qb][db][4 * j] * inv, oacc[qb][db][4 * j + 1] * inv, oacc[qb][db][4 * j + 2] * inv,
+                      oacc[qb][db][4 * j + 3] * inv};
+          OutT* d = dst + db * 32 + j * 8;
+          if constexpr (sizeof(OutT) == 4) {
+            *(f32x4*)d = v4;
+          } else {
+            u32x2 pk = {pack_bf16(v4[0], v4[1]), pack_bf16(v4[2], v4[3])};
+            *(u32x2*)d = pk;
+          }
+        }
+      if (hl == 0) {
+        const float lse = l_tot > 0.f ? m_run[qb] * a.scale + __logf(l_tot) : -INFINITY;
+        a.lse[((size_t)b * a.hq + h) * a.Lq + qrow[qb]] = lse;
+      }
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// fp32 instance: plain ALU, one thread per query row, key tiles staged in LDS.  Exists so that the
+// ring / merge / layout logic can be checked at fp32 accuracy on fp32 inputs; not tuned.
+// -------------------------------------------------------------------------------------------
+template <int HS, typename OutT>
+__global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
+  constexpr int KT = 32;
+  __shared__ float ks[KT][HS], vs[KT][HS];
+  const int n_groups = a.bs * a.hkv;
+  int w = blockIdx.x;
+  const int group = w % n_groups; w /= n_groups;
+  const int hg = w % a.g;
+  const int t = w / a.g;
+  const int qtile = a.causal ? a.n_qtiles - 1 - t : t;
+  const int b = group / a.hkv, kvh = group % a.hkv;
+  const int h = kvh * a.g + hg;
+  const int row0 = qtile * 64, row1 = min(a.Lq, row0 + 64);
+  const int row = row0 + threadIdx.x;
+  const bool live = row < a.Lq;
+  const int rr = min(row, a.Lq - 1);
+  const int qp = a.causal ? pos_of(a.qpos, rr) : 0;
+  const float* qsrc = (const float*)a.q + (((size_t)b * a.Lq + rr) * a.hq + h) * HS;
+  float q[HS], o[HS];
+#pragma unroll
+  for (int e = 0; e < HS; ++e) { q[e] = qsrc[e]; o[e] = 0.f; }
+  float m = -INFINITY, l = 0.f;
+  const TileRanges tr = visible_tiles<KT>(a, row0, row1);
+  const float* kg = (const float*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
+  const float* vg = (const float*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
+  const size_t stride = (size_t)a.hkv * HS;
+  for (int pass = 0; pass < 2; ++pass) {
+    const int j0 = pass ? tr.b0 : tr.a0, j1 = pass ? tr.b1 : tr.a1;
+    for (int jt = j0; jt < j1; ++jt) {
+      __syncthreads();
+      for (int c = threadIdx.x; c < KT * HS; c += 64) {
+        const int r = c / HS, e = c % HS;
+        const int key = min(jt * KT + r, a.Lk - 1);
+        ks[r][e] = kg[(size_t)key * stride + e];
+        vs[r][e] = vg[(size_t)key * stride + e];
+      }
+      __syncthreads();
+      for (int r = 0; r < KT; ++r) {
+        const int key = jt * KT + r;
+        if (key >= a.Lk) break;
+        if (a.causal && pos_of(a.kpos, key) > qp) continue;
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < HS; ++e) s = __builtin_fmaf(q[e], ks[r][e], s);
+        s *= a.scale;
+        const float mn = fmaxf(m, s);
+        const float alpha = expf(m - mn);     // m = -inf -> 0
+        const float p = expf(s - mn);
+        l = l * alpha + p;
+#pragma unroll
+        for (int e = 0; e < HS; ++e) o[e] = o[e] * alpha + p * vs[r][e];
+        m = mn;
+      }
+    }
+  }
+  if (live) {
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    OutT* dst = (OutT*)a.o + (((size_t)b * a.Lq + row) * a.hq + h) * HS;
+#pragma unroll
+    for (int e = 0; e < HS; ++e) dst[e] = (OutT)(o[e] * inv);
+    a.lse[((size_t)b * a.hq + h) * a.Lq + row] = l > 0.f ? m + logf(l) : -INFINITY;
+  }
+}
+
+template <int HS, int NQB, int NWAVES, int KT, typename OutT>
+int launch_mfma(AttnArgs a, hipStream_t stream) {
+  constexpr int BM = NWAVES * NQB * 32;
+  constexpr int KSTR = HS * 2 + 16, VSTR = (HS == 128) ? 320 : 192;
+  constexpr size_t lds = 2 * (size_t)KT * (KSTR + VSTR);
+  a.n_qtiles = (a.Lq + BM - 1) / BM;
+  const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs;
+  if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
+  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, OutT>;
+  static bool attr_set = false;   // raise the dynamic LDS limit once per instance
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return USP_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NWAVES * 64), lds, stream, a);
+  return launch_status();
+}
+
+template <int HS, typename OutT>
+int launch_fp32(AttnArgs a, hipStream_t stream) {
+  a.n_qtiles = (a.Lq + 63) / 64;
+  const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs;
+  if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL((block_attn_fwd_fp32<HS, OutT>), dim3((unsigned)grid), dim3(64), 0, stream, a);
+  return launch_status();
+}
+
+}  // namespace
+
+// Tile configuration of the bf16 instance; the environment variable is a tuning aid for sweeps.
+static int mfma_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("USP_ATTN_VARIANT");
+    v = e ? atoi(e) : 0;
+  }
+  return v;
+}
+
+int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int bs, int64_t Lq,
+                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
+                          const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream) {
+  AttnArgs a;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
+  a.Lq = (int)Lq; a.Lk = (int)Lk;
+  a.n_qtiles = 0;
+  a.causal = causal;
+  a.scale = scale;
+  a.scale_log2 = scale * 1.4426950408889634f;
+  a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
+  a.kpos = PosDesc32{(int)kpos.start0, (int)kpos.len0, (int)kpos.start1, (int)kpos.len1};
+  if (in_dtype == USP_FP32) {
+    if (hs == 128) return o_dtype == USP_FP32 ? launch_fp32<128, float>(a, stream) : launch_fp32<128, __bf16>(a, stream);
+    return o_dtype == USP_FP32 ? launch_fp32<64, float>(a, stream) : launch_fp32<64, __bf16>(a, stream);
+  }
+  const int var = mfma_variant();
+  if (hs == 128) {
+    if (o_dtype == USP_FP32) {
+      if (var == 1) return launch_mfma<128, 2, 4, 64, float>(a, stream);
+      if (var == 2) return launch_mfma<128, 1, 4, 64, float>(a, stream);
+      return launch_mfma<128, 1, 8, 64, float>(a, stream);
+    }
+    if (var == 1) return launch_mfma<128, 2, 4, 64, __bf16>(a, stream);
+    if (var == 2) return launch_mfma<128, 1, 4, 64, __bf16>(a, stream);
+    return launch_mfma<128, 1, 8, 64, __bf16>(a, stream);
+  }
+  if (o_dtype == USP_FP32) return launch_mfma<64, 1, 8, 64, float>(a, stream);
+  return launch_mfma<64, 1, 8, 64, __bf16>(a, stream);
+}
+
+}  // namespace usp

@@ -1,0 +1,107 @@
+// Ulysses all-to-all (Algorithm 1 steps 2-4 and 6) as a local permutation between the
+// sequence layout [N][bs][L/N][heads][hs] and the head layout [N][bs][L/R][heads/U][hs].
+//
+// HBM-bound bit copy.  One (head-layout rank, batch, source shard u') slab is a set of L/N rows;
+// on the head-layout side those rows are one contiguous range, on the sequence-layout side each
+// row is a run of (heads/U)*hs elements at a stride of heads*hs.  Threads walk the slab in the
+// head-layout (fully contiguous) order with the widest vector the run length allows, so both
+// sides are accessed in whole runs: 1 KiB runs for 4 Q heads of size 128, 256 B for one KV head.
+#include "usp_internal.h"
+
+namespace usp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 8;   // vectors per thread: 8 x 16 B in flight per lane
+
+struct LayoutArgs {
+  const char* seq;     // sequence-layout buffer base
+  const char* head;    // head-layout buffer base (slot of rank head_rank_base)
+  int64_t n;           // rows per slab = L/N
+  int64_t Lq;          // L/R
+  int bs, U, rank_begin, head_rank_base;
+  uint32_t run_vecs;   // vectors per run = (heads/U)*hs*esize / sizeof(Vec)
+  uint32_t row_vecs;   // vectors per sequence-layout row = heads*hs*esize / sizeof(Vec)
+};
+
+template <typename Vec, bool kToHead>
+__global__ __launch_bounds__(kThreads) void layout_a2a_kernel(LayoutArgs a) {
+  // blockIdx.z -> (rank, batch), blockIdx.y -> source shard u', blockIdx.x -> position in the slab
+  const int rank = a.rank_begin + (int)(blockIdx.z / a.bs);
+  const int b = (int)(blockIdx.z % a.bs);
+  const int up = (int)blockIdx.y;
+  const int r = rank / a.U, u = rank % a.U;
+  const uint64_t slab_vecs = (uint64_t)a.n * a.run_vecs;
+  const uint64_t head_row0 = (uint64_t)(rank - a.head_rank_base) * a.bs * a.Lq + (uint64_t)b * a.Lq + (uint64_t)up * a.n;
+  Vec* head = (Vec*)a.head + head_row0 * a.run_vecs;
+  const uint64_t seq_row0 = ((uint64_t)(r * a.U + up) * a.bs + b) * a.n;
+  Vec* seq = (Vec*)a.seq + seq_row0 * a.row_vecs + (uint64_t)u * a.run_vecs;
+
+  const uint64_t base = (uint64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+  Vec val[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const uint64_t idx = base + (uint64_t)i * kThreads;
+    if (idx < slab_vecs) {
+      const uint64_t row = idx / a.run_vecs;
+      const uint32_t c = (uint32_t)(idx - row * a.run_vecs);
+      const Vec* s = kToHead ? seq + row * a.row_vecs + c : head + idx;
+      val[i] = __builtin_nontemporal_load(s);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const uint64_t idx = base + (uint64_t)i * kThreads;
+    if (idx < slab_vecs) {
+      const uint64_t row = idx / a.run_vecs;
+      const uint32_t c = (uint32_t)(idx - row * a.run_vecs);
+      Vec* d = kToHead ? head + idx : seq + row * a.row_vecs + c;
+      __builtin_nontemporal_store(val[i], d);
+    }
+  }
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename Vec>
+int launch_vec(LayoutArgs a, int dir, size_t run_bytes, size_t row_bytes, int n_ranks, hipStream_t stream) {
+  a.run_vecs = (uint32_t)(run_bytes / sizeof(Vec));
+  a.row_vecs = (uint32_t)(row_bytes / sizeof(Vec));
+  const uint64_t slab_vecs = (uint64_t)a.n * a.run_vecs;
+  const uint64_t gx = (slab_vecs + (uint64_t)kThreads * kUnroll - 1) / ((uint64_t)kThreads * kUnroll);
+  if (gx > 0x7fffffffull || (uint64_t)n_ranks * a.bs > 65535ull || a.U > 65535) return USP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)gx, (unsigned)a.U, (unsigned)(n_ranks * a.bs));
+  if (dir == USP_SEQ_TO_HEAD)
+    hipLaunchKernelGGL((layout_a2a_kernel<Vec, true>), grid, dim3(kThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL((layout_a2a_kernel<Vec, false>), grid, dim3(kThreads), 0, stream, a);
+  return launch_status();
+}
+
+}  // namespace
+
+int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src, void* dst, int rank_begin,
+                      int rank_end, int head_rank_base, hipStream_t stream) {
+  const size_t es = dtype_size(p.dtype);
+  const int N = p.ulysses * p.ring;
+  LayoutArgs a;
+  a.seq = (const char*)(dir == USP_SEQ_TO_HEAD ? src : dst);
+  a.head = (const char*)(dir == USP_SEQ_TO_HEAD ? dst : src);
+  a.n = p.L / N;
+  a.Lq = p.L / p.ring;
+  a.bs = p.bs;
+  a.U = p.ulysses;
+  a.rank_begin = rank_begin;
+  a.head_rank_base = head_rank_base;
+  const size_t run_bytes = (size_t)(heads / p.ulysses) * p.hs * es;
+  const size_t row_bytes = (size_t)heads * p.hs * es;
+  const uintptr_t align = (uintptr_t)src | (uintptr_t)dst | run_bytes;
+  const int n_ranks = rank_end - rank_begin;
+  if (align % 16 == 0) return launch_vec<u32x4>(a, dir, run_bytes, row_bytes, n_ranks, stream);
+  if (align % 8 == 0) return launch_vec<u32x2>(a, dir, run_bytes, row_bytes, n_ranks, stream);
+  if (align % 4 == 0) return launch_vec<uint32_t>(a, dir, run_bytes, row_bytes, n_ranks, stream);
+  return launch_vec<uint16_t>(a, dir, run_bytes, row_bytes, n_ranks, stream);
+}
+
+}  // namespace usp

@@ -1,0 +1,286 @@
+// C-ABI entry points: host-side validation, Algorithm 2 index arithmetic, and the
+// orchestration of Algorithm 1 (all-to-all -> ring loop -> merge -> all-to-all) over kernels.
+// No arithmetic of the method runs on the host; every step is a kernel launch.
+#include <math.h>
+#include <string.h>
+
+#include "usp_internal.h"
+
+using namespace usp;
+
+extern "C" const char* usp_status_str(int s) {
+  switch (s) {
+    case USP_OK: return "ok";
+    case USP_ERR_NULL: return "null pointer";
+    case USP_ERR_SHAPE: return "bad shape (sizes must be positive; L must divide by N, or by 2*R*U for the zigzag split)";
+    case USP_ERR_DEGREE: return "bad degree (need U,R >= 1, hc % U == 0, hk % U == 0, hc % hk == 0)";
+    case USP_ERR_DTYPE: return "bad dtype";
+    case USP_ERR_WORKSPACE: return "workspace missing or too small";
+    case USP_ERR_UNSUPPORTED: return "unsupported configuration";
+    case USP_ERR_LAUNCH: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int usp_validate(const usp_problem* p) {
+  if (!p) return USP_ERR_NULL;
+  if (p->bs < 1 || p->L < 1 || p->hc < 1 || p->hk < 1 || p->hs < 1) return USP_ERR_SHAPE;
+  if (p->ulysses < 1 || p->ring < 1) return USP_ERR_DEGREE;
+  if (p->hc % p->hk) return USP_ERR_DEGREE;
+  // Sec. 3: the Ulysses degree is limited by the (KV) head count.
+  if (p->hc % p->ulysses || p->hk % p->ulysses) return USP_ERR_DEGREE;
+  if (p->dtype != USP_BF16 && p->dtype != USP_FP32) return USP_ERR_DTYPE;
+  if (p->split != USP_SPLIT_CONTIG && p->split != USP_SPLIT_ZIGZAG) return USP_ERR_UNSUPPORTED;
+  const int64_t n = (int64_t)p->ulysses * p->ring;
+  if (p->split == USP_SPLIT_ZIGZAG) {
+    if (p->L % (2 * n)) return USP_ERR_SHAPE;
+  } else if (p->L % n) {
+    return USP_ERR_SHAPE;
+  }
+  if (p->hs != 64 && p->hs != 128) return USP_ERR_UNSUPPORTED;
+  if (p->L >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  if (!(p->scale >= 0.0f) || isinf(p->scale)) return USP_ERR_UNSUPPORTED;
+  return USP_OK;
+}
+
+// Algorithm 2: ring rank r owns chunks r and 2R-1-r (of 2R); Ulysses rank u the u-th of U pieces.
+static void ring_block_desc(const usp_problem& p, int r, usp_posdesc* d) {
+  if (p.split == USP_SPLIT_ZIGZAG) {
+    const int64_t c = p.L / (2 * (int64_t)p.ring);
+    d->start0 = (int64_t)r * c;
+    d->len0 = c;
+    d->start1 = (2 * (int64_t)p.ring - 1 - r) * c;
+    d->len1 = c;
+  } else {
+    const int64_t n = p.L / p.ring;
+    d->start0 = (int64_t)r * n;
+    d->len0 = n;
+    d->start1 = d->start0 + n;
+    d->len1 = 0;
+  }
+}
+
+extern "C" int usp_local_positions(const usp_problem* p, int ring_rank, int ulysses_rank, usp_posdesc* shard,
+                                   usp_posdesc* ring_block) {
+  int st = usp_validate(p);
+  if (st != USP_OK) return st;
+  if (ring_rank < 0 || ring_rank >= p->ring || ulysses_rank < 0 || ulysses_rank >= p->ulysses)
+    return USP_ERR_UNSUPPORTED;
+  usp_posdesc blk;
+  ring_block_desc(*p, ring_rank, &blk);
+  if (ring_block) *ring_block = blk;
+  if (shard) {
+    // local indices [a, b) of the ring block, cut against the block's two runs
+    const int64_t n = (blk.len0 + blk.len1) / p->ulysses;
+    const int64_t a = (int64_t)ulysses_rank * n, b = a + n;
+    const int64_t a0 = a < blk.len0 ? a : blk.len0, b0 = b < blk.len0 ? b : blk.len0;   // part in run 0
+    const int64_t a1 = (a > blk.len0 ? a : blk.len0) - blk.len0, b1 = (b > blk.len0 ? b : blk.len0) - blk.len0;
+    shard->start0 = blk.start0 + a0;
+    shard->len0 = b0 - a0;
+    shard->start1 = blk.start1 + a1;
+    shard->len1 = b1 - a1;
+  }
+  return USP_OK;
+}
+
+extern "C" int usp_layout_a2a(const usp_problem* p, int heads, int dir, const void* src, void* dst, int rank_begin,
+                              int rank_end, void* stream) {
+  int st = usp_validate(p);
+  if (st != USP_OK) return st;
+  if (!src || !dst) return USP_ERR_NULL;
+  if (heads < 1 || heads % p->ulysses) return USP_ERR_DEGREE;
+  if (dir != USP_SEQ_TO_HEAD && dir != USP_HEAD_TO_SEQ) return USP_ERR_UNSUPPORTED;
+  const int n = p->ulysses * p->ring;
+  if (rank_begin < 0 || rank_end > n || rank_begin > rank_end) return USP_ERR_UNSUPPORTED;
+  if (rank_begin == rank_end) return USP_OK;
+  return launch_layout_a2a(*p, heads, dir, src, dst, rank_begin, rank_end, 0, (hipStream_t)stream);
+}
+
+static bool desc_ok(const usp_posdesc* d, int64_t len) {
+  // positions must fit 32 bits: the kernels narrow them
+  const int64_t lim = (int64_t)1 << 31;
+  return d && d->len0 >= 0 && d->len1 >= 0 && d->len0 + d->len1 == len && d->start0 >= 0 && d->start1 >= 0 &&
+         d->start0 + d->len0 < lim && d->start1 + d->len1 < lim;
+}
+
+extern "C" int usp_block_attn_fwd(const void* q, const void* k, const void* v, void* o_part, float* lse_part, int bs,
+                                  int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                                  const usp_posdesc* qpos, const usp_posdesc* kpos, int in_dtype, int o_dtype,
+                                  void* stream) {
+  if (!q || !k || !v || !o_part || !lse_part) return USP_ERR_NULL;
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
+  if (hq % hkv) return USP_ERR_DEGREE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if ((in_dtype != USP_BF16 && in_dtype != USP_FP32) || (o_dtype != USP_BF16 && o_dtype != USP_FP32))
+    return USP_ERR_DTYPE;
+  if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
+  if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  usp_posdesc qd = {0, Lq, 0, 0}, kd = {0, Lk, 0, 0};
+  if (causal) {
+    if (!qpos || !kpos) return USP_ERR_NULL;
+    if (!desc_ok(qpos, Lq) || !desc_ok(kpos, Lk)) return USP_ERR_SHAPE;
+    qd = *qpos;
+    kd = *kpos;
+  }
+  if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  return launch_block_attn_fwd(q, k, v, o_part, lse_part, bs, Lq, Lk, hq, hkv, hs, scale, causal ? 1 : 0, qd, kd,
+                               in_dtype, o_dtype, (hipStream_t)stream);
+}
+
+extern "C" int usp_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
+                             float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
+                             void* stream) {
+  if (!o_parts || !lse_parts || !o_out || !lse_out) return USP_ERR_NULL;
+  if (n_parts < 1 || n_parts > USP_MAX_MERGE_PARTS) return USP_ERR_UNSUPPORTED;
+  for (int i = 0; i < n_parts; ++i)
+    if (!o_parts[i] || !lse_parts[i]) return USP_ERR_NULL;
+  if (bs < 1 || Lq < 1 || hq < 1 || hs < 1) return USP_ERR_SHAPE;
+  if (hs % 8) return USP_ERR_UNSUPPORTED;
+  if ((part_dtype != USP_BF16 && part_dtype != USP_FP32) || (out_dtype != USP_BF16 && out_dtype != USP_FP32))
+    return USP_ERR_DTYPE;
+  return launch_lse_merge(o_parts, lse_parts, n_parts, o_out, lse_out, bs, Lq, hq, hs, part_dtype, out_dtype,
+                          (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Algorithm 1 forward.  Workspace plan (all sizes rounded up to 256 B):
+//   kv_head : K and V in head layout for every (ring row, Ulysses column in range): the ring loop of
+//             a rank reads block s = (r - i) mod R of its own column u;
+//   q_head, o_head : one rank's Q / O in head layout (reused rank after rank, stream-ordered);
+//   parts   : R partial O (fp32) + R partial LSE when R > 1.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct FwdPlan {
+  size_t q_head, o_head, k_head, v_head, o_parts, lse_parts, total;
+  size_t kv_block_bytes, part_o_bytes, part_lse_bytes;
+  int n_cols;
+};
+
+// Ulysses columns touched by ranks [rb, re): all U when the range spans more than one ring row.
+void column_range(const usp_problem& p, int rb, int re, int* c0, int* c1) {
+  const int U = p.ulysses;
+  if (re - rb >= U || (rb / U) != ((re - 1) / U)) {
+    *c0 = 0;
+    *c1 = U;
+  } else {
+    *c0 = rb % U;
+    *c1 = (re - 1) % U + 1;
+  }
+}
+
+FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
+  FwdPlan f;
+  const size_t es = dtype_size(p.dtype);
+  const size_t Lq = p.L / p.ring, hq = p.hc / p.ulysses, hkv = p.hk / p.ulysses;
+  const size_t qb = up256((size_t)p.bs * Lq * hq * p.hs * es);
+  f.kv_block_bytes = up256((size_t)p.bs * Lq * hkv * p.hs * es);
+  f.part_o_bytes = up256((size_t)p.bs * Lq * hq * p.hs * sizeof(float));
+  f.part_lse_bytes = up256((size_t)p.bs * Lq * hq * sizeof(float));
+  f.n_cols = n_cols;
+  size_t off = 0;
+  f.q_head = off; off += qb;
+  f.o_head = off; off += qb;
+  f.k_head = off; off += f.kv_block_bytes * p.ring * n_cols;
+  f.v_head = off; off += f.kv_block_bytes * p.ring * n_cols;
+  f.o_parts = off; off += p.ring > 1 ? f.part_o_bytes * p.ring : 0;
+  f.lse_parts = off; off += p.ring > 1 ? f.part_lse_bytes * p.ring : 0;
+  f.total = off;
+  return f;
+}
+
+}  // namespace
+
+extern "C" size_t usp_attn_fwd_workspace_bytes(const usp_problem* p, int n_ranks) {
+  if (usp_validate(p) != USP_OK || n_ranks < 1) return 0;
+  // one rank touches one Ulysses column; a wider range may straddle ring rows, so size for all U
+  const int cols = n_ranks == 1 ? 1 : p->ulysses;
+  return plan_fwd(*p, cols).total;
+}
+
+extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
+                            int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream_) {
+  int st = usp_validate(p);
+  if (st != USP_OK) return st;
+  if (!q || !k || !v || !o || !lse) return USP_ERR_NULL;
+  const int U = p->ulysses, R = p->ring, N = U * R;
+  if (rank_begin < 0 || rank_end > N || rank_begin >= rank_end) return USP_ERR_UNSUPPORTED;
+  int c0, c1;
+  column_range(*p, rank_begin, rank_end, &c0, &c1);
+  const FwdPlan f = plan_fwd(*p, c1 - c0);
+  if (!workspace || workspace_bytes < f.total) return USP_ERR_WORKSPACE;
+  if ((uintptr_t)workspace & 255) return USP_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+  char* ws = (char*)workspace;
+  const size_t es = dtype_size(p->dtype);
+  const int64_t Lq = p->L / R;
+  const int hq = p->hc / U, hkv = p->hk / U;
+  const float scale = p->scale == 0.0f ? 1.0f / sqrtf((float)p->hs) : p->scale;
+
+  (void)es;
+
+  // Steps 3-4 of Algorithm 1 for every K/V block the ranks in range will visit.
+  for (int r = 0; r < R; ++r)
+    for (int u = c0; u < c1; ++u) {
+      const int rank = r * U + u;
+      const size_t slot = ((size_t)r * (c1 - c0) + (u - c0)) * f.kv_block_bytes;
+      // the workspace slot holds this one rank: head-layout base pointer stands for `rank`
+      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, k, ws + f.k_head + slot, rank, rank + 1, rank, stream);
+      if (st != USP_OK) return st;
+      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, v, ws + f.v_head + slot, rank, rank + 1, rank, stream);
+      if (st != USP_OK) return st;
+    }
+
+  for (int rank = rank_begin; rank < rank_end; ++rank) {
+    const int r = rank / U, u = rank % U;
+    // Step 2: Q of this rank to head layout.
+    st = launch_layout_a2a(*p, p->hc, USP_SEQ_TO_HEAD, q, ws + f.q_head, rank, rank + 1, rank, stream);
+    if (st != USP_OK) return st;
+    usp_posdesc qd;
+    usp_local_positions(p, r, u, nullptr, &qd);
+    float* lse_rank = lse + (size_t)rank * p->bs * hq * Lq;
+    // Step 5: the ring loop.  Step i visits block s = (r - i) mod R.
+    const void* o_ptrs[USP_MAX_MERGE_PARTS];
+    const float* l_ptrs[USP_MAX_MERGE_PARTS];
+    if (R > USP_MAX_MERGE_PARTS) return USP_ERR_UNSUPPORTED;
+    for (int i = 0; i < R; ++i) {
+      const int s = ((r - i) % R + R) % R;
+      usp_posdesc kd;
+      usp_local_positions(p, s, u, nullptr, &kd);
+      const size_t slot = ((size_t)s * (c1 - c0) + (u - c0)) * f.kv_block_bytes;
+      void* o_dst = R > 1 ? (void*)(ws + f.o_parts + (size_t)i * f.part_o_bytes) : (void*)(ws + f.o_head);
+      float* l_dst = R > 1 ? (float*)(ws + f.lse_parts + (size_t)i * f.part_lse_bytes) : lse_rank;
+      st = launch_block_attn_fwd(ws + f.q_head, ws + f.k_head + slot, ws + f.v_head + slot, o_dst, l_dst, p->bs, Lq,
+                                 Lq, hq, hkv, p->hs, scale, p->causal ? 1 : 0, qd, kd, p->dtype,
+                                 R > 1 ? USP_FP32 : p->dtype, stream);
+      if (st != USP_OK) return st;
+      o_ptrs[i] = o_dst;
+      l_ptrs[i] = l_dst;
+    }
+    if (R > 1) {
+      st = launch_lse_merge(o_ptrs, l_ptrs, R, ws + f.o_head, lse_rank, p->bs, Lq, hq, p->hs, USP_FP32, p->dtype,
+                            stream);
+      if (st != USP_OK) return st;
+    }
+    // Step 6: O back to the sequence layout.
+    st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.o_head, o, rank, rank + 1, rank, stream);
+    if (st != USP_OK) return st;
+  }
+  return USP_OK;
+}
+
+extern "C" size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks) {
+  (void)p;
+  (void)n_ranks;
+  return 0;
+}
+
+extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,
+                            const float* lse, const void* d_o, void* dq, void* dk, void* dv, int rank_begin,
+                            int rank_end, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)p; (void)q; (void)k; (void)v; (void)o; (void)lse; (void)d_o; (void)dq; (void)dk; (void)dv;
+  (void)rank_begin; (void)rank_end; (void)workspace; (void)workspace_bytes; (void)stream;
+  return USP_ERR_UNSUPPORTED;
+}

@@ -1,0 +1,54 @@
+// Internal declarations shared by the translation units of libusp.so (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "usp.h"
+
+namespace usp {
+
+inline size_t dtype_size(int dt) { return dt == USP_BF16 ? 2 : (dt == USP_FP32 ? 4 : 0); }
+
+// Global position of local index i under a two-run descriptor.
+__host__ __device__ inline int64_t pos_of(const usp_posdesc& d, int64_t i) {
+  return i < d.len0 ? d.start0 + i : d.start1 + (i - d.len0);
+}
+
+// Smallest / largest global position over local indices [a, b), b > a, within the descriptor.
+__host__ __device__ inline int64_t pos_min(const usp_posdesc& d, int64_t a, int64_t b) {
+  int64_t m = INT64_MAX;
+  if (a < d.len0) m = d.start0 + a;
+  if (b > d.len0) {
+    int64_t a1 = (a > d.len0 ? a : d.len0) - d.len0;
+    int64_t v = d.start1 + a1;
+    m = v < m ? v : m;
+  }
+  return m;
+}
+__host__ __device__ inline int64_t pos_max(const usp_posdesc& d, int64_t a, int64_t b) {
+  int64_t m = INT64_MIN;
+  if (a < d.len0) {
+    int64_t e = b < d.len0 ? b : d.len0;
+    m = d.start0 + e - 1;
+  }
+  if (b > d.len0) {
+    int64_t v = d.start1 + (b - 1 - d.len0);
+    m = v > m ? v : m;
+  }
+  return m;
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? USP_OK : USP_ERR_LAUNCH; }
+
+// Kernel launchers (defined next to their kernels).  All take validated arguments.
+// head_rank_base: the rank whose slot the head-layout base pointer points at (0 for a whole buffer).
+int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src, void* dst, int rank_begin,
+                      int rank_end, int head_rank_base, hipStream_t stream);
+int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
+                     float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
+                     hipStream_t stream);
+int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int bs, int64_t Lq,
+                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
+                          const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream);
+
+}  // namespace usp

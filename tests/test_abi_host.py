@@ -1,0 +1,82 @@
+"""CPU-side checks of the C ABI: the library loads, exports what include/usp.h declares, and its
+host-only entry points (validation, Algorithm 2 positions, workspace sizes) agree with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import usp_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def usp():
+    import paper_2405_07719_amd as pkg
+    if not os.path.exists(pkg.LIB_PATH):
+        from paper_2405_07719_amd import build
+        build.build(verbose=False)
+    pkg.load()
+    return pkg
+
+
+def test_library_exports_every_declared_symbol(usp):
+    header = open(os.path.join(ROOT, "include", "usp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(usp_[a-z0-9_]+)\s*\(", header))
+    assert {"usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge", "usp_attn_fwd", "usp_attn_bwd",
+            "usp_validate", "usp_local_positions", "usp_status_str"} <= names
+    lib = ctypes.CDLL(usp.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} is declared in usp.h but not exported by libusp.so"
+
+
+def test_struct_layouts_match_the_header(usp):
+    # int32, (pad), int64, 8 x int32, float, (pad) -> 56 bytes; four int64 -> 32 bytes
+    assert ctypes.sizeof(usp.usp_problem) == 56
+    assert usp.usp_problem.L.offset == 8 and usp.usp_problem.scale.offset == 48
+    assert ctypes.sizeof(usp.usp_posdesc) == 32
+
+
+def test_validate_follows_the_paper_constraints(usp):
+    ok = usp.problem(1, 32768, 32, 8, 128, 8, 1, True)
+    assert usp.usp_validate(ok) == 0
+    assert usp.usp_validate(usp.problem(1, 212992, 32, 8, 128, 8, 2, True)) == 0      # llama3-8B, SP 16 = 8 x 2
+    assert usp.usp_validate(usp.problem(1, 32768, 32, 8, 128, 16, 1, True)) == 3      # U beyond the KV heads
+    assert usp.usp_validate(usp.problem(1, 32768, 32, 1, 128, 2, 4, True)) == 3       # MQA: Ulysses cannot split
+    assert usp.usp_validate(usp.problem(1, 32768, 32, 1, 128, 1, 8, True)) == 0       # ... but ring-only works
+    assert usp.usp_validate(usp.problem(1, 32768, 32, 5, 128, 1, 1, True)) == 3       # hc % hk
+    assert usp.usp_validate(usp.problem(1, 1004, 4, 4, 64, 2, 2, True)) == 2          # L % 2RU for zigzag
+    assert usp.usp_validate(usp.problem(1, 1004, 4, 4, 64, 2, 2, True, usp.USP_SPLIT_CONTIG)) == 0
+    assert usp.usp_validate(usp.problem(1, 1024, 4, 4, 96, 2, 2, True)) == 6          # head size
+    assert usp.usp_validate(usp.problem(0, 1024, 4, 4, 64, 2, 2, True)) == 2
+    assert usp.usp_validate(usp.problem(1, 1024, 4, 4, 64, 2, 2, True, dtype=7)) == 4
+    assert "degree" in usp.usp_status_str(3)
+
+
+@pytest.mark.parametrize("L,R,U,zz", [(16, 4, 1, True), (64, 2, 4, True), (96, 3, 2, True), (64, 1, 8, True),
+                                      (64, 8, 1, True), (60, 3, 5, False), (64, 4, 2, False)])
+def test_local_positions_match_algorithm2_oracle(usp, L, R, U, zz):
+    p = usp.problem(1, L, 8 * U, 8 * U, 64, U, R, True, usp.USP_SPLIT_ZIGZAG if zz else usp.USP_SPLIT_CONTIG)
+    for r in range(R):
+        for u in range(U):
+            shard, blk = usp.usp_local_positions(p, r, u)
+            assert shard.positions() == orc.zigzag_positions(L, R, U, r, u, zz).tolist()
+            assert blk.positions() == orc.ring_block_positions(L, R, r, zz).tolist()
+    with pytest.raises(usp.UspError):
+        usp.usp_local_positions(p, R, 0)
+
+
+def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
+    p = usp.problem(1, 32768, 32, 8, 128, 8, 1, True)
+    one = usp.usp_attn_fwd_workspace_bytes(p, 1)
+    # Q and O in head layout (32 MiB each) + one K and one V block (8 MiB each)
+    assert one == 2 * 32 * 2**20 + 2 * 8 * 2**20
+    assert usp.usp_attn_fwd_workspace_bytes(p, 8) > one
+    ring = usp.problem(1, 32768, 32, 8, 128, 1, 8, True)
+    w = usp.usp_attn_fwd_workspace_bytes(ring, 1)
+    # + 8 fp32 partial O (64 MiB each) and 8 partial LSE (0.5 MiB each)
+    assert w == 2 * 32 * 2**20 + 2 * 8 * 8 * 2**20 + 8 * 64 * 2**20 + 8 * 2**19
+    assert usp.usp_attn_fwd_workspace_bytes(p, 0) == 0
