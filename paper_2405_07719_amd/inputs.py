@@ -11,6 +11,8 @@ virtual rank's shard can be materialised without building the global tensor.
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_DO = 0, 1, 2, 3
@@ -49,21 +51,32 @@ def normal_at(seed: int, tensor_id: int, b, pos, head, elem) -> np.ndarray:
     return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
 
 
-def tensor_at(seed: int, tensor_id: int, bs: int, positions, heads, hs: int) -> np.ndarray:
-    """float64 array [bs, len(positions), len(heads), hs] of N(0,1) values.
+def tensor_at(seed: int, tensor_id: int, bs: int, positions, heads, hs: int, dtype=np.float64,
+              threads: int = 8) -> np.ndarray:
+    """float64 (or `dtype`) array [bs, len(positions), len(heads), hs] of N(0,1) values.
 
     `positions` are global sequence positions and `heads` global head indices,
     so a shard of any virtual rank is `tensor_at(..., its positions, its heads)`.
     """
     positions = np.asarray(positions, dtype=np.uint64)
     heads = np.asarray(heads, dtype=np.uint64)
-    out = np.empty((bs, positions.size, heads.size, hs), dtype=np.float64)
+    out = np.empty((bs, positions.size, heads.size, hs), dtype=dtype)
     e = np.arange(hs, dtype=np.uint64)[None, None, :]
-    step = max(1, (1 << 22) // max(1, heads.size * hs))
-    for b in range(bs):
-        for s in range(0, positions.size, step):
-            p = positions[s:s + step, None, None]
-            out[b, s:s + step] = normal_at(seed, tensor_id, b, p, heads[None, :, None], e)
+    step = max(1, (1 << 20) // max(1, heads.size * hs))
+
+    def fill(job):
+        b, s = job
+        p = positions[s:s + step, None, None]
+        out[b, s:s + step] = normal_at(seed, tensor_id, b, p, heads[None, :, None], e)
+
+    jobs = [(b, s) for b in range(bs) for s in range(0, positions.size, step)]
+    if len(jobs) > 1 and threads > 1:
+        # NumPy releases the GIL inside its loops; chunks are independent by construction
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(fill, jobs))
+    else:
+        for j in jobs:
+            fill(j)
     return out
 
 
