@@ -21,6 +21,8 @@
 //   * Work order: heaviest query tiles first (descending local index under a causal mask), KV
 //     group fastest so that workgroups sharing K/V land on the same XCD's L2 when the number of
 //     groups is a multiple of the 8 XCDs.
+#include <type_traits>
+
 #include "usp_internal.h"
 
 namespace usp {
@@ -100,11 +102,28 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
 }
 
 // -------------------------------------------------------------------------------------------
-// bf16 MFMA kernel
+// bf16 MFMA kernel, software pipelined: while the softmax of key tile j runs on the vector ALU,
+// the matrix core already computes the scores of tile j+1, then P(j) V(j).
 // -------------------------------------------------------------------------------------------
-template <int HS, int NQB, int NWAVES, int KT, typename OutT>
-__global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64),
-                          amdgpu_waves_per_eu((NWAVES + 3) / 4, (NWAVES + 3) / 4)))
+// Combine the two lane halves (lanes l and l ^ 32 hold the same query).  v_permlane32_swap(a, b) returns
+// {a.lower | b.lower, a.upper | b.upper}; with a = b = x that is x of the lower half and x of the upper
+// half, each broadcast to both halves.  (The two results are copied to scalars before the bit cast:
+// a bit cast applied directly to a vector element reads element 0.)
+__device__ inline float both_halves_max(float x) {
+  const uint32_t xi = __builtin_bit_cast(uint32_t, x);
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  const uint32_t lo = r[0], hi = r[1];
+  return fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
+}
+__device__ inline float both_halves_sum(float x) {
+  const uint32_t xi = __builtin_bit_cast(uint32_t, x);
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  const uint32_t lo = r[0], hi = r[1];
+  return __builtin_bit_cast(float, lo) + __builtin_bit_cast(float, hi);
+}
+
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
+__global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64), amdgpu_waves_per_eu(WPE, WPE)))
 void block_attn_fwd_mfma(const AttnArgs a) {
   constexpr int NT = NWAVES * 64;
   constexpr int BM = NWAVES * NQB * 32;
@@ -117,11 +136,12 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   constexpr int KBYTES = KT * KSTR, VBYTES = KT * VSTR;
   constexpr int CHUNKS = KT * HS / 8;      // 16 B chunks per tile (K and V alike)
   constexpr int CPT = CHUNKS / NT;         // chunks per thread
+  constexpr float kRescaleThreshold = 8.0f;   // in log2 units: P stays below 2^8
   static_assert(CHUNKS % NT == 0, "tile must split evenly over the workgroup");
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  // [buf][K | V]
-  char* const lds = smem;
+  char* const kbuf = smem;                  // [2][KBYTES]
+  char* const vbuf = smem + 2 * KBYTES;     // [2][VBYTES]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hl = lane >> 5;
@@ -159,6 +179,25 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
   }
 
+  const TileRanges tr = visible_tiles<KT>(a, tile_row0, tile_row1);
+  const int na = tr.a1 - tr.a0;
+  const int nt = na + (tr.b1 - tr.b0);
+  auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
+
+  if (nt == 0) {
+    // nothing visible to this query tile (workgroup-uniform): O = 0, LSE = -inf
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      if (qrow[qb] < a.Lq) {
+        OutT* dst = (OutT*)a.o + (((size_t)b * a.Lq + qrow[qb]) * a.hq + h) * HS + hl * (HS / 2);
+#pragma unroll
+        for (int e = 0; e < HS / 2; ++e) dst[e] = (OutT)0.f;
+        if (hl == 0) a.lse[((size_t)b * a.hq + h) * a.Lq + qrow[qb]] = -INFINITY;
+      }
+    }
+    return;
+  }
+
   f32x16 oacc[NQB][DB];
   float m_run[NQB], l_run[NQB];
 #pragma unroll
@@ -171,76 +210,62 @@ void block_attn_fwd_mfma(const AttnArgs a) {
       for (int i = 0; i < 16; ++i) oacc[qb][db][i] = 0.f;
   }
 
-  const TileRanges tr = visible_tiles<KT>(a, tile_row0, tile_row1);
-  const int na = tr.a1 - tr.a0;
-  const int nt = na + (tr.b1 - tr.b0);
-
   // wave-level bounds for the mask decision
   const int wave_row1 = min(a.Lq, wave_row0 + NQB * 32);
   const bool wave_live = wave_row0 < a.Lq;
   const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, wave_row1) : 0;
 
-  // ---- staging: thread copies CPT 16 B chunks of K and of V per tile
+  // ---- staging: each thread moves CPT 16 B chunks of a K tile and of a V tile
+  const int st_row = tid / (HS / 8), st_col = tid % (HS / 8);
+  constexpr int ROWS_PER_PASS = NT / (HS / 8);
   u32x4 kreg[CPT], vreg[CPT];
-  auto fetch = [&](int it) {
-    const int jt = it < na ? tr.a0 + it : tr.b0 + (it - na);
-    const int key0 = jt * KT;
+  auto fetch = [&](const __bf16* base, int it, u32x4* reg) {
+    const int key0 = tile_of(it) * KT;
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-      const int ch = tid + c * NT;
-      const int row = ch / (HS / 8), col = ch % (HS / 8);
-      const int key = min(key0 + row, a.Lk - 1);
-      kreg[c] = *(const u32x4*)(kg + (size_t)key * kv_row_stride + col * 8);
-      vreg[c] = *(const u32x4*)(vg + (size_t)key * kv_row_stride + col * 8);
+      const int key = min(key0 + st_row + c * ROWS_PER_PASS, a.Lk - 1);
+      reg[c] = *(const u32x4*)(base + (size_t)key * kv_row_stride + st_col * 8);
     }
   };
-  auto stash = [&](int buf) {
-    char* kb = lds + buf * (KBYTES + VBYTES);
-    char* vb = kb + KBYTES;
+  auto stash = [&](char* buf, int stride, const u32x4* reg) {
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int ch = tid + c * NT;
-      const int row = ch / (HS / 8), col = ch % (HS / 8);
-      *(u32x4*)(kb + row * KSTR + col * 16) = kreg[c];
-      *(u32x4*)(vb + row * VSTR + col * 16) = vreg[c];
-    }
+    for (int c = 0; c < CPT; ++c) *(u32x4*)(buf + (st_row + c * ROWS_PER_PASS) * stride + st_col * 16) = reg[c];
   };
 
-  if (nt > 0) {
-    fetch(0);
-    stash(0);
-  }
-  __syncthreads();
-
-  for (int it = 0; it < nt; ++it) {
-    const int cur = it & 1;
-    const bool more = it + 1 < nt;
-    if (more) fetch(it + 1);
-
-    const int jt = it < na ? tr.a0 + it : tr.b0 + (it - na);
-    const int key0 = jt * KT;
-    const char* kb = lds + cur * (KBYTES + VBYTES);
-    const char* vb = kb + KBYTES;
-
-    // ---- S^T = K Q^T   (rows = keys, cols = queries)
-    f32x16 sacc[NQB][KB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[qb][kbk][i] = 0.f;
+  // ---- S^T = K Q^T for the tile in K buffer kb_ (rows = keys, cols = queries)
+  auto qk = [&](const char* kb_, f32x16 (&sacc)[NQB][KB]) {
 #pragma unroll
     for (int kbk = 0; kbk < KB; ++kbk) {
-      const char* krow = kb + (kbk * 32 + l32) * KSTR + hl * 16;
+      const char* krow = kb_ + (kbk * 32 + l32) * KSTR + hl * 16;
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
         const bf16x8 kf = *(const bf16x8*)(krow + ks * 32);
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-          sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][kbk], 0, 0, 0);
+        for (int qb = 0; qb < NQB; ++qb) {
+          if (ks == 0) {
+            f32x16 z;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) z[i] = 0.f;
+            sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], z, 0, 0, 0);
+          } else {
+            sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][kbk], 0, 0, 0);
+          }
+        }
       }
     }
+  };
+
+  // One pipeline step on tile `it` whose scores are in s_cur.  Unless LAST, the scores of tile it+1
+  // are produced into s_next while the softmax of s_cur runs.
+  const int grp = lane >> 4, j16 = lane & 15;
+  const int v_lane_off = (4 * hl + (j16 >> 2)) * VSTR + (16 * (grp & 1) + 4 * (j16 & 3)) * 2;
+  auto step = [&](auto steady_tag, int it, f32x16 (&s_cur)[NQB][KB], f32x16 (&s_next)[NQB][KB]) {
+    // steady state (tag true): a next tile and a tile after that exist, no branches in the main block;
+    // otherwise the two conditions are evaluated at run time (the last up-to-three tiles)
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    const bool has1 = STEADY || it + 1 < nt;
+    const bool has2 = STEADY || it + 2 < nt;
+    const int key0 = tile_of(it) * KT;
 
     // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave
     const int key1 = min(a.Lk, key0 + KT);
@@ -257,26 +282,56 @@ void block_attn_fwd_mfma(const AttnArgs a) {
 #pragma unroll
           for (int qb = 0; qb < NQB; ++qb) {
             const bool vis = inb && (!a.causal || kp <= qp[qb]);
-            sacc[qb][kbk][i] = vis ? sacc[qb][kbk][i] : -INFINITY;
+            s_cur[qb][kbk][i] = vis ? s_cur[qb][kbk][i] : -INFINITY;
           }
         }
     }
 
-    // ---- online softmax per query block; P^T packed to bf16 in the B-operand layout
-    bf16x8 pf[NQB][PS];
+    // ---- row maxima; the running maximum only moves when a row grew by more than the threshold, so the
+    //      accumulator rescale is rare (P is then bounded by 2^threshold instead of 1)
+    float mc[NQB];
+    bool grow = false;
+    float mx[NQB];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      float mx = -INFINITY;
+      float x = -INFINITY;
 #pragma unroll
       for (int kbk = 0; kbk < KB; ++kbk)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[qb][kbk][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[qb], mx);
-      const float mc = (m_new == -INFINITY) ? 0.f : m_new * a.scale_log2;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[qb] * a.scale_log2 - mc);   // m_run = -inf -> 0
-      m_run[qb] = m_new;
-      float rs = 0.f;
+        for (int i = 0; i < 16; ++i) x = fmaxf(x, s_cur[qb][kbk][i]);
+      x = both_halves_max(x);
+      mx[qb] = x;
+      // first visible key of a row (m_run = -inf) always takes the branch: inf > threshold
+      grow = grow || ((x - m_run[qb]) * a.scale_log2 > kRescaleThreshold);
+    }
+    if (__any(grow)) {
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const float m_new = fmaxf(m_run[qb], mx[qb]);
+        const float mcn = (m_new == -INFINITY) ? 0.f : m_new * a.scale_log2;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] * a.scale_log2 - mcn);   // m_run = -inf -> 0
+        m_run[qb] = m_new;
+        l_run[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
+      }
+    }
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) mc[qb] = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb] * a.scale_log2;
+
+    // ---- global prefetch: K two tiles ahead, V one tile ahead
+    if (has2) fetch(kg, it + 2, kreg);
+    if (has1) fetch(vg, it + 1, vreg);
+
+    // ---- main block: scores of the next tile on the matrix core, softmax of this tile on the vector ALU
+    if (has1) qk(kbuf + ((it + 1) & 1) * KBYTES, s_next);
+
+    bf16x8 pf[NQB][PS];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      float rs = l_run[qb];
 #pragma unroll
       for (int kbk = 0; kbk < KB; ++kbk) {
 #pragma unroll
@@ -284,29 +339,24 @@ void block_attn_fwd_mfma(const AttnArgs a) {
           u32x4 pk;
 #pragma unroll
           for (int pr = 0; pr < 4; ++pr) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][kbk][half * 8 + 2 * pr], a.scale_log2, -mc));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][kbk][half * 8 + 2 * pr + 1], a.scale_log2, -mc));
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][kbk][half * 8 + 2 * pr], a.scale_log2, -mc[qb]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][kbk][half * 8 + 2 * pr + 1], a.scale_log2, -mc[qb]));
+            f32x2 pp = {p0, p1};
+            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
             rs += p0 + p1;
-            pk[pr] = pack_bf16(p0, p1);
+            pk[pr] = __builtin_bit_cast(uint32_t, pb);
           }
           pf[qb][kbk * 2 + half] = __builtin_bit_cast(bf16x8, pk);
         }
       }
-      l_run[qb] = l_run[qb] * alpha + rs;
-      if (__any(alpha != 1.0f)) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
-      }
+      l_run[qb] = rs;
     }
 
     // ---- O^T += V^T P^T   (rows = head dims, cols = queries, k = keys)
     // MFMA k index e of lane half hl in step s is key 16 s + 8 (e / 4) + 4 hl + (e % 4): the
     // accumulator layout of S^T.  The transpose read returns, for a 16-lane group whose lane j
     // points at (key base + j / 4, dim base + 4 (j % 4)), the 4 keys of dim base + j to lane j.
-    const int grp = lane >> 4, j16 = lane & 15;
-    const char* vlane = vb + (4 * hl + (j16 >> 2)) * VSTR + (16 * (grp & 1) + 4 * (j16 & 3)) * 2;
+    const char* vlane = vbuf + (it & 1) * VBYTES + v_lane_off;
 #pragma unroll
     for (int s = 0; s < PS; ++s) {
 #pragma unroll
@@ -321,14 +371,45 @@ void block_attn_fwd_mfma(const AttnArgs a) {
       }
     }
 
-    if (more) stash(cur ^ 1);
+    // ---- hand the prefetched tiles to LDS: K(it+2) replaces K(it), V(it+1) replaces V(it-1)
+    if (has2) stash(kbuf + (it & 1) * KBYTES, KSTR, kreg);
+    if (has1) stash(vbuf + ((it + 1) & 1) * VBYTES, VSTR, vreg);
     __syncthreads();
+  };
+
+  // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0
+  fetch(kg, 0, kreg);
+  fetch(vg, 0, vreg);
+  stash(kbuf, KSTR, kreg);
+  stash(vbuf, VSTR, vreg);
+  if (nt > 1) {
+    fetch(kg, 1, kreg);
+    stash(kbuf + KBYTES, KSTR, kreg);
+  }
+  __syncthreads();
+  f32x16 s0[NQB][KB], s1[NQB][KB];
+  qk(kbuf, s0);
+  __syncthreads();   // step 0 overwrites K buffer 0 with tile 2: every wave must have read tile 0 first
+
+  const std::integral_constant<bool, true> steady;
+  const std::integral_constant<bool, false> draining;
+  int it = 0;
+  for (; it + 3 < nt; it += 2) {   // two steps per trip so the score registers swap roles without copies
+    step(steady, it, s0, s1);
+    step(steady, it + 1, s1, s0);
+  }
+  for (; it < nt; ++it) {          // at most three tiles left
+    step(draining, it, s0, s1);
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int kbk = 0; kbk < KB; ++kbk) s0[qb][kbk] = s1[qb][kbk];
   }
 
   // ---- epilogue: normalise, write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
+    const float l_tot = both_halves_sum(l_run[qb]);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (qrow[qb] < a.Lq) {
       OutT* dst = (OutT*)a.o + (((size_t)b * a.Lq + qrow[qb]) * a.hq + h) * HS + 4 * hl;
@@ -422,7 +503,7 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
   }
 }
 
-template <int HS, int NQB, int NWAVES, int KT, typename OutT>
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
 int launch_mfma(AttnArgs a, hipStream_t stream) {
   constexpr int BM = NWAVES * NQB * 32;
   constexpr int KSTR = HS * 2 + 16, VSTR = (HS == 128) ? 320 : 192;
@@ -430,7 +511,7 @@ int launch_mfma(AttnArgs a, hipStream_t stream) {
   a.n_qtiles = (a.Lq + BM - 1) / BM;
   const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs;
   if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
-  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, OutT>;
+  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT>;
   static bool attr_set = false;   // raise the dynamic LDS limit once per instance
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -480,18 +561,24 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
     return o_dtype == USP_FP32 ? launch_fp32<64, float>(a, stream) : launch_fp32<64, __bf16>(a, stream);
   }
   const int var = mfma_variant();
+#define USP_VARIANT(id, NQB, NW, KT, WPE)                                                       \
+  if (var == id)                                                                                \
+    return o_dtype == USP_FP32 ? launch_mfma<128, NQB, NW, KT, WPE, float>(a, stream)           \
+                               : launch_mfma<128, NQB, NW, KT, WPE, __bf16>(a, stream);
   if (hs == 128) {
-    if (o_dtype == USP_FP32) {
-      if (var == 1) return launch_mfma<128, 2, 4, 64, float>(a, stream);
-      if (var == 2) return launch_mfma<128, 1, 4, 64, float>(a, stream);
-      return launch_mfma<128, 1, 8, 64, float>(a, stream);
-    }
-    if (var == 1) return launch_mfma<128, 2, 4, 64, __bf16>(a, stream);
-    if (var == 2) return launch_mfma<128, 1, 4, 64, __bf16>(a, stream);
-    return launch_mfma<128, 1, 8, 64, __bf16>(a, stream);
+    USP_VARIANT(1, 2, 4, 64, 1)
+    USP_VARIANT(2, 1, 4, 64, 1)
+    USP_VARIANT(3, 1, 4, 64, 2)
+    USP_VARIANT(4, 1, 4, 32, 2)
+    USP_VARIANT(5, 1, 8, 32, 2)
+    USP_VARIANT(6, 1, 8, 128, 2)
+    USP_VARIANT(7, 1, 4, 32, 3)
+    return o_dtype == USP_FP32 ? launch_mfma<128, 1, 8, 64, 2, float>(a, stream)
+                               : launch_mfma<128, 1, 8, 64, 2, __bf16>(a, stream);
   }
-  if (o_dtype == USP_FP32) return launch_mfma<64, 1, 8, 64, float>(a, stream);
-  return launch_mfma<64, 1, 8, 64, __bf16>(a, stream);
+#undef USP_VARIANT
+  if (o_dtype == USP_FP32) return launch_mfma<64, 1, 8, 64, 2, float>(a, stream);
+  return launch_mfma<64, 1, 8, 64, 2, __bf16>(a, stream);
 }
 
 }  // namespace usp
