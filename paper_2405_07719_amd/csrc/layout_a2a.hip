@@ -12,7 +12,7 @@ namespace usp {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 8;   // vectors per thread: 8 x 16 B in flight per lane
+constexpr int kUnroll = 4;   // vectors per thread; measured: 4 x 16 B per lane streams ~45 % faster than 8 on MI355X
 
 struct LayoutArgs {
   const char* seq;     // sequence-layout buffer base
@@ -37,27 +37,32 @@ __global__ __launch_bounds__(kThreads) void layout_a2a_kernel(LayoutArgs a) {
   const uint64_t seq_row0 = ((uint64_t)(r * a.U + up) * a.bs + b) * a.n;
   Vec* seq = (Vec*)a.seq + seq_row0 * a.row_vecs + (uint64_t)u * a.run_vecs;
 
-  const uint64_t base = (uint64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+  // One 32-bit division per thread; the following vectors step by kThreads with carried row / column.
+  const uint32_t slab32 = (uint32_t)slab_vecs;
+  const uint32_t base = blockIdx.x * (uint32_t)(kThreads * kUnroll) + threadIdx.x;
+  uint32_t row = base / a.run_vecs, col = base - row * a.run_vecs;
+  const uint32_t drow = kThreads / a.run_vecs, dcol = kThreads - drow * a.run_vecs;
+  uint64_t seq_off[kUnroll];
   Vec val[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const uint64_t idx = base + (uint64_t)i * kThreads;
-    if (idx < slab_vecs) {
-      const uint64_t row = idx / a.run_vecs;
-      const uint32_t c = (uint32_t)(idx - row * a.run_vecs);
-      const Vec* s = kToHead ? seq + row * a.row_vecs + c : head + idx;
-      val[i] = __builtin_nontemporal_load(s);
+    seq_off[i] = (uint64_t)row * a.row_vecs + col;
+    row += drow;
+    col += dcol;
+    if (col >= a.run_vecs) {
+      col -= a.run_vecs;
+      ++row;
     }
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const uint64_t idx = base + (uint64_t)i * kThreads;
-    if (idx < slab_vecs) {
-      const uint64_t row = idx / a.run_vecs;
-      const uint32_t c = (uint32_t)(idx - row * a.run_vecs);
-      Vec* d = kToHead ? head + idx : seq + row * a.row_vecs + c;
-      __builtin_nontemporal_store(val[i], d);
-    }
+    const uint32_t idx = base + (uint32_t)i * kThreads;
+    if (idx < slab32) val[i] = __builtin_nontemporal_load(kToHead ? seq + seq_off[i] : head + idx);
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const uint32_t idx = base + (uint32_t)i * kThreads;
+    if (idx < slab32) __builtin_nontemporal_store(val[i], kToHead ? head + idx : seq + seq_off[i]);
   }
 }
 
@@ -70,7 +75,9 @@ int launch_vec(LayoutArgs a, int dir, size_t run_bytes, size_t row_bytes, int n_
   a.row_vecs = (uint32_t)(row_bytes / sizeof(Vec));
   const uint64_t slab_vecs = (uint64_t)a.n * a.run_vecs;
   const uint64_t gx = (slab_vecs + (uint64_t)kThreads * kUnroll - 1) / ((uint64_t)kThreads * kUnroll);
-  if (gx > 0x7fffffffull || (uint64_t)n_ranks * a.bs > 65535ull || a.U > 65535) return USP_ERR_UNSUPPORTED;
+  // the kernel indexes a slab with 32 bits (a slab is one rank's share of one shard: far below 4 Gi vectors)
+  if (slab_vecs + (uint64_t)kThreads * kUnroll >= (1ull << 32) || (uint64_t)n_ranks * a.bs > 65535ull || a.U > 65535)
+    return USP_ERR_UNSUPPORTED;
   dim3 grid((unsigned)gx, (unsigned)a.U, (unsigned)(n_ranks * a.bs));
   if (dir == USP_SEQ_TO_HEAD)
     hipLaunchKernelGGL((layout_a2a_kernel<Vec, true>), grid, dim3(kThreads), 0, stream, a);

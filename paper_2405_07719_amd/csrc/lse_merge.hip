@@ -28,13 +28,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-__device__ inline f32x4 load4(const float* p) { return *(const f32x4*)p; }
+// streaming accesses: every byte is touched once, keep it out of the caches' way
+__device__ inline f32x4 load4(const float* p) { return __builtin_nontemporal_load((const f32x4*)p); }
 __device__ inline f32x4 load4(const __bf16* p) {
-  bf16x4 v = *(const bf16x4*)p;
+  bf16x4 v = __builtin_nontemporal_load((const bf16x4*)p);
   return __builtin_convertvector(v, f32x4);
 }
-__device__ inline void store4(float* p, f32x4 v) { *(f32x4*)p = v; }
-__device__ inline void store4(__bf16* p, f32x4 v) { *(bf16x4*)p = __builtin_convertvector(v, bf16x4); }
+__device__ inline void store4(float* p, f32x4 v) { __builtin_nontemporal_store(v, (f32x4*)p); }
+__device__ inline void store4(__bf16* p, f32x4 v) {
+  __builtin_nontemporal_store(__builtin_convertvector(v, bf16x4), (bf16x4*)p);
+}
 
 template <typename PartT, typename OutT>
 __global__ __launch_bounds__(kThreads) void lse_merge_kernel(MergeArgs a) {
@@ -76,15 +79,17 @@ __global__ __launch_bounds__(kThreads) void lse_merge_kernel(MergeArgs a) {
     const int64_t off = elem0 + vi * 4;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     int p = 0;
-    for (; p + 4 <= n; p += 4) {
-      f32x4 x0 = load4((const PartT*)a.o[p] + off), x1 = load4((const PartT*)a.o[p + 1] + off);
-      f32x4 x2 = load4((const PartT*)a.o[p + 2] + off), x3 = load4((const PartT*)a.o[p + 3] + off);
-      const float w0 = w_lds[p * kRows + lr], w1 = w_lds[(p + 1) * kRows + lr];
-      const float w2 = w_lds[(p + 2) * kRows + lr], w3 = w_lds[(p + 3) * kRows + lr];
-      // a zero weight must erase the part even if it holds garbage (a skipped step writes o = 0, but
-      // be safe against NaN payloads): select instead of multiply
-      acc += (w0 != 0.f ? x0 * w0 : f32x4{0, 0, 0, 0}) + (w1 != 0.f ? x1 * w1 : f32x4{0, 0, 0, 0}) +
-             (w2 != 0.f ? x2 * w2 : f32x4{0, 0, 0, 0}) + (w3 != 0.f ? x3 * w3 : f32x4{0, 0, 0, 0});
+    // eight partial rows in flight per lane before the first multiply
+    for (; p + 8 <= n; p += 8) {
+      f32x4 x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = load4((const PartT*)a.o[p + j] + off);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float w = w_lds[(p + j) * kRows + lr];
+        // a zero weight must erase the part even if it holds garbage (NaN payload of a skipped step)
+        if (w != 0.f) acc += x[j] * w;
+      }
     }
     for (; p < n; ++p) {
       f32x4 x = load4((const PartT*)a.o[p] + off);
