@@ -133,10 +133,35 @@ size_t usp_attn_fwd_workspace_bytes(const usp_problem* p, int n_ranks);
 int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
                  int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Algorithm 1 backward (Sec. 3: the all-to-alls swap their scatter/gather roles).
- *   d_o: seq layout; o, lse: as produced by usp_attn_fwd; dq, dk, dv: seq layout outputs.
- * dq is complete for the ranks in range; dk/dv receive only those ranks' contributions, so
- * complete dk/dv needs rank_begin = 0, rank_end = N.  dk and dv are overwritten. */
+/* D_i = sum_e dO[i][e] * O[i][e] per (batch, position, head) row: the row term of the softmax gradient
+ * (textbook backward of Eq. 1).  o, d_o [bs,L,h,hs] bf16 -> delta [bs,h,L] float. */
+int usp_attn_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs, void* stream);
+
+/* Backward of one ring step (gradient of Eq. 1 restricted to one K/V block; shapes and mask as in
+ * usp_block_attn_fwd; bf16 inputs only).  lse [bs,hq,Lq] is the FINAL log-sum-exp of each query row over
+ * all blocks (as usp_attn_fwd / usp_lse_merge return it) and delta comes from usp_attn_delta, so that
+ * P_ij = exp(scale q_i.k_j - lse_i) is exact and contributions of different blocks add:
+ *   dq [bs,Lq,hq,hs]  (+)= scale * sum_j dS_ij k_j      dS_ij = P_ij (dO_i.v_j - delta_i)
+ *   dk [bs,Lk,hkv,hs] (+)= scale * sum_i dS_ij q_i      (summed over the query heads of the KV head's group)
+ *   dv [bs,Lk,hkv,hs] (+)= sum_i P_ij dO_i
+ * dq, dk, dv are fp32; accumulate = 0 overwrites them, 1 adds to them (deterministic, no atomics). */
+int usp_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                       const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
+                       int hkv, int hs, float scale, int causal, const usp_posdesc* qpos, const usp_posdesc* kpos,
+                       int accumulate, void* stream);
+
+/* Algorithm 1 backward (Sec. 3: the all-to-alls swap their scatter/gather roles) for virtual ranks
+ * [rank_begin, rank_end); bf16 problems only.
+ *   q, k, v, o, d_o: seq layout (o as usp_attn_fwd wrote it); lse: [N][bs][hc/U][L/R] from usp_attn_fwd;
+ *   dq, dk, dv: seq layout outputs in the problem dtype.
+ * Per rank: all-to-all of Q, O, dO -> delta -> R block backwards (dQ accumulated over the ring steps in
+ * fp32; the dK/dV contribution of step i is added to block (r-i) mod R's fp32 accumulator, the buffer that
+ * would travel the ring with the block) -> all-to-all of dQ.  After the last rank the dK/dV accumulators
+ * are converted and all-to-all'ed back.
+ * dq is complete for the ranks in range (each fills its head slice of its Ulysses group's shards).
+ * dk/dv: for every ring row and every Ulysses column touched by the range, the column's head slice is
+ * OVERWRITTEN with the sum of the contributions of the ranks in range; complete dk/dv therefore needs
+ * rank_begin = 0, rank_end = N (or all R ring rows of one column for that column's head slice). */
 size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks);
 int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,
                  const float* lse, const void* d_o, void* dq, void* dk, void* dv, int rank_begin,

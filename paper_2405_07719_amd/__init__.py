@@ -65,11 +65,14 @@ def load():
     lib.usp_attn_fwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_fwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_fwd.argtypes = [P(usp_problem), V, V, V, V, V, I, I, V, C.c_size_t, V]
+    lib.usp_attn_delta.argtypes = [V, V, V, I, L, I, I, V]
+    lib.usp_block_attn_bwd.argtypes = [V, V, V, V, V, V, V, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc), P(usp_posdesc),
+                                       I, V]
     lib.usp_attn_bwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_bwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_bwd.argtypes = [P(usp_problem), V, V, V, V, V, V, V, V, V, I, I, V, C.c_size_t, V]
     for name in ("usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
-                 "usp_attn_fwd", "usp_attn_bwd"):
+                 "usp_attn_fwd", "usp_attn_bwd", "usp_attn_delta", "usp_block_attn_bwd"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -145,6 +148,19 @@ def usp_attn_fwd(p, q, k, v, o, lse, rank_begin, rank_end, workspace, workspace_
         workspace_bytes = workspace.numel() * workspace.element_size()
     _check(load().usp_attn_fwd(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), rank_begin, rank_end,
                                _ptr(workspace), workspace_bytes, _stream(stream)), "usp_attn_fwd")
+
+
+def usp_attn_delta(o, d_o, delta, bs, L, h, hs, stream=None):
+    _check(load().usp_attn_delta(_ptr(o), _ptr(d_o), _ptr(delta), bs, L, h, hs, _stream(stream)), "usp_attn_delta")
+
+
+def usp_block_attn_bwd(q, k, v, d_o, lse, delta, dq, dk, dv, bs, Lq, Lk, hq, hkv, hs, scale, causal, qpos, kpos,
+                       accumulate, stream=None):
+    _check(load().usp_block_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta), _ptr(dq), _ptr(dk),
+                                     _ptr(dv), bs, Lq, Lk, hq, hkv, hs, scale, int(bool(causal)),
+                                     C.byref(qpos) if qpos is not None else None,
+                                     C.byref(kpos) if kpos is not None else None, int(bool(accumulate)),
+                                     _stream(stream)), "usp_block_attn_bwd")
 
 
 def usp_attn_bwd_workspace_bytes(p, n_ranks):

@@ -1,0 +1,498 @@
+// Backward of one ring step of blockwise attention (textbook gradient of Eq. 1, Sec. 2, restricted to one
+// K/V block; the paper only says that the backward all-to-alls swap their scatter/gather roles, Sec. 3).
+//
+// With the FINAL log-sum-exp L_i of a query row (over all keys of all blocks) and D_i = sum_e dO_ie O_ie:
+//   P_ij = exp(scale q_i.k_j - L_i),  dV_j = sum_i P_ij dO_i,  dS_ij = P_ij (dO_i.v_j - D_i),
+//   dQ_i = scale sum_j dS_ij k_j,     dK_j = scale sum_i dS_ij q_i.
+// P and dS are exact per element, so the contributions of different K/V blocks simply add.
+//
+// Two deterministic kernels (no atomics), both on v_mfma_f32_32x32x16_bf16 with fp32 accumulation:
+//   dq_kernel    a workgroup owns 256 query rows, walks the visible key tiles:  S^T = K Q^T, dP^T = V dO^T
+//                (lane = query, so L_i and D_i are per-lane scalars), dQ^T += K^T dS^T.
+//   dkdv_kernel  a workgroup owns 128 keys of one KV head, walks the query heads of the group and the
+//                visible query tiles:  S = Q K^T, dP = dO V^T (lane = key; L_i, D_i read from LDS),
+//                dV^T += dO^T P, dK^T += Q^T dS.  The sum over the group's query heads stays in registers.
+// In both, the accumulator layout of the first product is the B-operand layout of the second, and the
+// transposed A operands come from LDS transpose reads (tiles are kept in LDS twice: rows padded for 16 B
+// row reads, and rows padded for the transpose read).
+// Outputs are fp32 accumulators (overwrite or add), so ring steps and ranks can be summed before the
+// final conversion to the problem dtype.
+#include "attn_device.h"
+#include "usp_internal.h"
+
+namespace usp {
+namespace {
+
+using namespace dev;
+
+struct BwdArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  const void* d_o;
+  const float* lse;     // [bs,hq,Lq]  final LSE (natural log)
+  const float* delta;   // [bs,hq,Lq]  D_i
+  float* dq;            // [bs,Lq,hq,hs]  fp32
+  float* dk;            // [bs,Lk,hkv,hs] fp32
+  float* dv;            // [bs,Lk,hkv,hs] fp32
+  int bs, hq, hkv, g;
+  int Lq, Lk;
+  int n_tiles;          // query tiles (dq) or key tiles (dkdv)
+  int causal;
+  int accumulate;       // 0: overwrite the outputs, 1: add to them
+  float scale, scale_log2;
+  PosDesc32 qpos, kpos;
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// transpose-read address of this lane inside a [rows][VSTR] tile: see the forward kernel
+template <int VSTR>
+__device__ inline int tr_lane_offset(int lane) {
+  const int hl = lane >> 5, grp = lane >> 4, j16 = lane & 15;
+  return (4 * hl + (j16 >> 2)) * VSTR + (16 * (grp & 1) + 4 * (j16 & 3)) * 2;
+}
+
+template <int VSTR>
+__device__ inline bf16x8 tr_read(const char* p0) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+__device__ inline void zero16(f32x16& x) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = 0.f;
+}
+
+// 16 fp32 values of a 32x32 accumulator block -> two bf16 B-operand fragments (k-steps of 16)
+__device__ inline void pack_b_operand(const float (&x)[16], bf16x8& lo, bf16x8& hi) {
+  u32x4 a, b;
+#pragma unroll
+  for (int pr = 0; pr < 4; ++pr) {
+    a[pr] = pack_bf16(x[2 * pr], x[2 * pr + 1]);
+    b[pr] = pack_bf16(x[8 + 2 * pr], x[8 + 2 * pr + 1]);
+  }
+  lo = __builtin_bit_cast(bf16x8, a);
+  hi = __builtin_bit_cast(bf16x8, b);
+}
+
+// -------------------------------------------------------------------------------------------------
+// D_i = sum_e dO_ie * O_ie   (rows of [bs,L,h,hs] tensors -> [bs,h,L] fp32)
+// -------------------------------------------------------------------------------------------------
+template <int HS>
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* o, const __bf16* d_o, float* delta, int bs,
+                                                        int L, int h) {
+  constexpr int TPR = HS / 8;   // lanes per row, 8 elements each
+  const int64_t rows = (int64_t)bs * L * h;
+  const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / TPR;
+  const int part = threadIdx.x % TPR;
+  float acc = 0.f;
+  if (row < rows) {
+    const bf16x8 a = *(const bf16x8*)(o + row * HS + part * 8);
+    const bf16x8 b = *(const bf16x8*)(d_o + row * HS + part * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
+  }
+#pragma unroll
+  for (int m = TPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+  if (row < rows && part == 0) {
+    const int64_t hh = row % h, i = (row / h) % L, b = row / ((int64_t)h * L);
+    delta[(b * h + hh) * L + i] = acc;
+  }
+}
+
+// -------------------------------------------------------------------------------------------------
+// dQ
+// -------------------------------------------------------------------------------------------------
+template <int HS>
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
+void bwd_dq_kernel(const BwdArgs a) {
+  constexpr int NT = 512, BM = 256, KT = 32;
+  constexpr int KSTEPS = HS / 16, DB = HS / 32;
+  constexpr int RSTR = HS * 2 + 16;                 // rows for 16 B row reads
+  constexpr int TSTR = (HS == 128) ? 320 : 192;     // rows for the transpose read
+  constexpr int CPR = HS / 8;                       // 16 B chunks per row
+  static_assert(KT * CPR <= NT, "one chunk per thread");
+  __shared__ __attribute__((aligned(16))) char k_rm[KT * RSTR];
+  __shared__ __attribute__((aligned(16))) char k_tr[KT * TSTR];
+  __shared__ __attribute__((aligned(16))) char v_rm[KT * RSTR];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hl = lane >> 5;
+  const int n_groups = a.bs * a.hkv;
+  int w = blockIdx.x;
+  const int group = w % n_groups; w /= n_groups;
+  const int hg = w % a.g;
+  const int t = w / a.g;
+  const int qtile = a.causal ? a.n_tiles - 1 - t : t;
+  const int b = group / a.hkv, kvh = group % a.hkv;
+  const int h = kvh * a.g + hg;
+  const int tile_row0 = qtile * BM, tile_row1 = min(a.Lq, tile_row0 + BM);
+  const int wave_row0 = tile_row0 + wave * 32;
+  const int qrow = wave_row0 + l32;
+  const int rr = min(qrow, a.Lq - 1);
+  const int qp = a.causal ? pos_of(a.qpos, rr) : 0;
+
+  const __bf16* kg = (const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
+  const __bf16* vg = (const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
+  const size_t kv_row_stride = (size_t)a.hkv * HS;
+
+  bf16x8 qf[KSTEPS], dof[KSTEPS];
+  {
+    const size_t off = (((size_t)b * a.Lq + rr) * a.hq + h) * HS + 8 * hl;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      qf[ks] = *(const bf16x8*)((const __bf16*)a.q + off + 16 * ks);
+      dof[ks] = *(const bf16x8*)((const __bf16*)a.d_o + off + 16 * ks);
+    }
+  }
+  const size_t stat = ((size_t)b * a.hq + h) * a.Lq + rr;
+  const float lse = a.lse[stat];
+  const float l2 = (lse == -INFINITY) ? INFINITY : lse * kLog2e;   // a row that saw nothing: P = 0
+  const float dlt = a.delta[stat];
+
+  f32x16 dq[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) zero16(dq[db]);
+
+  const TileRanges tr = visible_key_tiles<KT>(a.causal, a.qpos, a.kpos, a.Lk, tile_row0, tile_row1);
+  const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
+  auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
+  const bool wave_live = wave_row0 < a.Lq;
+  const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, min(a.Lq, wave_row0 + 32)) : 0;
+
+  const int st_row = tid / CPR, st_col = tid % CPR;
+  const bool stager = st_row < KT;
+  u32x4 kreg, vreg;
+  auto fetch = [&](int it) {
+    if (stager) {
+      const int key = min(tile_of(it) * KT + st_row, a.Lk - 1);
+      kreg = *(const u32x4*)(kg + (size_t)key * kv_row_stride + st_col * 8);
+      vreg = *(const u32x4*)(vg + (size_t)key * kv_row_stride + st_col * 8);
+    }
+  };
+  const int tr_off = tr_lane_offset<TSTR>(lane);
+
+  if (nt > 0) fetch(0);
+  for (int it = 0; it < nt; ++it) {
+    if (stager) {
+      *(u32x4*)(k_rm + st_row * RSTR + st_col * 16) = kreg;
+      *(u32x4*)(k_tr + st_row * TSTR + st_col * 16) = kreg;
+      *(u32x4*)(v_rm + st_row * RSTR + st_col * 16) = vreg;
+    }
+    __syncthreads();
+    if (it + 1 < nt) fetch(it + 1);
+    const int key0 = tile_of(it) * KT;
+
+    // S^T = K Q^T and dP^T = V dO^T   (rows = keys, cols = queries)
+    f32x16 s, dp;
+    zero16(s);
+    zero16(dp);
+    const int row_off = l32 * RSTR + hl * 16;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const bf16x8 kf = *(const bf16x8*)(k_rm + row_off + ks * 32);
+      const bf16x8 vf = *(const bf16x8*)(v_rm + row_off + ks * 32);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dp, 0, 0, 0);
+    }
+
+    const int key1 = min(a.Lk, key0 + KT);
+    bool need_mask = key0 + KT > a.Lk;
+    if (a.causal && wave_live) need_mask = need_mask || (pos_max(a.kpos, key0, key1) > wave_qmin);
+    float ds[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2));
+      if (need_mask) {
+        const int key = key0 + 8 * (i >> 2) + 4 * hl + (i & 3);
+        const bool vis = key < a.Lk && (!a.causal || pos_of(a.kpos, key) <= qp);
+        p = vis ? p : 0.f;
+      }
+      ds[i] = p * (dp[i] - dlt);
+    }
+    bf16x8 dsf[2];
+    pack_b_operand(ds, dsf[0], dsf[1]);
+
+    // dQ^T += K^T dS^T   (rows = head dims, cols = queries, k = keys)
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 kt = tr_read<TSTR>(k_tr + tr_off + (16 * st) * TSTR + db * 64);
+        dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf[st], dq[db], 0, 0, 0);
+      }
+    __syncthreads();
+  }
+
+  if (qrow < a.Lq) {
+    float* dst = a.dq + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x4 v4 = {dq[db][4 * j] * a.scale, dq[db][4 * j + 1] * a.scale, dq[db][4 * j + 2] * a.scale,
+                    dq[db][4 * j + 3] * a.scale};
+        f32x4* d = (f32x4*)(dst + db * 32 + j * 8);
+        if (a.accumulate) v4 += *d;
+        *d = v4;
+      }
+  }
+}
+
+// -------------------------------------------------------------------------------------------------
+// dK, dV
+// -------------------------------------------------------------------------------------------------
+template <int HS>
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(1, 1)))
+void bwd_dkdv_kernel(const BwdArgs a) {
+  constexpr int NT = 256, BN = 128, QT = 32;
+  constexpr int KSTEPS = HS / 16, DB = HS / 32;
+  constexpr int RSTR = HS * 2 + 16;
+  constexpr int TSTR = (HS == 128) ? 320 : 192;
+  constexpr int CPR = HS / 8;
+  constexpr int CPT = QT * CPR / NT;                 // chunks per thread per tensor
+  static_assert(QT * CPR % NT == 0 && CPT >= 1, "query tile must split evenly over the workgroup");
+  __shared__ __attribute__((aligned(16))) char q_rm[QT * RSTR];
+  __shared__ __attribute__((aligned(16))) char q_tr[QT * TSTR];
+  __shared__ __attribute__((aligned(16))) char o_rm[QT * RSTR];
+  __shared__ __attribute__((aligned(16))) char o_tr[QT * TSTR];
+  __shared__ __attribute__((aligned(16))) float l2_s[QT];
+  __shared__ __attribute__((aligned(16))) float dl_s[QT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hl = lane >> 5;
+  int w = blockIdx.x;
+  const int n_groups = a.bs * a.hkv;
+  const int group = w % n_groups;
+  const int ktile = w / n_groups;          // ascending local index: keys seen by the most queries first
+  const int b = group / a.hkv, kvh = group % a.hkv;
+  const int tile_key0 = ktile * BN, tile_key1 = min(a.Lk, tile_key0 + BN);
+  const int wave_key0 = tile_key0 + wave * 32;
+  const int key = wave_key0 + l32;
+  const int kk = min(key, a.Lk - 1);
+  const int kp = a.causal ? pos_of(a.kpos, kk) : 0;
+  const bool key_ok = key < a.Lk;
+
+  bf16x8 kf[KSTEPS], vf[KSTEPS];
+  {
+    const size_t off = (((size_t)b * a.Lk + kk) * a.hkv + kvh) * HS + 8 * hl;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      kf[ks] = *(const bf16x8*)((const __bf16*)a.k + off + 16 * ks);
+      vf[ks] = *(const bf16x8*)((const __bf16*)a.v + off + 16 * ks);
+    }
+  }
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    zero16(dk[db]);
+    zero16(dv[db]);
+  }
+
+  const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, a.kpos, a.Lq, tile_key0, tile_key1);
+  const int na = tr.a1 - tr.a0, nq = na + (tr.b1 - tr.b0);
+  const int nt = nq * a.g;                  // (query head of the group, visible query tile) pairs
+  auto tile_of = [&](int it) { const int j = it % nq; return j < na ? tr.a0 + j : tr.b0 + (j - na); };
+  const bool wave_live = wave_key0 < a.Lk;
+  const int wave_kmax = (a.causal && wave_live) ? pos_max(a.kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
+
+  const int st_row = tid / CPR, st_col = tid % CPR;
+  constexpr int ROWS_PER_PASS = NT / CPR;
+  u32x4 qreg[CPT], oreg[CPT];
+  float streg = 0.f;
+  auto fetch = [&](int it) {
+    const int h = kvh * a.g + it / nq;
+    const int q0 = tile_of(it) * QT;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int row = min(q0 + st_row + c * ROWS_PER_PASS, a.Lq - 1);
+      const size_t off = (((size_t)b * a.Lq + row) * a.hq + h) * HS + st_col * 8;
+      qreg[c] = *(const u32x4*)((const __bf16*)a.q + off);
+      oreg[c] = *(const u32x4*)((const __bf16*)a.d_o + off);
+    }
+    if (tid < 2 * QT) {
+      const int row = min(q0 + (tid % QT), a.Lq - 1);
+      const size_t si = ((size_t)b * a.hq + h) * a.Lq + row;
+      if (tid < QT) {
+        const float lse = a.lse[si];
+        streg = (lse == -INFINITY) ? INFINITY : lse * kLog2e;
+      } else {
+        streg = a.delta[si];
+      }
+    }
+  };
+  const int tr_off = tr_lane_offset<TSTR>(lane);
+
+  if (nt > 0) fetch(0);
+  for (int it = 0; it < nt; ++it) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int row = st_row + c * ROWS_PER_PASS;
+      *(u32x4*)(q_rm + row * RSTR + st_col * 16) = qreg[c];
+      *(u32x4*)(q_tr + row * TSTR + st_col * 16) = qreg[c];
+      *(u32x4*)(o_rm + row * RSTR + st_col * 16) = oreg[c];
+      *(u32x4*)(o_tr + row * TSTR + st_col * 16) = oreg[c];
+    }
+    if (tid < QT) l2_s[tid] = streg;
+    else if (tid < 2 * QT) dl_s[tid - QT] = streg;
+    __syncthreads();
+    if (it + 1 < nt) fetch(it + 1);
+    const int q0 = tile_of(it) * QT;
+
+    // S = Q K^T and dP = dO V^T   (rows = queries, cols = keys)
+    f32x16 s, dp;
+    zero16(s);
+    zero16(dp);
+    const int row_off = l32 * RSTR + hl * 16;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const bf16x8 qa = *(const bf16x8*)(q_rm + row_off + ks * 32);
+      const bf16x8 oa = *(const bf16x8*)(o_rm + row_off + ks * 32);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vf[ks], dp, 0, 0, 0);
+    }
+
+    // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile
+    const int q1 = min(a.Lq, q0 + QT);
+    bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
+    if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
+    float p[16], ds[16];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x4 l2v = *(const f32x4*)(l2_s + 8 * j + 4 * hl);
+      const f32x4 dlv = *(const f32x4*)(dl_s + 8 * j + 4 * hl);
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const int i = 4 * j + tt;
+        float pi = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2v[tt]));
+        if (need_mask) {
+          const int qr = q0 + 8 * j + 4 * hl + tt;
+          const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
+          pi = vis ? pi : 0.f;
+        }
+        p[i] = pi;
+        ds[i] = pi * (dp[i] - dlv[tt]);
+      }
+    }
+    bf16x8 pf[2], dsf[2];
+    pack_b_operand(p, pf[0], pf[1]);
+    pack_b_operand(ds, dsf[0], dsf[1]);
+
+    // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 ot = tr_read<TSTR>(o_tr + tr_off + (16 * st) * TSTR + db * 64);
+        const bf16x8 qt = tr_read<TSTR>(q_tr + tr_off + (16 * st) * TSTR + db * 64);
+        dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf[st], dv[db], 0, 0, 0);
+        dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf[st], dk[db], 0, 0, 0);
+      }
+    __syncthreads();
+  }
+
+  if (key_ok) {
+    const size_t off = (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x4 k4 = {dk[db][4 * j] * a.scale, dk[db][4 * j + 1] * a.scale, dk[db][4 * j + 2] * a.scale,
+                    dk[db][4 * j + 3] * a.scale};
+        f32x4 v4 = {dv[db][4 * j], dv[db][4 * j + 1], dv[db][4 * j + 2], dv[db][4 * j + 3]};
+        f32x4* pk = (f32x4*)(a.dk + off + db * 32 + j * 8);
+        f32x4* pv = (f32x4*)(a.dv + off + db * 32 + j * 8);
+        if (a.accumulate) {
+          k4 += *pk;
+          v4 += *pv;
+        }
+        *pk = k4;
+        *pv = v4;
+      }
+  }
+}
+
+// fp32 accumulator -> bf16 / fp32 output, 4 elements per lane
+template <typename OutT>
+__global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT* dst, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const f32x4 v = __builtin_nontemporal_load((const f32x4*)src + i);
+  if constexpr (sizeof(OutT) == 4) {
+    __builtin_nontemporal_store(v, (f32x4*)dst + i);
+  } else {
+    u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+    __builtin_nontemporal_store(pk, (u32x2*)dst + i);
+  }
+}
+
+}  // namespace
+
+int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
+                     hipStream_t stream) {
+  const int64_t rows = (int64_t)bs * L * h;
+  const int tpr = hs / 8;
+  const int64_t grid = (rows * tpr + 255) / 256;
+  if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
+  if (hs == 128)
+    hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)grid), dim3(256), 0, stream, (const __bf16*)o,
+                       (const __bf16*)d_o, delta, bs, (int)L, h);
+  else
+    hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)grid), dim3(256), 0, stream, (const __bf16*)o,
+                       (const __bf16*)d_o, delta, bs, (int)L, h);
+  return launch_status();
+}
+
+int launch_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                          const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
+                          int hkv, int hs, float scale, int causal, const usp_posdesc& qpos, const usp_posdesc& kpos,
+                          int accumulate_dq, int accumulate_dkdv, hipStream_t stream) {
+  BwdArgs a;
+  a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.lse = lse; a.delta = delta;
+  a.dq = dq; a.dk = dk; a.dv = dv;
+  a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
+  a.Lq = (int)Lq; a.Lk = (int)Lk;
+  a.causal = causal;
+  a.accumulate = accumulate_dq;
+  a.scale = scale;
+  a.scale_log2 = scale * kLog2e;
+  a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
+  a.kpos = PosDesc32{(int)kpos.start0, (int)kpos.len0, (int)kpos.start1, (int)kpos.len1};
+  {
+    a.n_tiles = (a.Lq + 255) / 256;
+    const int64_t grid = (int64_t)a.n_tiles * hq * bs;
+    if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
+    if (hs == 128)
+      hipLaunchKernelGGL((bwd_dq_kernel<128>), dim3((unsigned)grid), dim3(512), 0, stream, a);
+    else
+      hipLaunchKernelGGL((bwd_dq_kernel<64>), dim3((unsigned)grid), dim3(512), 0, stream, a);
+    const int st = launch_status();
+    if (st != USP_OK) return st;
+  }
+  {
+    a.accumulate = accumulate_dkdv;
+    a.n_tiles = (a.Lk + 127) / 128;
+    const int64_t grid = (int64_t)a.n_tiles * hkv * bs;
+    if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
+    if (hs == 128)
+      hipLaunchKernelGGL((bwd_dkdv_kernel<128>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+    else
+      hipLaunchKernelGGL((bwd_dkdv_kernel<64>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+  }
+  return launch_status();
+}
+
+int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream) {
+  const size_t n4 = n / 4;
+  const size_t grid = (n4 + 255) / 256;
+  if (grid > 0x7fffffffull) return USP_ERR_UNSUPPORTED;
+  if (out_dtype == USP_FP32)
+    hipLaunchKernelGGL((bwd_convert_kernel<float>), dim3((unsigned)grid), dim3(256), 0, stream, src, (float*)dst, n4);
+  else
+    hipLaunchKernelGGL((bwd_convert_kernel<__bf16>), dim3((unsigned)grid), dim3(256), 0, stream, src, (__bf16*)dst, n4);
+  return launch_status();
+}
+
+}  // namespace usp

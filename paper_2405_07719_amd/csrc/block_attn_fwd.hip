@@ -23,36 +23,13 @@
 //     groups is a multiple of the 8 XCDs.
 #include <type_traits>
 
+#include "attn_device.h"
 #include "usp_internal.h"
 
 namespace usp {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-// Position descriptor narrowed to 32 bits (the host checks L < 2^31): fewer registers in the mask path.
-struct PosDesc32 { int start0, len0, start1, len1; };
-__device__ inline int pos_of(const PosDesc32& d, int i) { return i < d.len0 ? d.start0 + i : d.start1 + (i - d.len0); }
-__device__ inline int pos_min(const PosDesc32& d, int a, int b) {
-  int m = INT32_MAX;
-  if (a < d.len0) m = d.start0 + a;
-  if (b > d.len0) m = min(m, d.start1 + (max(a, d.len0) - d.len0));
-  return m;
-}
-__device__ inline int pos_max(const PosDesc32& d, int a, int b) {
-  int m = INT32_MIN;
-  if (a < d.len0) m = d.start0 + min(b, d.len0) - 1;
-  if (b > d.len0) m = max(m, d.start1 + (b - 1 - d.len0));
-  return m;
-}
+using namespace dev;
 
 struct AttnArgs {
   const void* q;
@@ -69,59 +46,10 @@ struct AttnArgs {
   PosDesc32 qpos, kpos;
 };
 
-// Visible key-tile ranges of a query tile: tiles [a0,a1) then [b0,b1) (b may be empty).
-struct TileRanges { int a0, a1, b0, b1; };
-
-template <int KT>
-__device__ inline TileRanges visible_tiles(const AttnArgs& a, int row_lo, int row_hi) {
-  TileRanges t;
-  if (!a.causal) {
-    t.a0 = 0; t.a1 = (a.Lk + KT - 1) / KT; t.b0 = t.b1 = t.a1;
-    return t;
-  }
-  const int64_t qmax = pos_max(a.qpos, row_lo, row_hi);
-  // keys of run 0 / run 1 with position <= qmax form a prefix of each run
-  int64_t c0 = qmax - a.kpos.start0 + 1; c0 = c0 < 0 ? 0 : (c0 > a.kpos.len0 ? a.kpos.len0 : c0);
-  int64_t c1 = qmax - a.kpos.start1 + 1; c1 = c1 < 0 ? 0 : (c1 > a.kpos.len1 ? a.kpos.len1 : c1);
-  t.a0 = 0;
-  t.a1 = (int)((c0 + KT - 1) / KT);
-  if (c1 > 0) {
-    t.b0 = (int)(a.kpos.len0 / KT);
-    t.b1 = (int)(((int64_t)a.kpos.len0 + c1 + KT - 1) / KT);
-    if (t.b0 < t.a1) t.b0 = t.a1;
-    if (t.b1 < t.b0) t.b1 = t.b0;
-  } else {
-    t.b0 = t.b1 = t.a1;
-  }
-  return t;
-}
-
-__device__ inline uint32_t pack_bf16(float lo, float hi) {
-  f32x2 f = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
-}
-
 // -------------------------------------------------------------------------------------------
 // bf16 MFMA kernel, software pipelined: while the softmax of key tile j runs on the vector ALU,
 // the matrix core already computes the scores of tile j+1, then P(j) V(j).
 // -------------------------------------------------------------------------------------------
-// Combine the two lane halves (lanes l and l ^ 32 hold the same query).  v_permlane32_swap(a, b) returns
-// {a.lower | b.lower, a.upper | b.upper}; with a = b = x that is x of the lower half and x of the upper
-// half, each broadcast to both halves.  (The two results are copied to scalars before the bit cast:
-// a bit cast applied directly to a vector element reads element 0.)
-__device__ inline float both_halves_max(float x) {
-  const uint32_t xi = __builtin_bit_cast(uint32_t, x);
-  const u32x2 r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
-  const uint32_t lo = r[0], hi = r[1];
-  return fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
-}
-__device__ inline float both_halves_sum(float x) {
-  const uint32_t xi = __builtin_bit_cast(uint32_t, x);
-  const u32x2 r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
-  const uint32_t lo = r[0], hi = r[1];
-  return __builtin_bit_cast(float, lo) + __builtin_bit_cast(float, hi);
-}
-
 template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
 __global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64), amdgpu_waves_per_eu(WPE, WPE)))
 void block_attn_fwd_mfma(const AttnArgs a) {
@@ -179,7 +107,7 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
   }
 
-  const TileRanges tr = visible_tiles<KT>(a, tile_row0, tile_row1);
+  const TileRanges tr = visible_key_tiles<KT>(a.causal, a.qpos, a.kpos, a.Lk, tile_row0, tile_row1);
   const int na = tr.a1 - tr.a0;
   const int nt = na + (tr.b1 - tr.b0);
   auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
@@ -461,7 +389,7 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < HS; ++e) { q[e] = qsrc[e]; o[e] = 0.f; }
   float m = -INFINITY, l = 0.f;
-  const TileRanges tr = visible_tiles<KT>(a, row0, row1);
+  const TileRanges tr = visible_key_tiles<KT>(a.causal, a.qpos, a.kpos, a.Lk, row0, row1);
   const float* kg = (const float*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
   const float* vg = (const float*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
   const size_t stride = (size_t)a.hkv * HS;

@@ -271,16 +271,171 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
   return USP_OK;
 }
 
+extern "C" int usp_attn_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
+                              void* stream) {
+  if (!o || !d_o || !delta) return USP_ERR_NULL;
+  if (bs < 1 || L < 1 || h < 1) return USP_ERR_SHAPE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if (L >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  return launch_bwd_delta(o, d_o, delta, bs, L, h, hs, (hipStream_t)stream);
+}
+
+extern "C" int usp_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                                  const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk,
+                                  int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
+                                  const usp_posdesc* kpos, int accumulate, void* stream) {
+  if (!q || !k || !v || !d_o || !lse || !delta || !dq || !dk || !dv) return USP_ERR_NULL;
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
+  if (hq % hkv) return USP_ERR_DEGREE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
+  if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  usp_posdesc qd = {0, Lq, 0, 0}, kd = {0, Lk, 0, 0};
+  if (causal) {
+    if (!qpos || !kpos) return USP_ERR_NULL;
+    if (!desc_ok(qpos, Lq) || !desc_ok(kpos, Lk)) return USP_ERR_SHAPE;
+    qd = *qpos;
+    kd = *kpos;
+  }
+  if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  return launch_block_attn_bwd(q, k, v, d_o, lse, delta, dq, dk, dv, bs, Lq, Lk, hq, hkv, hs, scale, causal ? 1 : 0,
+                               qd, kd, accumulate ? 1 : 0, accumulate ? 1 : 0, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Algorithm 1 backward.  Workspace plan:
+//   q_head, o_head, do_head : one rank's Q, O, dO in head layout (reused rank after rank); q_head later
+//                             holds the rank's converted dQ before its all-to-all;
+//   delta                   : one rank's D_i;
+//   k_head, v_head          : as in the forward; later hold the converted dK / dV blocks;
+//   dq_acc                  : one rank's fp32 dQ;  dk_acc, dv_acc : fp32, one per K/V block.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct BwdPlan {
+  size_t q_head, o_head, do_head, delta, k_head, v_head, dq_acc, dk_acc, dv_acc, total;
+  size_t kv_block_bytes, kv_acc_bytes;
+};
+
+BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
+  BwdPlan f;
+  const size_t es = dtype_size(p.dtype);
+  const size_t Lq = p.L / p.ring, hq = p.hc / p.ulysses, hkv = p.hk / p.ulysses;
+  const size_t q_elems = (size_t)p.bs * Lq * hq * p.hs, kv_elems = (size_t)p.bs * Lq * hkv * p.hs;
+  const size_t qb = up256(q_elems * es);
+  f.kv_block_bytes = up256(kv_elems * es);
+  f.kv_acc_bytes = up256(kv_elems * sizeof(float));
+  const size_t blocks = (size_t)p.ring * n_cols;
+  size_t off = 0;
+  f.q_head = off; off += qb;
+  f.o_head = off; off += qb;
+  f.do_head = off; off += qb;
+  f.delta = off; off += up256((size_t)p.bs * hq * Lq * sizeof(float));
+  f.k_head = off; off += f.kv_block_bytes * blocks;
+  f.v_head = off; off += f.kv_block_bytes * blocks;
+  f.dq_acc = off; off += up256(q_elems * sizeof(float));
+  f.dk_acc = off; off += f.kv_acc_bytes * blocks;
+  f.dv_acc = off; off += f.kv_acc_bytes * blocks;
+  f.total = off;
+  return f;
+}
+
+}  // namespace
+
 extern "C" size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks) {
-  (void)p;
-  (void)n_ranks;
-  return 0;
+  if (usp_validate(p) != USP_OK || n_ranks < 1 || p->dtype != USP_BF16) return 0;
+  const int cols = n_ranks == 1 ? 1 : p->ulysses;
+  return plan_bwd(*p, cols).total;
 }
 
 extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,
                             const float* lse, const void* d_o, void* dq, void* dk, void* dv, int rank_begin,
-                            int rank_end, void* workspace, size_t workspace_bytes, void* stream) {
-  (void)p; (void)q; (void)k; (void)v; (void)o; (void)lse; (void)d_o; (void)dq; (void)dk; (void)dv;
-  (void)rank_begin; (void)rank_end; (void)workspace; (void)workspace_bytes; (void)stream;
-  return USP_ERR_UNSUPPORTED;
+                            int rank_end, void* workspace, size_t workspace_bytes, void* stream_) {
+  int st = usp_validate(p);
+  if (st != USP_OK) return st;
+  if (p->dtype != USP_BF16) return USP_ERR_DTYPE;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return USP_ERR_NULL;
+  const int U = p->ulysses, R = p->ring, N = U * R;
+  if (rank_begin < 0 || rank_end > N || rank_begin >= rank_end) return USP_ERR_UNSUPPORTED;
+  int c0, c1;
+  column_range(*p, rank_begin, rank_end, &c0, &c1);
+  const int n_cols = c1 - c0;
+  const BwdPlan f = plan_bwd(*p, n_cols);
+  if (!workspace || workspace_bytes < f.total) return USP_ERR_WORKSPACE;
+  if ((uintptr_t)workspace & 255) return USP_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+  char* ws = (char*)workspace;
+  const int64_t Lq = p->L / R;
+  const int hq = p->hc / U, hkv = p->hk / U;
+  const float scale = p->scale == 0.0f ? 1.0f / sqrtf((float)p->hs) : p->scale;
+  const size_t q_elems = (size_t)p->bs * Lq * hq * p->hs, kv_elems = (size_t)p->bs * Lq * hkv * p->hs;
+  auto slot = [&](int r, int u) { return (size_t)r * n_cols + (u - c0); };
+
+  for (int r = 0; r < R; ++r)
+    for (int u = c0; u < c1; ++u) {
+      const int rank = r * U + u;
+      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, k, ws + f.k_head + slot(r, u) * f.kv_block_bytes, rank, rank + 1,
+                             rank, stream);
+      if (st != USP_OK) return st;
+      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, v, ws + f.v_head + slot(r, u) * f.kv_block_bytes, rank, rank + 1,
+                             rank, stream);
+      if (st != USP_OK) return st;
+    }
+
+  // first contribution to a K/V block overwrites its accumulator, later ones add
+  bool touched[USP_MAX_MERGE_PARTS] = {false};
+  if ((size_t)R * n_cols > USP_MAX_MERGE_PARTS) return USP_ERR_UNSUPPORTED;
+
+  for (int rank = rank_begin; rank < rank_end; ++rank) {
+    const int r = rank / U, u = rank % U;
+    const void* srcs[3] = {q, o, d_o};
+    const size_t dsts[3] = {f.q_head, f.o_head, f.do_head};
+    for (int t = 0; t < 3; ++t) {
+      st = launch_layout_a2a(*p, p->hc, USP_SEQ_TO_HEAD, srcs[t], ws + dsts[t], rank, rank + 1, rank, stream);
+      if (st != USP_OK) return st;
+    }
+    float* delta = (float*)(ws + f.delta);
+    st = launch_bwd_delta(ws + f.o_head, ws + f.do_head, delta, p->bs, Lq, hq, p->hs, stream);
+    if (st != USP_OK) return st;
+    usp_posdesc qd;
+    usp_local_positions(p, r, u, nullptr, &qd);
+    const float* lse_rank = lse + (size_t)rank * p->bs * hq * Lq;
+    for (int i = 0; i < R; ++i) {
+      const int s = ((r - i) % R + R) % R;
+      usp_posdesc kd;
+      usp_local_positions(p, s, u, nullptr, &kd);
+      const size_t sl = slot(s, u);
+      // dQ adds after the first ring step of this rank; dK/dV add after the first rank that touched the block
+      st = launch_block_attn_bwd(ws + f.q_head, ws + f.k_head + sl * f.kv_block_bytes,
+                                 ws + f.v_head + sl * f.kv_block_bytes, ws + f.do_head, lse_rank, delta,
+                                 (float*)(ws + f.dq_acc), (float*)(ws + f.dk_acc + sl * f.kv_acc_bytes),
+                                 (float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), p->bs, Lq, Lq, hq, hkv, p->hs, scale,
+                                 p->causal ? 1 : 0, qd, kd, i > 0 ? 1 : 0, touched[sl] ? 1 : 0, stream);
+      if (st != USP_OK) return st;
+      touched[sl] = true;
+    }
+    // dQ of this rank: convert into the (now free) q_head region and send it back to the sequence layout
+    st = launch_bwd_convert((const float*)(ws + f.dq_acc), ws + f.q_head, q_elems, p->dtype, stream);
+    if (st != USP_OK) return st;
+    st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.q_head, dq, rank, rank + 1, rank, stream);
+    if (st != USP_OK) return st;
+  }
+
+  // dK, dV of every block the range touched (all ring rows of the columns in range)
+  for (int r = 0; r < R; ++r)
+    for (int u = c0; u < c1; ++u) {
+      const int rank = r * U + u;
+      const size_t sl = slot(r, u);
+      char* kdst = ws + f.k_head + sl * f.kv_block_bytes;
+      char* vdst = ws + f.v_head + sl * f.kv_block_bytes;
+      st = launch_bwd_convert((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), kdst, kv_elems, p->dtype, stream);
+      if (st != USP_OK) return st;
+      st = launch_bwd_convert((const float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), vdst, kv_elems, p->dtype, stream);
+      if (st != USP_OK) return st;
+      st = launch_layout_a2a(*p, p->hk, USP_HEAD_TO_SEQ, kdst, dk, rank, rank + 1, rank, stream);
+      if (st != USP_OK) return st;
+      st = launch_layout_a2a(*p, p->hk, USP_HEAD_TO_SEQ, vdst, dv, rank, rank + 1, rank, stream);
+      if (st != USP_OK) return st;
+    }
+  return USP_OK;
 }

@@ -51,4 +51,12 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
                           int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
                           const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream);
 
+int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
+                     hipStream_t stream);
+int launch_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                          const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
+                          int hkv, int hs, float scale, int causal, const usp_posdesc& qpos, const usp_posdesc& kpos,
+                          int accumulate_dq, int accumulate_dkdv, hipStream_t stream);
+int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream);
+
 }  // namespace usp
