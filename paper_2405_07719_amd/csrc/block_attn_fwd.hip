@@ -162,12 +162,13 @@ void block_attn_fwd_mfma(const AttnArgs a) {
 
   // ---- S^T = K Q^T for the tile in K buffer kb_ (rows = keys, cols = queries)
   auto qk = [&](const char* kb_, f32x16 (&sacc)[NQB][KB]) {
+    const char* krow = kb_ + l32 * KSTR + hl * 16;
+    // k-step outermost: consecutive MFMAs go to different accumulators (no back-to-back dependence)
 #pragma unroll
-    for (int kbk = 0; kbk < KB; ++kbk) {
-      const char* krow = kb_ + (kbk * 32 + l32) * KSTR + hl * 16;
+    for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
-        const bf16x8 kf = *(const bf16x8*)(krow + ks * 32);
+      for (int kbk = 0; kbk < KB; ++kbk) {
+        const bf16x8 kf = *(const bf16x8*)(krow + kbk * 32 * KSTR + ks * 32);
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
           if (ks == 0) {
