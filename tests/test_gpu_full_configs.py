@@ -1,0 +1,113 @@
+"""GPU parity at the FULL sizes of the benchmark configurations, one virtual rank each, in the launch
+configuration bench.py times: sampled rows against the oracle, plus properties that hold at any size.
+
+Config 2: Ulysses-only rank   (L=32768, U=8, R=1)      Config 3: ring-only rank (L=32768, U=1, R=8)
+Config 4: hybrid 208K rank    (L=212992, U=8, R=2)     Config 5: training rank  (L=65536, U=2, R=4, fwd+bwd)
+All: bs=1, 32 Q / 8 KV heads, head size 128, bf16, causal, zigzag split.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import usp_oracle as orc
+from paper_2405_07719_amd import inputs
+from tests import usp_testlib as tl
+
+pytestmark = pytest.mark.gpu
+O_TOL, LSE_TOL, GRAD_TOL = 2e-2, 1e-3, 5e-2
+
+
+def _check_forward_rows(case, rows):
+    pos = case.block_pos[rows]
+    allpos = np.arange(case.L)
+    qv = case.values(inputs.TENSOR_Q, pos, case.q_heads)
+    kv = case.values(inputs.TENSOR_K, allpos, case.kv_heads)
+    vv = case.values(inputs.TENSOR_V, allpos, case.kv_heads)
+    ref_o, ref_l = orc.attention_rows(qv, pos, kv, vv, True)
+    got_o = case.seq_rows(case.o, rows, slice(case.u * case.hq, (case.u + 1) * case.hq))
+    got_l = case.lse[case.rank].cpu().double().numpy()[:, :, rows]
+    assert tl.max_abs(got_l, ref_l) <= LSE_TOL
+    assert tl.max_abs(got_o, ref_o) <= O_TOL
+    return kv, vv
+
+
+@pytest.mark.parametrize("name,L,U,R,rank,samples", [
+    ("config2_ulysses8", 32768, 8, 1, 0, 256),
+    ("config2_ulysses8_last_rank", 32768, 8, 1, 7, 64),
+    ("config3_ring8_rank0", 32768, 1, 8, 0, 256),
+    ("config3_ring8_rank7", 32768, 1, 8, 7, 64),
+    ("config4_hybrid208k", 212992, 8, 2, 0, 256),
+])
+def test_full_size_forward_one_rank(usp, name, L, U, R, rank, samples):
+    case = tl.OneRankCase(usp, 1000 + len(name), 1, L, 32, 8, 128, U, R, rank)
+    case.forward()
+    rows = case.sample_rows(np.random.default_rng(3), samples)
+    _check_forward_rows(case, rows)
+    # properties over ALL rows of the rank: LSE finite (every query sees itself), bounded by ln(#visible keys) +
+    # max score bound, O rows are convex combinations of V rows: |O| <= max|V|
+    lse = case.lse[case.rank]
+    assert torch.isfinite(lse).all()
+    o_slice = case.o[case.r * U:(case.r + 1) * U, :, :, case.u * case.hq:(case.u + 1) * case.hq]
+    vmax = max(float(case.v[:, :, :, case.kv_heads[0]:case.kv_heads[-1] + 1].abs().max()), 1e-6)
+    assert float(o_slice.abs().max()) <= vmax * (1 + 2 ** -7)
+    # the first global position sees only itself: O = V[0] exactly (bf16 of a bf16 value), LSE = scale * q.k
+    if 0 in case.block_pos[:1]:
+        o0 = case.seq_rows(case.o, [0], slice(case.u * case.hq, (case.u + 1) * case.hq))
+        v0 = case.values(inputs.TENSOR_V, np.array([0]), case.kv_heads)
+        g = case.hq // case.hkv
+        for h in range(case.hq):
+            assert np.array_equal(o0[0, 0, h], v0[0, 0, h // g])
+
+
+def test_full_size_training_rank_config5(usp):
+    L, U, R, rank = 65536, 2, 4, 0
+    case = tl.OneRankCase(usp, 1005, 1, L, 32, 8, 128, U, R, rank, with_do=True)
+    case.forward()
+    rng = np.random.default_rng(5)
+    rows = case.sample_rows(rng, 48)
+    kv, vv = _check_forward_rows(case, rows)
+
+    p = case.p
+    dq = torch.zeros_like(case.q)
+    dk = torch.zeros_like(case.k)
+    dv = torch.zeros_like(case.v)
+    ws = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, 1), dtype=torch.uint8, device="cuda")
+    usp.usp_attn_bwd(p, case.q, case.k, case.v, case.o, case.lse, case.d_o, dq, dk, dv, rank, rank + 1, ws)
+    torch.cuda.synchronize()
+    qs = slice(case.u * case.hq, (case.u + 1) * case.hq)
+    ks = slice(case.u * case.hkv, (case.u + 1) * case.hkv)
+    allpos = np.arange(L)
+
+    # dQ on sampled rows: each row's gradient needs only that row's attention over all keys
+    pos = case.block_pos[rows]
+    qv = case.values(inputs.TENSOR_Q, pos, case.q_heads)
+    gv = case.values(inputs.TENSOR_DO, pos, case.q_heads)
+    ref_dq, _, _ = orc.attention_backward(qv, kv, vv, gv, True, None, pos, allpos)
+    assert tl.max_abs(case.seq_rows(dq, rows, qs), ref_dq) <= GRAD_TOL
+
+    # dK, dV of the LAST 128 key positions: only queries at or after them contribute, all of which are rows of
+    # this ring rank (its second zigzag chunk is the end of the sequence), so the rank's contribution is complete
+    last = np.arange(L - 128, L)
+    ql = case.values(inputs.TENSOR_Q, last, case.q_heads)
+    gl = case.values(inputs.TENSOR_DO, last, case.q_heads)
+    _, ref_dk, ref_dv = orc.attention_backward(ql, kv, vv, gl, True, None, last, allpos)
+    # those key positions sit at the end of ring block 0's second chunk = last rows of the shard of rank (0, U-1)
+    got_dk = tl.to_f64(dk[U - 1, :, -128:, ks, :])
+    got_dv = tl.to_f64(dv[U - 1, :, -128:, ks, :])
+    assert tl.max_abs(got_dk, ref_dk[:, -128:]) <= GRAD_TOL
+    assert tl.max_abs(got_dv, ref_dv[:, -128:]) <= GRAD_TOL
+
+    # properties over ALL keys (every ring block of this Ulysses column), exact in real arithmetic:
+    #   sum_j dV_j = sum over the rank's rows and the group's heads of dO_i   (softmax rows sum to one)
+    #   sum_j dK_j = 0                                                        (rows of dS sum to zero)
+    g = case.hq // case.hkv
+    dv_sum = dv[:, :, :, ks, :].double().sum(dim=(0, 2)).cpu().numpy()                    # [bs, hkv, hs]
+    do_rows = case.d_o[case.r * U:(case.r + 1) * U, :, :, qs, :].double().sum(dim=(0, 2)).cpu().numpy()   # [bs, hq, hs]
+    do_sum = do_rows.reshape(1, case.hkv, g, case.hs).sum(axis=2)
+    n_terms = case.Lq * g
+    assert np.max(np.abs(dv_sum - do_sum)) <= 0.02 * np.sqrt(n_terms)       # bf16 rounding of ~65k outputs, random sign
+    dk_sum = dk[:, :, :, ks, :].double().sum(dim=(0, 2)).cpu().numpy()
+    dk_abs = float(dk[:, :, :, ks, :].double().abs().sum(dim=(0, 2)).max())
+    assert np.max(np.abs(dk_sum)) <= 2e-3 * dk_abs
+    # nothing outside this rank's slices was written
+    assert float(dq[:, :, :, case.hq:].abs().max()) == 0.0 and float(dk[:, :, :, case.hkv:].abs().max()) == 0.0
