@@ -28,6 +28,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
+# rocprofv3 --pmc FETCH_SIZE (x2, the factor a plain copy of known size gives) + WRITE_SIZE, KiB -> bytes, per
+# launch of the block-attention kernel
+# (FETCH_SIZE 217999 KiB; copy calibration: a 524288 KiB copy reads FETCH_SIZE 262158, WRITE_SIZE 524288)
+MEASURED_TRAFFIC_BYTES = {"ulysses8_L32768": round((217999 * (524288 / 262158) + 36352 * (524288 / 524288)) * 1024.0)}
+
 WORKLOADS = {
     # name: (bs, L, hc, hk, hs, U, R, timed rank)
     "ulysses8_L32768": (1, 32768, 32, 8, 128, 8, 1, 0),
@@ -63,6 +68,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-extras", action="store_true", help="skip the layout / merge bandwidth legs")
     ap.add_argument("--cpu-rows", type=int, default=16384, help="sampled query rows per head for the oracle leg")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward (usp_attn_bwd) timing leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 512 MiB device copies: the known-size kernel that scales FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (ring and Ulysses ranks are simulated locally); "
@@ -146,9 +154,14 @@ def main():
         attn_only()
     attn_ms = event_ms(attn_only, args.steps)            # all R launches of one step
     attn_tflops = flop / (attn_ms * 1e-3) / 1e12
+    # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload, each scaled by what
+    # the same counter reads for a plain 512 MiB copy (FETCH_SIZE reads half the bytes, WRITE_SIZE all of them):
+    # see profiles/traffic_pmc_ulysses8_L32768.md.  Only known for the default workload.
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
     roofline = {"bound": "mfma", "kernel": "block_attn_fwd_mfma", "achieved": round(attn_tflops, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                "launches_per_step": R, "avg_launch_ms": round(attn_ms / R, 4), "traffic": None}
+                "launches_per_step": R, "avg_launch_ms": round(attn_ms / R, 4), "traffic": traffic,
+                "algorithmic_bytes": float(2 * qh.numel() * 2 + 2 * kh.numel() * 2 + bs * hq * Lq * 4)}
 
     out = {
         "metric": "one-rank USP attention TFLOP/s (bf16 causal fwd) + % MFMA peak; a2a GB/s",
@@ -198,6 +211,29 @@ def main():
                                "shape": f"{mp} fp32 partials [1,{mL},{mh},{hs}] -> bf16 (ring-only rank)"}
         del parts, lparts
         out["hbm_kernels"] = extras
+
+    # ---- backward of the same rank (usp_attn_bwd): 2.5 x the forward flop by the usual accounting
+    if not args.no_backward:
+        d_o = seq_buffer(inputs.TENSOR_DO, hc, q_heads)
+        dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+        ws_b = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, 1), dtype=torch.uint8, device="cuda")
+
+        def bwd():
+            usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, rank, rank + 1, ws_b)
+        bwd()
+        bms = event_ms(bwd, max(3, args.steps // 4))
+        out["backward"] = {"ms_per_step": round(bms, 4), "value": round(2.5 * flop / (bms * 1e-3) / 1e12, 2),
+                           "unit": "TFLOP/s", "frac_of_mfma_peak": round(2.5 * flop / (bms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                           "note": "whole usp_attn_bwd of the timed rank (all-to-alls, delta, dQ and dK/dV kernels, conversion)"}
+        del d_o, dq, dk, dv, ws_b
+
+    if args.copy_calibration:
+        src = torch.empty(512 * 2**20, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- CPU oracle on a bounded sample of the same workload (rows of the timed rank), with parity
     if not args.no_cpu_baseline:
