@@ -253,6 +253,9 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     // ---- global prefetch: K two tiles ahead, V one tile ahead
     if (has2) fetch(kg, it + 2, kreg);
     if (has1) fetch(vg, it + 1, vreg);
+    // keep the loads up here: left alone, the scheduler sinks them to just before the LDS stores below to
+    // save registers, and every step then waits out a full global-memory latency
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- main block: scores of the next tile on the matrix core, softmax of this tile on the vector ALU
     if (has1) qk(kbuf + ((it + 1) & 1) * KBYTES, s_next);
@@ -495,13 +498,9 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
     return o_dtype == USP_FP32 ? launch_mfma<128, NQB, NW, KT, WPE, float>(a, stream)           \
                                : launch_mfma<128, NQB, NW, KT, WPE, __bf16>(a, stream);
   if (hs == 128) {
-    USP_VARIANT(1, 2, 4, 64, 1)
-    USP_VARIANT(2, 1, 4, 64, 1)
-    USP_VARIANT(3, 1, 4, 64, 2)
-    USP_VARIANT(4, 1, 4, 32, 2)
-    USP_VARIANT(5, 1, 8, 32, 2)
-    USP_VARIANT(6, 1, 8, 128, 2)
-    USP_VARIANT(7, 1, 4, 32, 3)
+    USP_VARIANT(2, 1, 4, 64, 1)   // 128-row tiles, one wave per SIMD
+    USP_VARIANT(3, 1, 4, 64, 2)   // 128-row tiles, two workgroups per CU
+    USP_VARIANT(5, 1, 8, 32, 2)   // 32-key tiles
     return o_dtype == USP_FP32 ? launch_mfma<128, 1, 8, 64, 2, float>(a, stream)
                                : launch_mfma<128, 1, 8, 64, 2, __bf16>(a, stream);
   }
