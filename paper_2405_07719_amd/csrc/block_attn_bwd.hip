@@ -6,12 +6,12 @@
 //   dQ_i = scale sum_j dS_ij k_j,     dK_j = scale sum_i dS_ij q_i.
 // P and dS are exact per element, so the contributions of different K/V blocks simply add.
 //
-// Two deterministic kernels (no atomics), both on v_mfma_f32_32x32x16_bf16 with fp32 accumulation:
+// Two kernels, both on v_mfma_f32_32x32x16_bf16 with fp32 accumulation:
 //   dq_kernel    a workgroup owns 256 query rows, walks the visible key tiles:  S^T = K Q^T, dP^T = V dO^T
-//                (lane = query, so L_i and D_i are per-lane scalars), dQ^T += K^T dS^T.
-//   dkdv_kernel  a workgroup owns 128 keys of one KV head, walks the query heads of the group and the
-//                visible query tiles:  S = Q K^T, dP = dO V^T (lane = key; L_i, D_i read from LDS),
-//                dV^T += dO^T P, dK^T += Q^T dS.  The sum over the group's query heads stays in registers.
+//                (lane = query, so L_i and D_i are per-lane scalars), dQ^T += K^T dS^T.  Deterministic.
+//   dkdv_kernel  a workgroup owns 128 keys of one KV head and one query head, walks the visible query
+//                tiles:  S = Q K^T, dP = dO V^T (lane = key; L_i, D_i read from LDS), dV^T += dO^T P,
+//                dK^T += Q^T dS; the query heads of a group are summed with fp32 atomic adds.
 // In both, the accumulator layout of the first product is the B-operand layout of the second, and the
 // transposed A operands come from LDS transpose reads (tiles are kept in LDS twice: rows padded for 16 B
 // row reads, and rows padded for the transpose read).
@@ -242,75 +242,74 @@ void bwd_dq_kernel(const BwdArgs a) {
 }
 
 // -------------------------------------------------------------------------------------------------
-// dK, dV
+// dK, dV.  A workgroup owns 128 keys of one KV head and ONE query head of its group; eight waves in two
+// roles share every staged query tile: waves 0-3 ("dV waves", 32 keys each) compute S, P and dV^T += dO^T P,
+// waves 4-7 ("dK waves", the same 32 keys) compute S, dP, dS and dK^T += Q^T dS.  The score product is
+// done twice, but each wave keeps one 64-register accumulator, so two waves fit a SIMD and the two roles'
+// matrix-core and vector work interleave.  The query heads of a group (and nothing else) meet in the fp32
+// outputs through atomic adds: at most hq/hkv addends per element, the only non-deterministic rounding here.
 // -------------------------------------------------------------------------------------------------
 template <int HS>
-__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(1, 1)))
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void bwd_dkdv_kernel(const BwdArgs a) {
-  constexpr int NT = 256, BN = 128, QT = 32;
+  constexpr int NT = 512, BN = 128, QT = 32;
   constexpr int KSTEPS = HS / 16, DB = HS / 32;
   constexpr int RSTR = HS * 2 + 16;
   constexpr int TSTR = (HS == 128) ? 320 : 192;
   constexpr int CPR = HS / 8;
-  constexpr int CPT = QT * CPR / NT;                 // chunks per thread per tensor
-  static_assert(QT * CPR % NT == 0 && CPT >= 1, "query tile must split evenly over the workgroup");
-  __shared__ __attribute__((aligned(16))) char q_rm[QT * RSTR];
-  __shared__ __attribute__((aligned(16))) char q_tr[QT * TSTR];
-  __shared__ __attribute__((aligned(16))) char o_rm[QT * RSTR];
-  __shared__ __attribute__((aligned(16))) char o_tr[QT * TSTR];
-  __shared__ __attribute__((aligned(16))) float l2_s[QT];
-  __shared__ __attribute__((aligned(16))) float dl_s[QT];
+  constexpr int STAGE = 2 * QT * RSTR + 2 * QT * TSTR + 2 * QT * 4;   // Q rm, dO rm, Q tr, dO tr, l2, delta
+  static_assert(QT * CPR <= NT, "one chunk per thread and tensor");
+  __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hl = lane >> 5;
+  const bool dk_role = wave >= 4;
+  const int kw = wave & 3;
   int w = blockIdx.x;
   const int n_groups = a.bs * a.hkv;
-  const int group = w % n_groups;
-  const int ktile = w / n_groups;          // ascending local index: keys seen by the most queries first
+  const int group = w % n_groups; w /= n_groups;
+  const int hg = w % a.g;
+  const int ktile = w / a.g;               // ascending local index: keys seen by the most queries first
   const int b = group / a.hkv, kvh = group % a.hkv;
+  const int h = kvh * a.g + hg;
   const int tile_key0 = ktile * BN, tile_key1 = min(a.Lk, tile_key0 + BN);
-  const int wave_key0 = tile_key0 + wave * 32;
+  const int wave_key0 = tile_key0 + kw * 32;
   const int key = wave_key0 + l32;
   const int kk = min(key, a.Lk - 1);
   const int kp = a.causal ? pos_of(a.kpos, kk) : 0;
   const bool key_ok = key < a.Lk;
 
+  // B operands of S = Q K^T (both roles) and dP = dO V^T (dK waves): lane = key l32, dims 16 ks + 8 hl ..
   bf16x8 kf[KSTEPS], vf[KSTEPS];
   {
     const size_t off = (((size_t)b * a.Lk + kk) * a.hkv + kvh) * HS + 8 * hl;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       kf[ks] = *(const bf16x8*)((const __bf16*)a.k + off + 16 * ks);
-      vf[ks] = *(const bf16x8*)((const __bf16*)a.v + off + 16 * ks);
+      if (dk_role) vf[ks] = *(const bf16x8*)((const __bf16*)a.v + off + 16 * ks);
     }
   }
-  f32x16 dk[DB], dv[DB];
+  f32x16 acc[DB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db) {
-    zero16(dk[db]);
-    zero16(dv[db]);
-  }
+  for (int db = 0; db < DB; ++db) zero16(acc[db]);
 
   const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, a.kpos, a.Lq, tile_key0, tile_key1);
-  const int na = tr.a1 - tr.a0, nq = na + (tr.b1 - tr.b0);
-  const int nt = nq * a.g;                  // (query head of the group, visible query tile) pairs
-  auto tile_of = [&](int it) { const int j = it % nq; return j < na ? tr.a0 + j : tr.b0 + (j - na); };
+  const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
+  auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
   const bool wave_live = wave_key0 < a.Lk;
   const int wave_kmax = (a.causal && wave_live) ? pos_max(a.kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
 
   const int st_row = tid / CPR, st_col = tid % CPR;
-  constexpr int ROWS_PER_PASS = NT / CPR;
-  u32x4 qreg[CPT], oreg[CPT];
+  const bool stager = st_row < QT;
+  u32x4 qreg, oreg;
   float streg = 0.f;
   auto fetch = [&](int it) {
-    const int h = kvh * a.g + it / nq;
     const int q0 = tile_of(it) * QT;
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int row = min(q0 + st_row + c * ROWS_PER_PASS, a.Lq - 1);
+    if (stager) {
+      const int row = min(q0 + st_row, a.Lq - 1);
       const size_t off = (((size_t)b * a.Lq + row) * a.hq + h) * HS + st_col * 8;
-      qreg[c] = *(const u32x4*)((const __bf16*)a.q + off);
-      oreg[c] = *(const u32x4*)((const __bf16*)a.d_o + off);
+      qreg = *(const u32x4*)((const __bf16*)a.q + off);
+      oreg = *(const u32x4*)((const __bf16*)a.d_o + off);
     }
     if (tid < 2 * QT) {
       const int row = min(q0 + (tid % QT), a.Lq - 1);
@@ -323,46 +322,61 @@ void bwd_dkdv_kernel(const BwdArgs a) {
       }
     }
   };
-  const int tr_off = tr_lane_offset<TSTR>(lane);
-
-  if (nt > 0) fetch(0);
-  for (int it = 0; it < nt; ++it) {
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int row = st_row + c * ROWS_PER_PASS;
-      *(u32x4*)(q_rm + row * RSTR + st_col * 16) = qreg[c];
-      *(u32x4*)(q_tr + row * TSTR + st_col * 16) = qreg[c];
-      *(u32x4*)(o_rm + row * RSTR + st_col * 16) = oreg[c];
-      *(u32x4*)(o_tr + row * TSTR + st_col * 16) = oreg[c];
+  auto stash = [&](int buf) {
+    char* base = lds + buf * STAGE;
+    if (stager) {
+      *(u32x4*)(base + st_row * RSTR + st_col * 16) = qreg;
+      *(u32x4*)(base + QT * RSTR + st_row * RSTR + st_col * 16) = oreg;
+      *(u32x4*)(base + 2 * QT * RSTR + st_row * TSTR + st_col * 16) = qreg;
+      *(u32x4*)(base + 2 * QT * RSTR + QT * TSTR + st_row * TSTR + st_col * 16) = oreg;
     }
-    if (tid < QT) l2_s[tid] = streg;
-    else if (tid < 2 * QT) dl_s[tid - QT] = streg;
-    __syncthreads();
-    if (it + 1 < nt) fetch(it + 1);
+    if (tid < 2 * QT) *(float*)(base + 2 * QT * RSTR + 2 * QT * TSTR + tid * 4) = streg;
+  };
+  const int tr_off = tr_lane_offset<TSTR>(lane);
+  const int row_off = l32 * RSTR + hl * 16;
+
+  if (nt > 0) {
+    fetch(0);
+    stash(0);
+  }
+  __syncthreads();
+  for (int it = 0; it < nt; ++it) {
+    const bool more = it + 1 < nt;
+    if (more) fetch(it + 1);
+    __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
+    const char* base = lds + (it & 1) * STAGE;
+    const char* q_rm = base;
+    const char* o_rm = base + QT * RSTR;
+    const char* q_tr = base + 2 * QT * RSTR;
+    const char* o_tr = q_tr + QT * TSTR;
+    const float* l2_s = (const float*)(o_tr + QT * TSTR);
+    const float* dl_s = l2_s + QT;
     const int q0 = tile_of(it) * QT;
 
-    // S = Q K^T and dP = dO V^T   (rows = queries, cols = keys)
+    // S = Q K^T (and dP = dO V^T): rows = queries, cols = keys
     f32x16 s, dp;
     zero16(s);
     zero16(dp);
-    const int row_off = l32 * RSTR + hl * 16;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       const bf16x8 qa = *(const bf16x8*)(q_rm + row_off + ks * 32);
-      const bf16x8 oa = *(const bf16x8*)(o_rm + row_off + ks * 32);
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vf[ks], dp, 0, 0, 0);
+      if (dk_role) {
+        const bf16x8 oa = *(const bf16x8*)(o_rm + row_off + ks * 32);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vf[ks], dp, 0, 0, 0);
+      }
     }
 
     // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile
     const int q1 = min(a.Lq, q0 + QT);
     bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
     if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
-    float p[16], ds[16];
+    float x[16];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const f32x4 l2v = *(const f32x4*)(l2_s + 8 * j + 4 * hl);
-      const f32x4 dlv = *(const f32x4*)(dl_s + 8 * j + 4 * hl);
+      f32x4 dlv = {0.f, 0.f, 0.f, 0.f};
+      if (dk_role) dlv = *(const f32x4*)(dl_s + 8 * j + 4 * hl);
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) {
         const int i = 4 * j + tt;
@@ -372,46 +386,41 @@ void bwd_dkdv_kernel(const BwdArgs a) {
           const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
           pi = vis ? pi : 0.f;
         }
-        p[i] = pi;
-        ds[i] = pi * (dp[i] - dlv[tt]);
+        x[i] = dk_role ? pi * (dp[i] - dlv[tt]) : pi;    // dS for the dK waves, P for the dV waves
       }
     }
-    bf16x8 pf[2], dsf[2];
-    pack_b_operand(p, pf[0], pf[1]);
-    pack_b_operand(ds, dsf[0], dsf[1]);
+    bf16x8 xf[2];
+    pack_b_operand(x, xf[0], xf[1]);
 
-    // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
+    // dV^T += dO^T P   or   dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
+    const char* a_tr = (dk_role ? q_tr : o_tr) + tr_off;
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const bf16x8 ot = tr_read<TSTR>(o_tr + tr_off + (16 * st) * TSTR + db * 64);
-        const bf16x8 qt = tr_read<TSTR>(q_tr + tr_off + (16 * st) * TSTR + db * 64);
-        dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf[st], dv[db], 0, 0, 0);
-        dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf[st], dk[db], 0, 0, 0);
+        const bf16x8 at = tr_read<TSTR>(a_tr + (16 * st) * TSTR + db * 64);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at, xf[st], acc[db], 0, 0, 0);
       }
+    if (more) stash((it + 1) & 1);
     __syncthreads();
   }
 
   if (key_ok) {
     const size_t off = (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
+    float* dst = (dk_role ? a.dk : a.dv) + off;
+    const float sc = dk_role ? a.scale : 1.0f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4 k4 = {dk[db][4 * j] * a.scale, dk[db][4 * j + 1] * a.scale, dk[db][4 * j + 2] * a.scale,
-                    dk[db][4 * j + 3] * a.scale};
-        f32x4 v4 = {dv[db][4 * j], dv[db][4 * j + 1], dv[db][4 * j + 2], dv[db][4 * j + 3]};
-        f32x4* pk = (f32x4*)(a.dk + off + db * 32 + j * 8);
-        f32x4* pv = (f32x4*)(a.dv + off + db * 32 + j * 8);
-        if (a.accumulate) {
-          k4 += *pk;
-          v4 += *pv;
-        }
-        *pk = k4;
-        *pv = v4;
-      }
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) atomicAdd(dst + db * 32 + j * 8 + tt, acc[db][4 * j + tt] * sc);
   }
+}
+
+__global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* dst, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n4) dst[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
 // fp32 accumulator -> bf16 / fp32 output, 4 elements per lane
@@ -472,14 +481,22 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
     if (st != USP_OK) return st;
   }
   {
-    a.accumulate = accumulate_dkdv;
+    // dK / dV meet through atomic adds: start from zero unless the caller accumulates
+    if (!accumulate_dkdv) {
+      const size_t n4 = (size_t)bs * Lk * hkv * hs / 4;
+      const size_t zg = (n4 + 255) / 256;
+      if (zg > 0x7fffffffull) return USP_ERR_UNSUPPORTED;
+      hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dk, n4);
+      hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dv, n4);
+    }
+    a.accumulate = 1;
     a.n_tiles = (a.Lk + 127) / 128;
-    const int64_t grid = (int64_t)a.n_tiles * hkv * bs;
+    const int64_t grid = (int64_t)a.n_tiles * hq * bs;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
     if (hs == 128)
-      hipLaunchKernelGGL((bwd_dkdv_kernel<128>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+      hipLaunchKernelGGL((bwd_dkdv_kernel<128>), dim3((unsigned)grid), dim3(512), 0, stream, a);
     else
-      hipLaunchKernelGGL((bwd_dkdv_kernel<64>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+      hipLaunchKernelGGL((bwd_dkdv_kernel<64>), dim3((unsigned)grid), dim3(512), 0, stream, a);
   }
   return launch_status();
 }

@@ -103,7 +103,8 @@ def test_block_attn_bwd_accumulate_adds(usp):
         torch.cuda.synchronize()
         outs.append((dq.cpu(), dk.cpu(), dv.cpu()))
     for a, b in zip(*outs):
-        assert torch.equal(a + 1.0, b)          # same kernel, same order: adding to ones is exact here or off by rounding
+        # same kernels on the same data; only the fp32 rounding of (1 + x) and the order of the atomic adds differ
+        assert torch.allclose(a + 1.0, b, rtol=0, atol=2e-5)
     with pytest.raises(usp.UspError):
         usp.usp_block_attn_bwd(q, k, v, d_o, lse, delta, None, dk, dv, bs, L, L, hq, hkv, hs, 0.0, True, d, d, False)
     with pytest.raises(usp.UspError):
