@@ -114,10 +114,12 @@ def _rand_parts(rng, n, bs, Lq, hq, hs, neg_inf_frac=0.0):
 
 @pytest.mark.parametrize("n,bs,Lq,hq,hs,out_dtype", [
     (2, 1, 128, 2, 64, tl.FP32),
-    (8, 1, 1000, 4, 128, tl.BF16),      # ragged against the 128-row workgroup tile
+    (8, 1, 1000, 4, 128, tl.BF16),      # ragged against the 256-thread workgroup
     (4, 2, 333, 3, 128, tl.FP32),
     (1, 1, 77, 5, 64, tl.FP32),
-    (5, 1, 64, 32, 128, tl.BF16),       # more heads than rows in a tile along the position axis
+    (5, 1, 64, 32, 128, tl.BF16),       # more heads than positions
+    (12, 1, 100, 2, 64, tl.FP32),       # more than eight parts: the general (looping) instance
+    (3, 2, 50, 4, 128, tl.BF16),
 ])
 def test_lse_merge_matches_oracle(usp, n, bs, Lq, hq, hs, out_dtype):
     rng = np.random.default_rng(11 + n)
