@@ -19,7 +19,7 @@ struct LayoutArgs {
   const char* head;    // head-layout buffer base (slot of rank head_rank_base)
   int64_t n;           // rows per slab = L/N
   int64_t Lq;          // L/R
-  int bs, U, rank_begin, head_rank_base;
+  int bs, U, rank_begin, rank_step, head_rank_base;
   uint32_t run_vecs;   // vectors per run = (heads/U)*hs*esize / sizeof(Vec)
   uint32_t row_vecs;   // vectors per sequence-layout row = heads*hs*esize / sizeof(Vec)
 };
@@ -27,12 +27,15 @@ struct LayoutArgs {
 template <typename Vec, bool kToHead>
 __global__ __launch_bounds__(kThreads) void layout_a2a_kernel(LayoutArgs a) {
   // blockIdx.z -> (rank, batch), blockIdx.y -> source shard u', blockIdx.x -> position in the slab
-  const int rank = a.rank_begin + (int)(blockIdx.z / a.bs);
+  const int slot = (int)(blockIdx.z / a.bs);                 // the slot-th rank of this launch
+  const int rank = a.rank_begin + slot * a.rank_step;
   const int b = (int)(blockIdx.z % a.bs);
   const int up = (int)blockIdx.y;
   const int r = rank / a.U, u = rank % a.U;
   const uint64_t slab_vecs = (uint64_t)a.n * a.run_vecs;
-  const uint64_t head_row0 = (uint64_t)(rank - a.head_rank_base) * a.bs * a.Lq + (uint64_t)b * a.Lq + (uint64_t)up * a.n;
+  // head-layout side: whole buffers are indexed by rank; a packed workspace holds the launch's ranks back to back
+  const uint64_t head_slot = a.head_rank_base < 0 ? (uint64_t)slot : (uint64_t)(rank - a.head_rank_base);
+  const uint64_t head_row0 = head_slot * a.bs * a.Lq + (uint64_t)b * a.Lq + (uint64_t)up * a.n;
   Vec* head = (Vec*)a.head + head_row0 * a.run_vecs;
   const uint64_t seq_row0 = ((uint64_t)(r * a.U + up) * a.bs + b) * a.n;
   Vec* seq = (Vec*)a.seq + seq_row0 * a.row_vecs + (uint64_t)u * a.run_vecs;
@@ -89,7 +92,7 @@ int launch_vec(LayoutArgs a, int dir, size_t run_bytes, size_t row_bytes, int n_
 }  // namespace
 
 int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src, void* dst, int rank_begin,
-                      int rank_end, int head_rank_base, hipStream_t stream) {
+                      int rank_end, int head_rank_base, hipStream_t stream, int rank_step) {
   const size_t es = dtype_size(p.dtype);
   const int N = p.ulysses * p.ring;
   LayoutArgs a;
@@ -100,11 +103,12 @@ int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src,
   a.bs = p.bs;
   a.U = p.ulysses;
   a.rank_begin = rank_begin;
+  a.rank_step = rank_step;
   a.head_rank_base = head_rank_base;
   const size_t run_bytes = (size_t)(heads / p.ulysses) * p.hs * es;
   const size_t row_bytes = (size_t)heads * p.hs * es;
   const uintptr_t align = (uintptr_t)src | (uintptr_t)dst | run_bytes;
-  const int n_ranks = rank_end - rank_begin;
+  const int n_ranks = (rank_end - rank_begin + rank_step - 1) / rank_step;
   if (align % 16 == 0) return launch_vec<u32x4>(a, dir, run_bytes, row_bytes, n_ranks, stream);
   if (align % 8 == 0) return launch_vec<u32x2>(a, dir, run_bytes, row_bytes, n_ranks, stream);
   if (align % 4 == 0) return launch_vec<uint32_t>(a, dir, run_bytes, row_bytes, n_ranks, stream);

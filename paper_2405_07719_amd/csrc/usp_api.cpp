@@ -176,19 +176,45 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   const size_t es = dtype_size(p.dtype);
   const size_t Lq = p.L / p.ring, hq = p.hc / p.ulysses, hkv = p.hk / p.ulysses;
   const size_t qb = up256((size_t)p.bs * Lq * hq * p.hs * es);
-  f.kv_block_bytes = up256((size_t)p.bs * Lq * hkv * p.hs * es);
+  f.kv_block_bytes = (size_t)p.bs * Lq * hkv * p.hs * es;   // exact: blocks are packed back to back (multiple of 128 B)
   f.part_o_bytes = up256((size_t)p.bs * Lq * hq * p.hs * sizeof(float));
   f.part_lse_bytes = up256((size_t)p.bs * Lq * hq * sizeof(float));
   f.n_cols = n_cols;
   size_t off = 0;
   f.q_head = off; off += qb;
   f.o_head = off; off += qb;
-  f.k_head = off; off += f.kv_block_bytes * p.ring * n_cols;
-  f.v_head = off; off += f.kv_block_bytes * p.ring * n_cols;
+  f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
+  f.v_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.o_parts = off; off += p.ring > 1 ? f.part_o_bytes * p.ring : 0;
   f.lse_parts = off; off += p.ring > 1 ? f.part_lse_bytes * p.ring : 0;
   f.total = off;
   return f;
+}
+
+}  // namespace
+
+namespace {
+
+// K and V of every (ring row, Ulysses column in [c0, c1)) to head layout, packed by slot r * n_cols + (u - c0).
+int stage_kv_blocks(const usp_problem& p, const void* k, const void* v, char* k_head, char* v_head, size_t block_bytes,
+                    int c0, int c1, hipStream_t stream) {
+  const int U = p.ulysses, R = p.ring, n_cols = c1 - c0;
+  const void* src[2] = {k, v};
+  char* dst[2] = {k_head, v_head};
+  for (int t = 0; t < 2; ++t) {
+    int st = USP_OK;
+    if (n_cols == U) {
+      st = launch_layout_a2a(p, p.hk, USP_SEQ_TO_HEAD, src[t], dst[t], 0, U * R, -1, stream);
+    } else if (n_cols == 1) {
+      st = launch_layout_a2a(p, p.hk, USP_SEQ_TO_HEAD, src[t], dst[t], c0, U * R, -1, stream, U);
+    } else {
+      for (int r = 0; r < R && st == USP_OK; ++r)
+        st = launch_layout_a2a(p, p.hk, USP_SEQ_TO_HEAD, src[t], dst[t] + (size_t)r * n_cols * block_bytes, r * U + c0,
+                               r * U + c1, -1, stream);
+    }
+    if (st != USP_OK) return st;
+  }
+  return USP_OK;
 }
 
 }  // namespace
@@ -221,17 +247,11 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
 
   (void)es;
 
-  // Steps 3-4 of Algorithm 1 for every K/V block the ranks in range will visit.
-  for (int r = 0; r < R; ++r)
-    for (int u = c0; u < c1; ++u) {
-      const int rank = r * U + u;
-      const size_t slot = ((size_t)r * (c1 - c0) + (u - c0)) * f.kv_block_bytes;
-      // the workspace slot holds this one rank: head-layout base pointer stands for `rank`
-      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, k, ws + f.k_head + slot, rank, rank + 1, rank, stream);
-      if (st != USP_OK) return st;
-      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, v, ws + f.v_head + slot, rank, rank + 1, rank, stream);
-      if (st != USP_OK) return st;
-    }
+  // Steps 3-4 of Algorithm 1 for every K/V block the ranks in range will visit.  The workspace slot of
+  // block (r, u) is r * n_cols + (u - c0): with all U columns that is the rank order (one launch per
+  // tensor); with one column the ranks r * U + u are a stride-U sequence (again one launch per tensor).
+  st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream);
+  if (st != USP_OK) return st;
 
   for (int rank = rank_begin; rank < rank_end; ++rank) {
     const int r = rank / U, u = rank % U;
@@ -323,7 +343,7 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   const size_t Lq = p.L / p.ring, hq = p.hc / p.ulysses, hkv = p.hk / p.ulysses;
   const size_t q_elems = (size_t)p.bs * Lq * hq * p.hs, kv_elems = (size_t)p.bs * Lq * hkv * p.hs;
   const size_t qb = up256(q_elems * es);
-  f.kv_block_bytes = up256(kv_elems * es);
+  f.kv_block_bytes = kv_elems * es;   // exact: blocks are packed back to back
   f.kv_acc_bytes = up256(kv_elems * sizeof(float));
   const size_t blocks = (size_t)p.ring * n_cols;
   size_t off = 0;
@@ -331,8 +351,8 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   f.o_head = off; off += qb;
   f.do_head = off; off += qb;
   f.delta = off; off += up256((size_t)p.bs * hq * Lq * sizeof(float));
-  f.k_head = off; off += f.kv_block_bytes * blocks;
-  f.v_head = off; off += f.kv_block_bytes * blocks;
+  f.k_head = off; off += up256(f.kv_block_bytes * blocks);
+  f.v_head = off; off += up256(f.kv_block_bytes * blocks);
   f.dq_acc = off; off += up256(q_elems * sizeof(float));
   f.dk_acc = off; off += f.kv_acc_bytes * blocks;
   f.dv_acc = off; off += f.kv_acc_bytes * blocks;
@@ -371,16 +391,8 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
   const size_t q_elems = (size_t)p->bs * Lq * hq * p->hs, kv_elems = (size_t)p->bs * Lq * hkv * p->hs;
   auto slot = [&](int r, int u) { return (size_t)r * n_cols + (u - c0); };
 
-  for (int r = 0; r < R; ++r)
-    for (int u = c0; u < c1; ++u) {
-      const int rank = r * U + u;
-      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, k, ws + f.k_head + slot(r, u) * f.kv_block_bytes, rank, rank + 1,
-                             rank, stream);
-      if (st != USP_OK) return st;
-      st = launch_layout_a2a(*p, p->hk, USP_SEQ_TO_HEAD, v, ws + f.v_head + slot(r, u) * f.kv_block_bytes, rank, rank + 1,
-                             rank, stream);
-      if (st != USP_OK) return st;
-    }
+  st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream);
+  if (st != USP_OK) return st;
 
   // first contribution to a K/V block overwrites its accumulator, later ones add
   bool touched[USP_MAX_MERGE_PARTS] = {false};

@@ -41,9 +41,11 @@ __host__ __device__ inline int64_t pos_max(const usp_posdesc& d, int64_t a, int6
 inline int launch_status() { return hipGetLastError() == hipSuccess ? USP_OK : USP_ERR_LAUNCH; }
 
 // Kernel launchers (defined next to their kernels).  All take validated arguments.
-// head_rank_base: the rank whose slot the head-layout base pointer points at (0 for a whole buffer).
+// Ranks rank_begin, rank_begin + rank_step, ... below rank_end are transformed in one launch.
+// head_rank_base >= 0: the rank whose slot the head-layout base pointer points at (0 for a whole buffer);
+// head_rank_base < 0: the head-layout side is a packed workspace holding the launch's ranks back to back.
 int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src, void* dst, int rank_begin,
-                      int rank_end, int head_rank_base, hipStream_t stream);
+                      int rank_end, int head_rank_base, hipStream_t stream, int rank_step = 1);
 int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                      float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
                      hipStream_t stream);
