@@ -9,7 +9,7 @@
 // Two kernels, both on v_mfma_f32_32x32x16_bf16 with fp32 accumulation:
 //   dq_kernel    a workgroup owns 256 query rows, walks the visible key tiles:  S^T = K Q^T, dP^T = V dO^T
 //                (lane = query, so L_i and D_i are per-lane scalars), dQ^T += K^T dS^T.  Deterministic.
-//   dkdv_kernel  a workgroup owns 128 keys of one KV head and one query head, walks the visible query
+//   dkdv_kernel  a workgroup owns 256 keys of one KV head and one query head, walks the visible query
 //                tiles:  S = Q K^T, dP = dO V^T (lane = key; L_i, D_i read from LDS), dV^T += dO^T P,
 //                dK^T += Q^T dS; the query heads of a group are summed with fp32 atomic adds.
 // In both, the accumulator layout of the first product is the B-operand layout of the second, and the
@@ -242,17 +242,15 @@ void bwd_dq_kernel(const BwdArgs a) {
 }
 
 // -------------------------------------------------------------------------------------------------
-// dK, dV.  A workgroup owns 128 keys of one KV head and ONE query head of its group; eight waves in two
-// roles share every staged query tile: waves 0-3 ("dV waves", 32 keys each) compute S, P and dV^T += dO^T P,
-// waves 4-7 ("dK waves", the same 32 keys) compute S, dP, dS and dK^T += Q^T dS.  The score product is
-// done twice, but each wave keeps one 64-register accumulator, so two waves fit a SIMD and the two roles'
-// matrix-core and vector work interleave.  The query heads of a group (and nothing else) meet in the fp32
-// outputs through atomic adds: at most hq/hkv addends per element, the only non-deterministic rounding here.
+// dK, dV.  A workgroup owns 256 keys of one KV head (eight waves of 32 keys) and ONE query head of its
+// group, and walks the visible query tiles of 32 rows, double buffered in LDS.  The query heads of a
+// group (and nothing else) meet in the fp32 outputs through atomic adds: at most hq/hkv addends per
+// element, the only non-deterministic rounding of the backward.
 // -------------------------------------------------------------------------------------------------
 template <int HS>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void bwd_dkdv_kernel(const BwdArgs a) {
-  constexpr int NT = 512, BN = 128, QT = 32;
+  constexpr int NT = 512, BN = 256, QT = 32;
   constexpr int KSTEPS = HS / 16, DB = HS / 32;
   constexpr int RSTR = HS * 2 + 16;
   constexpr int TSTR = (HS == 128) ? 320 : 192;
@@ -263,8 +261,6 @@ void bwd_dkdv_kernel(const BwdArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hl = lane >> 5;
-  const bool dk_role = wave >= 4;
-  const int kw = wave & 3;
   int w = blockIdx.x;
   const int n_groups = a.bs * a.hkv;
   const int group = w % n_groups; w /= n_groups;
@@ -273,25 +269,28 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   const int b = group / a.hkv, kvh = group % a.hkv;
   const int h = kvh * a.g + hg;
   const int tile_key0 = ktile * BN, tile_key1 = min(a.Lk, tile_key0 + BN);
-  const int wave_key0 = tile_key0 + kw * 32;
+  const int wave_key0 = tile_key0 + wave * 32;
   const int key = wave_key0 + l32;
   const int kk = min(key, a.Lk - 1);
   const int kp = a.causal ? pos_of(a.kpos, kk) : 0;
   const bool key_ok = key < a.Lk;
 
-  // B operands of S = Q K^T (both roles) and dP = dO V^T (dK waves): lane = key l32, dims 16 ks + 8 hl ..
+  // B operands of S = Q K^T and dP = dO V^T: lane = key l32, dims 16 ks + 8 hl ..
   bf16x8 kf[KSTEPS], vf[KSTEPS];
   {
     const size_t off = (((size_t)b * a.Lk + kk) * a.hkv + kvh) * HS + 8 * hl;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       kf[ks] = *(const bf16x8*)((const __bf16*)a.k + off + 16 * ks);
-      if (dk_role) vf[ks] = *(const bf16x8*)((const __bf16*)a.v + off + 16 * ks);
+      vf[ks] = *(const bf16x8*)((const __bf16*)a.v + off + 16 * ks);
     }
   }
-  f32x16 acc[DB];
+  f32x16 dk[DB], dv[DB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db) zero16(acc[db]);
+  for (int db = 0; db < DB; ++db) {
+    zero16(dk[db]);
+    zero16(dv[db]);
+  }
 
   const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, a.kpos, a.Lq, tile_key0, tile_key1);
   const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
@@ -353,30 +352,27 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     const float* dl_s = l2_s + QT;
     const int q0 = tile_of(it) * QT;
 
-    // S = Q K^T (and dP = dO V^T): rows = queries, cols = keys
+    // S = Q K^T and dP = dO V^T: rows = queries, cols = keys
     f32x16 s, dp;
     zero16(s);
     zero16(dp);
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       const bf16x8 qa = *(const bf16x8*)(q_rm + row_off + ks * 32);
+      const bf16x8 oa = *(const bf16x8*)(o_rm + row_off + ks * 32);
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
-      if (dk_role) {
-        const bf16x8 oa = *(const bf16x8*)(o_rm + row_off + ks * 32);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vf[ks], dp, 0, 0, 0);
-      }
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vf[ks], dp, 0, 0, 0);
     }
 
-    // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile
+    // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile.
+    // P and dS overwrite s and dp in place.
     const int q1 = min(a.Lq, q0 + QT);
     bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
     if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
-    float x[16];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const f32x4 l2v = *(const f32x4*)(l2_s + 8 * j + 4 * hl);
-      f32x4 dlv = {0.f, 0.f, 0.f, 0.f};
-      if (dk_role) dlv = *(const f32x4*)(dl_s + 8 * j + 4 * hl);
+      const f32x4 dlv = *(const f32x4*)(dl_s + 8 * j + 4 * hl);
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) {
         const int i = 4 * j + tt;
@@ -386,35 +382,44 @@ void bwd_dkdv_kernel(const BwdArgs a) {
           const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
           pi = vis ? pi : 0.f;
         }
-        x[i] = dk_role ? pi * (dp[i] - dlv[tt]) : pi;    // dS for the dK waves, P for the dV waves
+        s[i] = pi;
+        dp[i] = pi * (dp[i] - dlv[tt]);
       }
     }
-    bf16x8 xf[2];
-    pack_b_operand(x, xf[0], xf[1]);
 
-    // dV^T += dO^T P   or   dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
-    const char* a_tr = (dk_role ? q_tr : o_tr) + tr_off;
+    // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
+    for (int st = 0; st < 2; ++st) {
+      u32x4 pw, dw;
+#pragma unroll
+      for (int pr = 0; pr < 4; ++pr) {
+        pw[pr] = pack_bf16(s[8 * st + 2 * pr], s[8 * st + 2 * pr + 1]);
+        dw[pr] = pack_bf16(dp[8 * st + 2 * pr], dp[8 * st + 2 * pr + 1]);
+      }
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw), dsf = __builtin_bit_cast(bf16x8, dw);
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const bf16x8 at = tr_read<TSTR>(a_tr + (16 * st) * TSTR + db * 64);
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at, xf[st], acc[db], 0, 0, 0);
+        const bf16x8 ot = tr_read<TSTR>(o_tr + tr_off + (16 * st) * TSTR + db * 64);
+        const bf16x8 qt = tr_read<TSTR>(q_tr + tr_off + (16 * st) * TSTR + db * 64);
+        dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf, dv[db], 0, 0, 0);
+        dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[db], 0, 0, 0);
       }
+    }
     if (more) stash((it + 1) & 1);
     __syncthreads();
   }
 
   if (key_ok) {
     const size_t off = (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
-    float* dst = (dk_role ? a.dk : a.dv) + off;
-    const float sc = dk_role ? a.scale : 1.0f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) atomicAdd(dst + db * 32 + j * 8 + tt, acc[db][4 * j + tt] * sc);
+        for (int tt = 0; tt < 4; ++tt) {
+          atomicAdd(a.dk + off + db * 32 + j * 8 + tt, dk[db][4 * j + tt] * a.scale);
+          atomicAdd(a.dv + off + db * 32 + j * 8 + tt, dv[db][4 * j + tt]);
+        }
   }
 }
 
@@ -490,7 +495,7 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
       hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dv, n4);
     }
     a.accumulate = 1;
-    a.n_tiles = (a.Lk + 127) / 128;
+    a.n_tiles = (a.Lk + 255) / 256;
     const int64_t grid = (int64_t)a.n_tiles * hq * bs;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
     if (hs == 128)
