@@ -138,6 +138,30 @@ def test_usp_bwd_all_ranks(usp, U, R, zigzag):
             assert tl.max_abs(g[rank], ref[:, prob.rank_positions(rank)]) <= GRAD_TOL, (name, rank)
 
 
+@pytest.mark.parametrize("name,bs,L,hc,hk,hs,U,R,causal", [
+    ("mqa_ring_only", 1, 512, 4, 1, 128, 1, 4, True),
+    ("head_size_64_batch2", 2, 512, 8, 4, 64, 2, 2, True),
+    ("noncausal", 1, 768, 8, 4, 128, 2, 2, False),
+])
+def test_usp_bwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
+    prob = tl.Problem(400 + len(name), bs, L, hc, hk, hs, U, R, causal, True, tl.BF16, with_do=True)
+    p = usp.problem(bs, L, hc, hk, hs, U, R, causal, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
+    q, k, v, d_o = (prob.seq_layout_dev(n) for n in ("q", "k", "v", "do"))
+    o = torch.empty_like(q)
+    lse = torch.empty((prob.N, bs, hc // U, L // R), dtype=torch.float32, device="cuda")
+    ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    usp.usp_attn_fwd(p, q, k, v, o, lse, 0, prob.N, ws)
+    ws2 = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, 0, prob.N, ws2)
+    torch.cuda.synchronize()
+    ref = orc.attention_backward(prob.val["q"], prob.val["k"], prob.val["v"], prob.val["do"], causal)
+    for name_, got, r in zip(("dq", "dk", "dv"), (dq, dk, dv), ref):
+        g = tl.to_f64(got)
+        for rank in range(prob.N):
+            assert tl.max_abs(g[rank], r[:, prob.rank_positions(rank)]) <= GRAD_TOL, (name_, rank)
+
+
 def test_usp_bwd_rejects_bad_arguments(usp):
     p32 = usp.problem(1, 256, 4, 4, 64, 2, 2, False, dtype=usp.USP_FP32)
     assert usp.usp_attn_bwd_workspace_bytes(p32, 1) == 0          # bf16 only

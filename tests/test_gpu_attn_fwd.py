@@ -174,6 +174,21 @@ def test_usp_fwd_causal_gqa_all_factorisations(usp, U, R, zigzag):
         assert tl.max_abs(o[rank], ref_o[rank]) <= to, rank
 
 
+@pytest.mark.parametrize("name,bs,L,hc,hk,hs,U,R,causal", [
+    ("mha_llama2_like", 1, 1024, 8, 8, 128, 4, 2, True),          # MHA: one KV head per query head
+    ("mqa_ring_only", 1, 1024, 8, 1, 128, 1, 4, True),            # MQA: Ulysses cannot split the single KV head, the ring can
+    ("noncausal_visual_tokens", 1, 1536, 8, 4, 128, 2, 2, False),  # bidirectional, length not a power of two
+    ("head_size_64", 2, 768, 8, 4, 64, 2, 2, True),
+    ("gqa_group_of_eight", 1, 1024, 16, 2, 128, 2, 2, True),
+])
+def test_usp_fwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
+    prob = tl.Problem(300 + len(name), bs, L, hc, hk, hs, U, R, causal, True, tl.BF16)
+    o, lse = _run_usp_fwd(usp, prob)
+    ref_o, to = _check_against_reference(prob, o, lse)
+    for rank in range(prob.N):
+        assert tl.max_abs(o[rank], ref_o[rank]) <= to, rank
+
+
 def test_usp_fwd_single_rank_range_and_batch(usp):
     prob = tl.Problem(78, 2, 1024, 8, 4, 128, 2, 2, True, True, tl.BF16)
     o, lse = _run_usp_fwd(usp, prob, 3, 4)                      # rank (r=1, u=1) only
