@@ -89,9 +89,8 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   const int wave_row0 = tile_row0 + wave * (NQB * 32);
 
   const __bf16* qg = (const __bf16*)a.q;
-  const __bf16* kg = (const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS;   // + key * hkv * HS
-  const __bf16* vg = (const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
-  const size_t kv_row_stride = (size_t)a.hkv * HS;
+  const char* kg = (const char*)((const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS);   // + key * hkv * HS * 2 bytes
+  const char* vg = (const char*)((const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
   bf16x8 qf[NQB][KSTEPS];
@@ -147,13 +146,19 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   const int st_row = tid / (HS / 8), st_col = tid % (HS / 8);
   constexpr int ROWS_PER_PASS = NT / (HS / 8);
   u32x4 kreg[CPT], vreg[CPT];
-  auto fetch = [&](const __bf16* base, int it, u32x4* reg) {
-    const int key0 = tile_of(it) * KT;
+  // A tile's base address is wave-uniform (scalar registers); each thread adds a 32-bit byte offset that is the
+  // same for every tile.  Rows past the last key (ragged final tile only) are clamped by a min on the offset:
+  // offsets grow with the row, and (last row, this column) is the largest valid one not beyond this thread's.
+  const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
+  uint32_t st_off[CPT];
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int key = min(key0 + st_row + c * ROWS_PER_PASS, a.Lk - 1);
-      reg[c] = *(const u32x4*)(base + (size_t)key * kv_row_stride + st_col * 8);
-    }
+  for (int c = 0; c < CPT; ++c) st_off[c] = (uint32_t)(st_row + c * ROWS_PER_PASS) * row_bytes + st_col * 16;
+  auto fetch = [&](const char* base, int it, u32x4* reg) {
+    const int key0 = tile_of(it) * KT;
+    const char* tb = base + (size_t)key0 * row_bytes;
+    const uint32_t lim = (uint32_t)min(a.Lk - 1 - key0, KT - 1) * row_bytes + st_col * 16;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) reg[c] = *(const u32x4*)(tb + min(st_off[c], lim));
   };
   auto stash = [&](char* buf, int stride, const u32x4* reg) {
 #pragma unroll
