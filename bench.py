@@ -212,6 +212,19 @@ def main():
         del parts, lparts
         out["hbm_kernels"] = extras
 
+        # ---- what the matrix core delivers on this machine: a pure MFMA loop, and a loop with the forward kernel's
+        #      steady-state instruction mix (MFMA + exp2 + LDS operand reads, random operand bits, no global memory)
+        sink = torch.empty(usp.USP_CALIB_SINK_BYTES, dtype=torch.uint8, device="cuda")
+        calib = {}
+        for mode, name in ((0, "pure_mfma"), (1, "attention_mix_random_operands")):
+            cflop = usp.usp_calib_mfma(mode, 2000, sink)
+            cms = event_ms(lambda: usp.usp_calib_mfma(mode, 2000, sink), 5)
+            calib[name] = {"TFLOP/s": round(cflop / (cms * 1e-3) / 1e12, 1), "ms": round(cms, 3)}
+        calib["note"] = ("context for roofline.frac: loops without global-memory traffic, masks or bookkeeping; "
+                         "256 workgroups x 8 waves, v_mfma_f32_32x32x16_bf16")
+        out["mfma_calibration"] = calib
+        del sink
+
     # ---- backward of the same rank (usp_attn_bwd): 2.5 x the forward flop by the usual accounting
     if not args.no_backward:
         d_o = seq_buffer(inputs.TENSOR_DO, hc, q_heads)

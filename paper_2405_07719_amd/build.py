@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libusp.so")
-SOURCES = ["usp_api.cpp", "layout_a2a.hip", "lse_merge.hip", "block_attn_fwd.hip", "block_attn_bwd.hip"]
+SOURCES = ["usp_api.cpp", "layout_a2a.hip", "lse_merge.hip", "block_attn_fwd.hip", "block_attn_bwd.hip", "calib_mfma.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",

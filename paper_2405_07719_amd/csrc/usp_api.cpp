@@ -451,3 +451,11 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
     }
   return USP_OK;
 }
+
+extern "C" int usp_calib_mfma(int mode, int iters, void* sink, size_t sink_bytes, double* flop, void* stream) {
+  if (!sink || !flop) return USP_ERR_NULL;
+  if (mode != 0 && mode != 1) return USP_ERR_UNSUPPORTED;
+  if (iters < 2 || iters > (1 << 24)) return USP_ERR_SHAPE;
+  if (sink_bytes < kCalibSinkBytes) return USP_ERR_WORKSPACE;
+  return launch_calib_mfma(mode, iters, (float*)sink, flop, (hipStream_t)stream);
+}

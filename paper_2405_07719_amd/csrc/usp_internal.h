@@ -61,4 +61,8 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
                           int accumulate_dq, int accumulate_dkdv, hipStream_t stream);
 int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream);
 
+// Calibration loops (mode 0 pure MFMA, 1 attention mix); sink holds kCalibSinkBytes.  *flop = MFMA flop of the launch.
+constexpr size_t kCalibSinkBytes = 256 * 512 * sizeof(float);
+int launch_calib_mfma(int mode, int iters, float* sink, double* flop, hipStream_t stream);
+
 }  // namespace usp
