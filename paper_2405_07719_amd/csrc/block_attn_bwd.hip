@@ -13,8 +13,8 @@
 //                tiles:  S = Q K^T, dP = dO V^T (lane = key; L_i, D_i read from LDS), dV^T += dO^T P,
 //                dK^T += Q^T dS; the query heads of a group are summed with fp32 atomic adds.
 // In both, the accumulator layout of the first product is the B-operand layout of the second, and the
-// transposed A operands come from LDS transpose reads (tiles are kept in LDS twice: rows padded for 16 B
-// row reads, and rows padded for the transpose read).
+// transposed A operands come from LDS transpose reads of the same tile copy: a row stride of 2*hs + 48 bytes is
+// free of bank conflicts for the 16 B row reads and for the transpose reads alike.
 // Outputs are fp32 accumulators (overwrite or add), so ring steps and ranks can be summed before the
 // final conversion to the problem dtype.
 #include "attn_device.h"
@@ -110,13 +110,11 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_pe
 void bwd_dq_kernel(const BwdArgs a) {
   constexpr int NT = 512, BM = 256, KT = 32;
   constexpr int KSTEPS = HS / 16, DB = HS / 32;
-  constexpr int RSTR = HS * 2 + 16;                 // rows for 16 B row reads
-  constexpr int TSTR = (HS == 128) ? 320 : 192;     // rows for the transpose read
+  constexpr int USTR = HS * 2 + 48;                 // conflict-free for 16 B row reads and for transpose reads
   constexpr int CPR = HS / 8;                       // 16 B chunks per row
-  static_assert(KT * CPR <= NT, "one chunk per thread");
-  __shared__ __attribute__((aligned(16))) char k_rm[KT * RSTR];
-  __shared__ __attribute__((aligned(16))) char k_tr[KT * TSTR];
-  __shared__ __attribute__((aligned(16))) char v_rm[KT * RSTR];
+  constexpr int STAGE = 2 * KT * USTR;              // K, V
+  static_assert(KT * CPR <= NT, "one chunk per thread and tensor");
+  __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hl = lane >> 5;
@@ -134,9 +132,9 @@ void bwd_dq_kernel(const BwdArgs a) {
   const int rr = min(qrow, a.Lq - 1);
   const int qp = a.causal ? pos_of(a.qpos, rr) : 0;
 
-  const __bf16* kg = (const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
-  const __bf16* vg = (const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
-  const size_t kv_row_stride = (size_t)a.hkv * HS;
+  const char* kg = (const char*)((const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
+  const char* vg = (const char*)((const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
+  const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
 
   bf16x8 qf[KSTEPS], dof[KSTEPS];
   {
@@ -162,38 +160,52 @@ void bwd_dq_kernel(const BwdArgs a) {
   const bool wave_live = wave_row0 < a.Lq;
   const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, min(a.Lq, wave_row0 + 32)) : 0;
 
+  // staging: one 16 B chunk of K and of V per thread and tile; the tile base is wave-uniform, the per-thread
+  // byte offset constant, rows past the last key clamped by a min on the offset
   const int st_row = tid / CPR, st_col = tid % CPR;
   const bool stager = st_row < KT;
+  const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
   u32x4 kreg, vreg;
   auto fetch = [&](int it) {
     if (stager) {
-      const int key = min(tile_of(it) * KT + st_row, a.Lk - 1);
-      kreg = *(const u32x4*)(kg + (size_t)key * kv_row_stride + st_col * 8);
-      vreg = *(const u32x4*)(vg + (size_t)key * kv_row_stride + st_col * 8);
+      const int key0 = tile_of(it) * KT;
+      const uint32_t lim = (uint32_t)min(a.Lk - 1 - key0, KT - 1) * row_bytes + st_col * 16;
+      const uint32_t off = min(st_off, lim);
+      kreg = *(const u32x4*)(kg + (size_t)key0 * row_bytes + off);
+      vreg = *(const u32x4*)(vg + (size_t)key0 * row_bytes + off);
     }
   };
-  const int tr_off = tr_lane_offset<TSTR>(lane);
-
-  if (nt > 0) fetch(0);
-  for (int it = 0; it < nt; ++it) {
+  auto stash = [&](int buf) {
     if (stager) {
-      *(u32x4*)(k_rm + st_row * RSTR + st_col * 16) = kreg;
-      *(u32x4*)(k_tr + st_row * TSTR + st_col * 16) = kreg;
-      *(u32x4*)(v_rm + st_row * RSTR + st_col * 16) = vreg;
+      char* base = lds + buf * STAGE;
+      *(u32x4*)(base + st_row * USTR + st_col * 16) = kreg;
+      *(u32x4*)(base + KT * USTR + st_row * USTR + st_col * 16) = vreg;
     }
-    __syncthreads();
-    if (it + 1 < nt) fetch(it + 1);
+  };
+  const int tr_off = tr_lane_offset<USTR>(lane);
+  const int row_off = l32 * USTR + hl * 16;
+
+  if (nt > 0) {
+    fetch(0);
+    stash(0);
+  }
+  __syncthreads();
+  for (int it = 0; it < nt; ++it) {
+    const bool more = it + 1 < nt;
+    if (more) fetch(it + 1);
+    __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
+    const char* k_s = lds + (it & 1) * STAGE;
+    const char* v_s = k_s + KT * USTR;
     const int key0 = tile_of(it) * KT;
 
     // S^T = K Q^T and dP^T = V dO^T   (rows = keys, cols = queries)
     f32x16 s, dp;
     zero16(s);
     zero16(dp);
-    const int row_off = l32 * RSTR + hl * 16;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
-      const bf16x8 kf = *(const bf16x8*)(k_rm + row_off + ks * 32);
-      const bf16x8 vf = *(const bf16x8*)(v_rm + row_off + ks * 32);
+      const bf16x8 kf = *(const bf16x8*)(k_s + row_off + ks * 32);
+      const bf16x8 vf = *(const bf16x8*)(v_s + row_off + ks * 32);
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dp, 0, 0, 0);
     }
@@ -201,17 +213,19 @@ void bwd_dq_kernel(const BwdArgs a) {
     const int key1 = min(a.Lk, key0 + KT);
     bool need_mask = key0 + KT > a.Lk;
     if (a.causal && wave_live) need_mask = need_mask || (pos_max(a.kpos, key0, key1) > wave_qmin);
-    float ds[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2));
-      if (need_mask) {
+    for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2));
+    if (need_mask) {     // wave-uniform and rare: tiles on the causal boundary or the ragged tail
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
         const int key = key0 + 8 * (i >> 2) + 4 * hl + (i & 3);
         const bool vis = key < a.Lk && (!a.causal || pos_of(a.kpos, key) <= qp);
-        p = vis ? p : 0.f;
+        s[i] = vis ? s[i] : 0.f;
       }
-      ds[i] = p * (dp[i] - dlt);
     }
+    float ds[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ds[i] = s[i] * (dp[i] - dlt);
     bf16x8 dsf[2];
     pack_b_operand(ds, dsf[0], dsf[1]);
 
@@ -220,9 +234,10 @@ void bwd_dq_kernel(const BwdArgs a) {
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const bf16x8 kt = tr_read<TSTR>(k_tr + tr_off + (16 * st) * TSTR + db * 64);
+        const bf16x8 kt = tr_read<USTR>(k_s + tr_off + (16 * st) * USTR + db * 64);
         dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf[st], dq[db], 0, 0, 0);
       }
+    if (more) stash((it + 1) & 1);
     __syncthreads();
   }
 
@@ -252,12 +267,13 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_pe
 void bwd_dkdv_kernel(const BwdArgs a) {
   constexpr int NT = 512, BN = 256, QT = 32;
   constexpr int KSTEPS = HS / 16, DB = HS / 32;
-  constexpr int RSTR = HS * 2 + 16;
-  constexpr int TSTR = (HS == 128) ? 320 : 192;
+  constexpr int USTR = HS * 2 + 48;        // one row stride that is conflict-free for 16 B row reads AND transpose reads
   constexpr int CPR = HS / 8;
-  constexpr int STAGE = 2 * QT * RSTR + 2 * QT * TSTR + 2 * QT * 4;   // Q rm, dO rm, Q tr, dO tr, l2, delta
+  constexpr int STAGE = 2 * QT * USTR + 2 * QT * 4;   // Q, dO, l2, delta
   static_assert(QT * CPR <= NT, "one chunk per thread and tensor");
-  __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* const v_s = smem;                  // [BN][USTR]: the workgroup's V rows, resident for the whole kernel
+  char* const lds = smem + BN * USTR;      // [2][STAGE]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hl = lane >> 5;
@@ -275,16 +291,24 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   const int kp = a.causal ? pos_of(a.kpos, kk) : 0;
   const bool key_ok = key < a.Lk;
 
-  // B operands of S = Q K^T and dP = dO V^T: lane = key l32, dims 16 ks + 8 hl ..
-  bf16x8 kf[KSTEPS], vf[KSTEPS];
+  // B operands of S = Q K^T and dP = dO V^T: lane = key l32, dims 16 ks + 8 hl ..  The K fragments stay in
+  // registers; the V fragments are read from LDS every step (both in registers next to the two accumulators
+  // do not fit 256 VGPRs: the spills' reloads share the counter of the prefetch loads and stall on them).
+  bf16x8 kf[KSTEPS];
   {
     const size_t off = (((size_t)b * a.Lk + kk) * a.hkv + kvh) * HS + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      kf[ks] = *(const bf16x8*)((const __bf16*)a.k + off + 16 * ks);
-      vf[ks] = *(const bf16x8*)((const __bf16*)a.v + off + 16 * ks);
+    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8*)((const __bf16*)a.k + off + 16 * ks);
+    const char* vg = (const char*)((const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
+    const uint32_t v_row_bytes = (uint32_t)a.hkv * HS * 2;
+#pragma unroll
+    for (int c = 0; c < BN * CPR / NT; ++c) {
+      const int r = (tid + c * NT) / CPR, col = (tid + c * NT) % CPR;
+      const int krow = min(tile_key0 + r, a.Lk - 1);
+      *(u32x4*)(v_s + r * USTR + col * 16) = *(const u32x4*)(vg + (size_t)krow * v_row_bytes + col * 16);
     }
   }
+  const char* v_row = v_s + (wave * 32 + l32) * USTR + hl * 16;
   f32x16 dk[DB], dv[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db) {
@@ -294,7 +318,10 @@ void bwd_dkdv_kernel(const BwdArgs a) {
 
   const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, a.kpos, a.Lq, tile_key0, tile_key1);
   const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
-  auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
+  // Query tiles are walked from the LAST one down: every workgroup of a head then starts on the same tile and
+  // the ones running side by side on an XCD read the same Q / dO rows at about the same time (one L2 fill
+  // serves them all); walking up from each workgroup's own diagonal would spread them over the sequence.
+  auto tile_of = [&](int it) { const int j = nt - 1 - it; return j < na ? tr.a0 + j : tr.b0 + (j - na); };
   const bool wave_live = wave_key0 < a.Lk;
   const int wave_kmax = (a.causal && wave_live) ? pos_max(a.kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
 
@@ -302,37 +329,42 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   const bool stager = st_row < QT;
   u32x4 qreg, oreg;
   float streg = 0.f;
+  // tile base addresses are wave-uniform; the per-thread byte offset is the same for every tile, clamped by a
+  // min on the offset for rows past the last query (offsets grow with the row)
+  const uint32_t row_bytes = (uint32_t)a.hq * HS * 2;
+  const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
+  const char* qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
+  const char* og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
+  const float* lse_g = a.lse + ((size_t)b * a.hq + h) * a.Lq;
+  const float* dlt_g = a.delta + ((size_t)b * a.hq + h) * a.Lq;
   auto fetch = [&](int it) {
     const int q0 = tile_of(it) * QT;
     if (stager) {
-      const int row = min(q0 + st_row, a.Lq - 1);
-      const size_t off = (((size_t)b * a.Lq + row) * a.hq + h) * HS + st_col * 8;
-      qreg = *(const u32x4*)((const __bf16*)a.q + off);
-      oreg = *(const u32x4*)((const __bf16*)a.d_o + off);
+      const uint32_t lim = (uint32_t)min(a.Lq - 1 - q0, QT - 1) * row_bytes + st_col * 16;
+      const uint32_t off = min(st_off, lim);
+      qreg = *(const u32x4*)(qg + (size_t)q0 * row_bytes + off);
+      oreg = *(const u32x4*)(og + (size_t)q0 * row_bytes + off);
     }
     if (tid < 2 * QT) {
       const int row = min(q0 + (tid % QT), a.Lq - 1);
-      const size_t si = ((size_t)b * a.hq + h) * a.Lq + row;
       if (tid < QT) {
-        const float lse = a.lse[si];
+        const float lse = lse_g[row];
         streg = (lse == -INFINITY) ? INFINITY : lse * kLog2e;
       } else {
-        streg = a.delta[si];
+        streg = dlt_g[row];
       }
     }
   };
   auto stash = [&](int buf) {
     char* base = lds + buf * STAGE;
     if (stager) {
-      *(u32x4*)(base + st_row * RSTR + st_col * 16) = qreg;
-      *(u32x4*)(base + QT * RSTR + st_row * RSTR + st_col * 16) = oreg;
-      *(u32x4*)(base + 2 * QT * RSTR + st_row * TSTR + st_col * 16) = qreg;
-      *(u32x4*)(base + 2 * QT * RSTR + QT * TSTR + st_row * TSTR + st_col * 16) = oreg;
+      *(u32x4*)(base + st_row * USTR + st_col * 16) = qreg;
+      *(u32x4*)(base + QT * USTR + st_row * USTR + st_col * 16) = oreg;
     }
-    if (tid < 2 * QT) *(float*)(base + 2 * QT * RSTR + 2 * QT * TSTR + tid * 4) = streg;
+    if (tid < 2 * QT) *(float*)(base + 2 * QT * USTR + tid * 4) = streg;
   };
-  const int tr_off = tr_lane_offset<TSTR>(lane);
-  const int row_off = l32 * RSTR + hl * 16;
+  const int tr_off = tr_lane_offset<USTR>(lane);
+  const int row_off = l32 * USTR + hl * 16;
 
   if (nt > 0) {
     fetch(0);
@@ -344,11 +376,9 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     if (more) fetch(it + 1);
     __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
     const char* base = lds + (it & 1) * STAGE;
-    const char* q_rm = base;
-    const char* o_rm = base + QT * RSTR;
-    const char* q_tr = base + 2 * QT * RSTR;
-    const char* o_tr = q_tr + QT * TSTR;
-    const float* l2_s = (const float*)(o_tr + QT * TSTR);
+    const char* q_s = base;
+    const char* o_s = base + QT * USTR;
+    const float* l2_s = (const float*)(o_s + QT * USTR);
     const float* dl_s = l2_s + QT;
     const int q0 = tile_of(it) * QT;
 
@@ -358,14 +388,16 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     zero16(dp);
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
-      const bf16x8 qa = *(const bf16x8*)(q_rm + row_off + ks * 32);
-      const bf16x8 oa = *(const bf16x8*)(o_rm + row_off + ks * 32);
+      const bf16x8 qa = *(const bf16x8*)(q_s + row_off + ks * 32);
+      const bf16x8 oa = *(const bf16x8*)(o_s + row_off + ks * 32);
+      const bf16x8 vb = *(const bf16x8*)(v_row + ks * 32);
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vf[ks], dp, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vb, dp, 0, 0, 0);
     }
 
     // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile.
-    // P and dS overwrite s and dp in place.
+    // P and dS overwrite s and dp in place; the mask (rare: tiles on the causal boundary or ragged) sits
+    // behind a wave-uniform branch.
     const int q1 = min(a.Lq, q0 + QT);
     bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
     if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
@@ -374,17 +406,18 @@ void bwd_dkdv_kernel(const BwdArgs a) {
       const f32x4 l2v = *(const f32x4*)(l2_s + 8 * j + 4 * hl);
       const f32x4 dlv = *(const f32x4*)(dl_s + 8 * j + 4 * hl);
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        const int i = 4 * j + tt;
-        float pi = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2v[tt]));
-        if (need_mask) {
+      for (int tt = 0; tt < 4; ++tt)
+        s[4 * j + tt] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * j + tt], a.scale_log2, -l2v[tt]));
+      if (need_mask) {
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
           const int qr = q0 + 8 * j + 4 * hl + tt;
           const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
-          pi = vis ? pi : 0.f;
+          s[4 * j + tt] = vis ? s[4 * j + tt] : 0.f;
         }
-        s[i] = pi;
-        dp[i] = pi * (dp[i] - dlv[tt]);
       }
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) dp[4 * j + tt] = s[4 * j + tt] * (dp[4 * j + tt] - dlv[tt]);
     }
 
     // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
@@ -399,8 +432,8 @@ void bwd_dkdv_kernel(const BwdArgs a) {
       const bf16x8 pf = __builtin_bit_cast(bf16x8, pw), dsf = __builtin_bit_cast(bf16x8, dw);
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const bf16x8 ot = tr_read<TSTR>(o_tr + tr_off + (16 * st) * TSTR + db * 64);
-        const bf16x8 qt = tr_read<TSTR>(q_tr + tr_off + (16 * st) * TSTR + db * 64);
+        const bf16x8 ot = tr_read<USTR>(o_s + tr_off + (16 * st) * USTR + db * 64);
+        const bf16x8 qt = tr_read<USTR>(q_s + tr_off + (16 * st) * USTR + db * 64);
         dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf, dv[db], 0, 0, 0);
         dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[db], 0, 0, 0);
       }
@@ -440,6 +473,20 @@ __global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT
     u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
     __builtin_nontemporal_store(pk, (u32x2*)dst + i);
   }
+}
+
+template <int HS>
+int launch_dkdv(const BwdArgs& a, int64_t grid, hipStream_t stream) {
+  constexpr int USTR = HS * 2 + 48;
+  constexpr size_t lds = 256 * USTR + 2 * (2 * 32 * USTR + 2 * 32 * 4);
+  static bool attr_set = false;   // raise the dynamic LDS limit once per instance
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)bwd_dkdv_kernel<HS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return USP_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((bwd_dkdv_kernel<HS>), dim3((unsigned)grid), dim3(512), lds, stream, a);
+  return launch_status();
 }
 
 }  // namespace
@@ -498,10 +545,8 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
     a.n_tiles = (a.Lk + 255) / 256;
     const int64_t grid = (int64_t)a.n_tiles * hq * bs;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
-    if (hs == 128)
-      hipLaunchKernelGGL((bwd_dkdv_kernel<128>), dim3((unsigned)grid), dim3(512), 0, stream, a);
-    else
-      hipLaunchKernelGGL((bwd_dkdv_kernel<64>), dim3((unsigned)grid), dim3(512), 0, stream, a);
+    const int dk_st = hs == 128 ? launch_dkdv<128>(a, grid, stream) : launch_dkdv<64>(a, grid, stream);
+    if (dk_st != USP_OK) return dk_st;
   }
   return launch_status();
 }
