@@ -92,6 +92,17 @@ __device__ inline TileRanges visible_query_tiles(int causal, const PosDesc32& qp
   return t;
 }
 
+// Make a value that was loaded BEFORE a loop "arrive" here: the empty asm reads and redefines the register, so
+// the compiler waits for the load at this point.  Without it the wait-count pass keeps the pre-loop load pending at
+// the loop header and places its s_waitcnt vmcnt(n) at the first use INSIDE the loop, where, from the second trip
+// on, it waits for that trip's freshly issued prefetch loads instead (the counter only knows "all but n").
+__device__ inline void settle(bf16x8& x) {
+  u32x4 t = __builtin_bit_cast(u32x4, x);
+  asm volatile("" : "+v"(t));
+  x = __builtin_bit_cast(bf16x8, t);
+}
+__device__ inline void settle(float& x) { asm volatile("" : "+v"(x)); }
+
 __device__ inline uint32_t pack_bf16(float lo, float hi) {
   f32x2 f = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));

@@ -147,8 +147,15 @@ void bwd_dq_kernel(const BwdArgs a) {
   }
   const size_t stat = ((size_t)b * a.hq + h) * a.Lq + rr;
   const float lse = a.lse[stat];
-  const float l2 = (lse == -INFINITY) ? INFINITY : lse * kLog2e;   // a row that saw nothing: P = 0
-  const float dlt = a.delta[stat];
+  float dlt = a.delta[stat];
+  float l2 = (lse == -INFINITY) ? INFINITY : lse * kLog2e;   // a row that saw nothing: P = 0
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) {
+    settle(qf[ks]);
+    settle(dof[ks]);
+  }
+  settle(l2);
+  settle(dlt);
 
   f32x16 dq[DB];
 #pragma unroll
@@ -309,6 +316,8 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     }
   }
   const char* v_row = v_s + (wave * 32 + l32) * USTR + hl * 16;
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) settle(kf[ks]);
   f32x16 dk[DB], dv[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db) {
@@ -335,8 +344,7 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
   const char* qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
   const char* og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
-  const float* lse_g = a.lse + ((size_t)b * a.hq + h) * a.Lq;
-  const float* dlt_g = a.delta + ((size_t)b * a.hq + h) * a.Lq;
+  const float* stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
   auto fetch = [&](int it) {
     const int q0 = tile_of(it) * QT;
     if (stager) {
@@ -345,15 +353,7 @@ void bwd_dkdv_kernel(const BwdArgs a) {
       qreg = *(const u32x4*)(qg + (size_t)q0 * row_bytes + off);
       oreg = *(const u32x4*)(og + (size_t)q0 * row_bytes + off);
     }
-    if (tid < 2 * QT) {
-      const int row = min(q0 + (tid % QT), a.Lq - 1);
-      if (tid < QT) {
-        const float lse = lse_g[row];
-        streg = (lse == -INFINITY) ? INFINITY : lse * kLog2e;
-      } else {
-        streg = dlt_g[row];
-      }
-    }
+    if (tid < 2 * QT) streg = stat_g[min(q0 + (tid % QT), a.Lq - 1)];   // raw: converted when stashed, not here
   };
   auto stash = [&](int buf) {
     char* base = lds + buf * STAGE;
@@ -361,7 +361,11 @@ void bwd_dkdv_kernel(const BwdArgs a) {
       *(u32x4*)(base + st_row * USTR + st_col * 16) = qreg;
       *(u32x4*)(base + QT * USTR + st_row * USTR + st_col * 16) = oreg;
     }
-    if (tid < 2 * QT) *(float*)(base + 2 * QT * USTR + tid * 4) = streg;
+    if (tid < 2 * QT) {
+      // threads 0..QT-1 carry LSE -> base-2 units (a row that saw nothing: +inf, so that P = 0), the next QT carry D
+      const float val = tid < QT ? ((streg == -INFINITY) ? INFINITY : streg * kLog2e) : streg;
+      *(float*)(base + 2 * QT * USTR + tid * 4) = val;
+    }
   };
   const int tr_off = tr_lane_offset<USTR>(lane);
   const int row_off = l32 * USTR + hl * 16;
