@@ -276,8 +276,10 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   constexpr int KSTEPS = HS / 16, DB = HS / 32;
   constexpr int USTR = HS * 2 + 48;        // one row stride that is conflict-free for 16 B row reads AND transpose reads
   constexpr int CPR = HS / 8;
-  constexpr int STAGE = 2 * QT * USTR + 2 * QT * 4;   // Q, dO, l2, delta
+  constexpr int STAGE = 2 * QT * USTR;     // Q, dO (each row carries its statistic in the padding, see below)
+  constexpr int XOFF = HS * 2;             // byte offset, inside a row, of the extra k-step that holds the statistic
   static_assert(QT * CPR <= NT, "one chunk per thread and tensor");
+  static_assert(XOFF + 32 <= USTR, "the extra k-step lives in the row padding");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* const v_s = smem;                  // [BN][USTR]: the workgroup's V rows, resident for the whole kernel
   char* const lds = smem + BN * USTR;      // [2][STAGE]
@@ -345,6 +347,7 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   const char* qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
   const char* og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
   const float* stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
+  const float inv_scale = 1.0f / a.scale;
   auto fetch = [&](int it) {
     const int q0 = tile_of(it) * QT;
     if (stager) {
@@ -362,13 +365,28 @@ void bwd_dkdv_kernel(const BwdArgs a) {
       *(u32x4*)(base + QT * USTR + st_row * USTR + st_col * 16) = oreg;
     }
     if (tid < 2 * QT) {
-      // threads 0..QT-1 carry LSE -> base-2 units (a row that saw nothing: +inf, so that P = 0), the next QT carry D
-      const float val = tid < QT ? ((streg == -INFINITY) ? INFINITY : streg * kLog2e) : streg;
-      *(float*)(base + 2 * QT * USTR + tid * 4) = val;
+      // The row statistics ride through the matrix core: with one more k-step whose A row is x split into three
+      // bf16 pieces (exact to fp32 accuracy) and whose B column is 1, 1, 1, the first product comes out as
+      // q.k - LSE/scale (threads 0..QT-1, into the Q rows) and dO.v - D (the next QT threads, into the dO rows)
+      // without any per-row read by the 16 rows a lane holds.  A row that saw nothing gets -1e30: P = 0.
+      float x = tid < QT ? ((streg == -INFINITY) ? -1e30f : fmaxf(fminf(-streg * inv_scale, 1e30f), -1e30f)) : -streg;
+      const __bf16 hi = (__bf16)x;
+      x -= (float)hi;
+      const __bf16 mid = (__bf16)x;
+      x -= (float)mid;
+      const __bf16 lo = (__bf16)x;
+      const bf16x8 piece = {hi, mid, lo, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+      *(bf16x8*)(base + (tid < QT ? 0 : QT * USTR) + (tid % QT) * USTR + XOFF) = piece;
     }
   };
   const int tr_off = tr_lane_offset<USTR>(lane);
   const int row_off = l32 * USTR + hl * 16;
+  // B operand of the extra k-step: k indices 0..2 are one (lanes of the lower half hold k 0..7), the rest zero;
+  // the upper 16 bytes of the A rows' extra step are zeroed once (nothing else writes them)
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)((hl == 0 && e < 3) ? 1.f : 0.f);
+  if (tid < 4 * QT) *(u32x4*)(lds + (tid / QT) * (QT * USTR) + (tid % QT) * USTR + XOFF + 16) = u32x4{0, 0, 0, 0};
 
   if (nt > 0) {
     fetch(0);
@@ -382,8 +400,6 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     const char* base = lds + (it & 1) * STAGE;
     const char* q_s = base;
     const char* o_s = base + QT * USTR;
-    const float* l2_s = (const float*)(o_s + QT * USTR);
-    const float* dl_s = l2_s + QT;
     const int q0 = tile_of(it) * QT;
 
     // S = Q K^T and dP = dO V^T: rows = queries, cols = keys
@@ -398,6 +414,12 @@ void bwd_dkdv_kernel(const BwdArgs a) {
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vb, dp, 0, 0, 0);
     }
+    {   // the extra k-step: s -= LSE / scale, dp -= D
+      const bf16x8 qa = *(const bf16x8*)(q_s + row_off + XOFF);
+      const bf16x8 oa = *(const bf16x8*)(o_s + row_off + XOFF);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, ones, s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, ones, dp, 0, 0, 0);
+    }
 
     // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile.
     // P and dS overwrite s and dp in place; the mask (rare: tiles on the causal boundary or ragged) sits
@@ -406,23 +428,17 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
     if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const f32x4 l2v = *(const f32x4*)(l2_s + 8 * j + 4 * hl);
-      const f32x4 dlv = *(const f32x4*)(dl_s + 8 * j + 4 * hl);
+    for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(s[i] * a.scale_log2);
+    if (need_mask) {
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt)
-        s[4 * j + tt] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * j + tt], a.scale_log2, -l2v[tt]));
-      if (need_mask) {
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-          const int qr = q0 + 8 * j + 4 * hl + tt;
-          const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
-          s[4 * j + tt] = vis ? s[4 * j + tt] : 0.f;
-        }
+      for (int i = 0; i < 16; ++i) {
+        const int qr = q0 + 8 * (i >> 2) + 4 * hl + (i & 3);
+        const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
+        s[i] = vis ? s[i] : 0.f;
       }
-#pragma unroll
-      for (int tt = 0; tt < 4; ++tt) dp[4 * j + tt] = s[4 * j + tt] * (dp[4 * j + tt] - dlv[tt]);
     }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dp[i] *= s[i];
 
     // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
 #pragma unroll
@@ -482,7 +498,7 @@ __global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT
 template <int HS>
 int launch_dkdv(const BwdArgs& a, int64_t grid, hipStream_t stream) {
   constexpr int USTR = HS * 2 + 48;
-  constexpr size_t lds = 256 * USTR + 2 * (2 * 32 * USTR + 2 * 32 * 4);
+  constexpr size_t lds = 256 * USTR + 2 * (2 * 32 * USTR);
   static bool attr_set = false;   // raise the dynamic LDS limit once per instance
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)bwd_dkdv_kernel<HS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
