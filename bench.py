@@ -139,29 +139,46 @@ def main():
         rk = s * U + u
         usp.usp_layout_a2a(p, hk, usp.USP_SEQ_TO_HEAD, k, kh[s].data_ptr() - rk * kh[s].numel() * 2, rk, rk + 1)
         usp.usp_layout_a2a(p, hk, usp.USP_SEQ_TO_HEAD, v, vh[s].data_ptr() - rk * vh[s].numel() * 2, rk, rk + 1)
-    part_dtype = usp.USP_BF16 if R == 1 else usp.USP_FP32
-    o_parts = [torch.empty((bs, Lq, hq, hs), dtype=torch.bfloat16 if R == 1 else torch.float32, device="cuda") for _ in range(R)]
-    l_parts = [torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda") for _ in range(R)]
+    o_ring = torch.empty((bs, Lq, hq, hs), dtype=torch.bfloat16, device="cuda")
+    l_ring = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
     kds = [usp.usp_local_positions(p, (r - i) % R, u)[1] for i in range(R)]
+    k_blocks = [kh[(r - i) % R] for i in range(R)]
+    v_blocks = [vh[(r - i) % R] for i in range(R)]
 
-    def attn_only():
-        for i in range(R):
-            s = (r - i) % R
-            usp.usp_block_attn_fwd(qh, kh[s], vh[s], o_parts[i], l_parts[i], bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd,
-                                   kds[i], usp.USP_BF16, part_dtype)
+    def attn_only():      # what the step launches: the rank's whole ring loop, R resident blocks, one launch
+        usp.usp_ring_attn_fwd(qh, k_blocks, v_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd,
+                              usp.USP_BF16, usp.USP_BF16)
 
     for _ in range(args.warmup):
         attn_only()
-    attn_ms = event_ms(attn_only, args.steps)            # all R launches of one step
+    attn_ms = event_ms(attn_only, args.steps)
     attn_tflops = flop / (attn_ms * 1e-3) / 1e12
+    stepwise = None
+    if R > 1 and not args.no_extras:
+        # the same work as a real ring would issue it: one launch per arriving block with fp32 partials, then the merge
+        o_parts = [torch.empty((bs, Lq, hq, hs), dtype=torch.float32, device="cuda") for _ in range(R)]
+        l_parts = [torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda") for _ in range(R)]
+
+        def attn_stepwise():
+            for i in range(R):
+                usp.usp_block_attn_fwd(qh, k_blocks[i], v_blocks[i], o_parts[i], l_parts[i], bs, Lq, Lq, hq, hkv, hs,
+                                       0.0, True, qd, kds[i], usp.USP_BF16, usp.USP_FP32)
+            usp.usp_lse_merge(o_parts, l_parts, o_ring, l_ring, bs, Lq, hq, hs, usp.USP_FP32, usp.USP_BF16)
+        attn_stepwise()
+        sms = event_ms(attn_stepwise, max(3, args.steps // 2))
+        stepwise = {"launches": R + 1, "ms": round(sms, 4), "TFLOP/s": round(flop / (sms * 1e-3) / 1e12, 2),
+                    "note": "one usp_block_attn_fwd per block (fp32 partials) + usp_lse_merge"}
+        del o_parts, l_parts
     # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload, each scaled by what
     # the same counter reads for a plain 512 MiB copy (FETCH_SIZE reads half the bytes, WRITE_SIZE all of them):
     # see profiles/traffic_pmc_ulysses8_L32768.md.  Only known for the default workload.
     traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
     roofline = {"bound": "mfma", "kernel": "block_attn_fwd_mfma", "achieved": round(attn_tflops, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                "launches_per_step": R, "avg_launch_ms": round(attn_ms / R, 4), "traffic": traffic,
+                "launches_per_step": 1, "avg_launch_ms": round(attn_ms, 4), "traffic": traffic,
                 "algorithmic_bytes": float(2 * qh.numel() * 2 + 2 * kh.numel() * 2 + bs * hq * Lq * 4)}
+    if stepwise is not None:
+        roofline["stepwise_ring"] = stepwise
 
     out = {
         "metric": "one-rank USP attention TFLOP/s (bf16 causal fwd) + % MFMA peak; a2a GB/s",

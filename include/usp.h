@@ -74,6 +74,7 @@ typedef struct {
 } usp_posdesc;
 
 #define USP_MAX_MERGE_PARTS 64
+#define USP_MAX_RING_BLOCKS 16
 
 /* Text for a status code (static storage). */
 const char* usp_status_str(int status);
@@ -124,8 +125,25 @@ int usp_lse_merge(const void* const* o_parts, const float* const* lse_parts, int
                   float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
                   void* stream);
 
+/* The whole ring loop of one rank in ONE launch (Algorithm 1 step 5 with the merge folded in; Sec. 2, the
+ * blockwise loop of SP-Ring): attention of q over the n_blocks K/V blocks that are already resident, each of
+ * Lk keys with its own position descriptor.  The online-softmax state of a query row (running maximum, sum and
+ * unnormalised output) stays in registers from the first block to the last, so there are no partial outputs and
+ * no merge pass; the result equals usp_block_attn_fwd per block followed by usp_lse_merge, up to rounding.
+ *   k_blocks, v_blocks: HOST arrays of n_blocks DEVICE pointers, each [bs,Lk,hkv,hs]; kpos_blocks: HOST array
+ *   of n_blocks descriptors (ignored, may be NULL, when causal == 0); 1 <= n_blocks <= USP_MAX_RING_BLOCKS;
+ *   bf16 inputs only (in_dtype is checked); o [bs,Lq,hq,hs] (o_dtype), lse [bs,hq,Lq] float.
+ * Everything else as in usp_block_attn_fwd.  The order of the blocks changes the result only by rounding. */
+int usp_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                      const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
+                      int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
+                      int in_dtype, int o_dtype, void* stream);
+
 /* Algorithm 1 forward for virtual ranks [rank_begin, rank_end):
  * all-to-all of Q,K,V -> ring loop of block attention -> LSE merge -> all-to-all of O.
+ * With bf16 data and R <= USP_MAX_RING_BLOCKS the ring loop and the merge are the single launch of
+ * usp_ring_attn_fwd (all blocks are resident on the one GPU); otherwise one usp_block_attn_fwd per ring step
+ * with fp32 partials, then usp_lse_merge.
  *   q, o: seq layout with hc heads; k, v: seq layout with hk heads (ALL N shards must be
  *   present: the ring reads the other ring ranks' K/V where hardware would receive them);
  *   lse: [N][bs][hc/U][L/R] float, written for the ranks in range. */

@@ -21,6 +21,7 @@ USP_BF16, USP_FP32 = 0, 1
 USP_SPLIT_CONTIG, USP_SPLIT_ZIGZAG = 0, 1
 USP_SEQ_TO_HEAD, USP_HEAD_TO_SEQ = 0, 1
 USP_MAX_MERGE_PARTS = 64
+USP_MAX_RING_BLOCKS = 16
 
 
 class usp_problem(C.Structure):
@@ -62,6 +63,8 @@ def load():
     lib.usp_layout_a2a.argtypes = [P(usp_problem), I, I, V, V, I, I, V]
     lib.usp_block_attn_fwd.argtypes = [V, V, V, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc), P(usp_posdesc), I, I, V]
     lib.usp_lse_merge.argtypes = [P(V), P(V), I, V, V, I, L, I, I, I, I, V]
+    lib.usp_ring_attn_fwd.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc),
+                                      I, I, V]
     lib.usp_attn_fwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_fwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_fwd.argtypes = [P(usp_problem), V, V, V, V, V, I, I, V, C.c_size_t, V]
@@ -72,7 +75,7 @@ def load():
     lib.usp_attn_bwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_bwd.argtypes = [P(usp_problem), V, V, V, V, V, V, V, V, V, I, I, V, C.c_size_t, V]
     lib.usp_calib_mfma.argtypes = [I, I, V, C.c_size_t, P(C.c_double), V]
-    for name in ("usp_calib_mfma", "usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
+    for name in ("usp_ring_attn_fwd", "usp_calib_mfma", "usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
                  "usp_attn_fwd", "usp_attn_bwd", "usp_attn_delta", "usp_block_attn_bwd"):
         getattr(lib, name).restype = I
     _lib = lib
@@ -138,6 +141,17 @@ def usp_lse_merge(o_parts, lse_parts, o_out, lse_out, bs, Lq, hq, hs, part_dtype
     la = (C.c_void_p * n)(*[_ptr(x) for x in lse_parts])
     _check(load().usp_lse_merge(oa, la, n, _ptr(o_out), _ptr(lse_out), bs, Lq, hq, hs, part_dtype, out_dtype,
                                 _stream(stream)), "usp_lse_merge")
+
+
+def usp_ring_attn_fwd(q, k_blocks, v_blocks, kpos_blocks, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal, qpos,
+                      in_dtype, o_dtype, stream=None):
+    n = len(k_blocks)
+    ka = (C.c_void_p * n)(*[_ptr(x) for x in k_blocks])
+    va = (C.c_void_p * n)(*[_ptr(x) for x in v_blocks])
+    kd = (usp_posdesc * n)(*kpos_blocks) if kpos_blocks is not None else None
+    _check(load().usp_ring_attn_fwd(_ptr(q), ka, va, kd, n, _ptr(o), _ptr(lse), bs, Lq, Lk, hq, hkv, hs, scale,
+                                    int(bool(causal)), C.byref(qpos) if qpos is not None else None, in_dtype,
+                                    o_dtype, _stream(stream)), "usp_ring_attn_fwd")
 
 
 def usp_attn_fwd_workspace_bytes(p, n_ranks):

@@ -116,7 +116,8 @@ void bwd_dq_kernel(const BwdArgs a) {
   static_assert(KT * CPR <= NT, "one chunk per thread and tensor");
   __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
   const int l32 = lane & 31, hl = lane >> 5;
   const int n_groups = a.bs * a.hkv;
   int w = blockIdx.x;
@@ -284,7 +285,8 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   char* const v_s = smem;                  // [BN][USTR]: the workgroup's V rows, resident for the whole kernel
   char* const lds = smem + BN * USTR;      // [2][STAGE]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
   const int l32 = lane & 31, hl = lane >> 5;
   int w = blockIdx.x;
   const int n_groups = a.bs * a.hkv;

@@ -31,19 +31,26 @@ namespace {
 
 using namespace dev;
 
+constexpr int kMaxBlocks = USP_MAX_RING_BLOCKS;
+
+// One launch covers n_blocks K/V blocks of Lk keys each (the ring steps of one rank, Algorithm 1 step 5): the
+// online-softmax state of a query row stays in registers from the first block to the last, so no partial results
+// and no merge pass exist.  n_blocks = 1 is the plain single ring step.
 struct AttnArgs {
   const void* q;
-  const void* k;
-  const void* v;
+  const void* k[kMaxBlocks];
+  const void* v[kMaxBlocks];
   void* o;
   float* lse;
   int bs, hq, hkv, g;
   int Lq, Lk;
   int n_qtiles;
+  int n_blocks;
   int causal;
   float scale;        // natural-units scale (for the LSE)
   float scale_log2;   // scale * log2(e)
-  PosDesc32 qpos, kpos;
+  PosDesc32 qpos;
+  PosDesc32 kpos[kMaxBlocks];
 };
 
 // -------------------------------------------------------------------------------------------
@@ -59,7 +66,7 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   constexpr int DB = HS / 32;              // 32-wide head-dim blocks of O^T
   constexpr int KB = KT / 32;              // 32-key blocks of S^T
   constexpr int PS = KT / 16;              // MFMA k-steps of P V
-  constexpr int KSTR = HS * 2 + 16;        // LDS row stride of K in bytes (16 B pad: conflict-free b128 rows)
+  constexpr int KSTR = HS * 2 + 48;        // LDS row stride of K in bytes: conflict-free 16 B row reads (measured)
   constexpr int VSTR = (HS == 128) ? 320 : 192;   // V rows: stride = odd multiple of 64 B for the transpose read
   constexpr int KBYTES = KT * KSTR, VBYTES = KT * VSTR;
   constexpr int CHUNKS = KT * HS / 8;      // 16 B chunks per tile (K and V alike)
@@ -71,7 +78,8 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   char* const kbuf = smem;                  // [2][KBYTES]
   char* const vbuf = smem + 2 * KBYTES;     // [2][VBYTES]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
   const int l32 = lane & 31, hl = lane >> 5;
 
   // ---- work item decode: KV group fastest, then head within group, then query tile (heavy first)
@@ -89,8 +97,7 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   const int wave_row0 = tile_row0 + wave * (NQB * 32);
 
   const __bf16* qg = (const __bf16*)a.q;
-  const char* kg = (const char*)((const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS);   // + key * hkv * HS * 2 bytes
-  const char* vg = (const char*)((const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
+  const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes; + key * hkv * HS * 2
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
   bf16x8 qf[NQB][KSTEPS];
@@ -106,24 +113,13 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
   }
 
-  const TileRanges tr = visible_key_tiles<KT>(a.causal, a.qpos, a.kpos, a.Lk, tile_row0, tile_row1);
-  const int na = tr.a1 - tr.a0;
-  const int nt = na + (tr.b1 - tr.b0);
+  // per-block state of the tile walk (workgroup-uniform), set at the top of the block loop
+  const char* kg = nullptr;
+  const char* vg = nullptr;
+  PosDesc32 kpos = a.kpos[0];
+  TileRanges tr = {0, 0, 0, 0};
+  int na = 0, nt = 0;
   auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
-
-  if (nt == 0) {
-    // nothing visible to this query tile (workgroup-uniform): O = 0, LSE = -inf
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      if (qrow[qb] < a.Lq) {
-        OutT* dst = (OutT*)a.o + (((size_t)b * a.Lq + qrow[qb]) * a.hq + h) * HS + hl * (HS / 2);
-#pragma unroll
-        for (int e = 0; e < HS / 2; ++e) dst[e] = (OutT)0.f;
-        if (hl == 0) a.lse[((size_t)b * a.hq + h) * a.Lq + qrow[qb]] = -INFINITY;
-      }
-    }
-    return;
-  }
 
   f32x16 oacc[NQB][DB];
   float m_run[NQB], l_run[NQB];
@@ -204,7 +200,7 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave
     const int key1 = min(a.Lk, key0 + KT);
     bool need_mask = key0 + KT > a.Lk;
-    if (a.causal && wave_live) need_mask = need_mask || (pos_max(a.kpos, key0, key1) > wave_qmin);
+    if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
     if (need_mask) {
 #pragma unroll
       for (int kbk = 0; kbk < KB; ++kbk)
@@ -212,7 +208,7 @@ void block_attn_fwd_mfma(const AttnArgs a) {
         for (int i = 0; i < 16; ++i) {
           const int key = key0 + kbk * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
           const bool inb = key < a.Lk;
-          const int kp = a.causal ? pos_of(a.kpos, key) : 0;
+          const int kp = a.causal ? pos_of(kpos, key) : 0;
 #pragma unroll
           for (int qb = 0; qb < NQB; ++qb) {
             const bool vis = inb && (!a.causal || kp <= qp[qb]);
@@ -314,36 +310,48 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     __syncthreads();
   };
 
-  // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0
-  fetch(kg, 0, kreg);
-  fetch(vg, 0, vreg);
-  stash(kbuf, KSTR, kreg);
-  stash(vbuf, VSTR, vreg);
-  if (nt > 1) {
-    fetch(kg, 1, kreg);
-    stash(kbuf + KBYTES, KSTR, kreg);
-  }
-  __syncthreads();
-  f32x16 s0[NQB][KB], s1[NQB][KB];
-  qk(kbuf, s0);
-  __syncthreads();   // step 0 overwrites K buffer 0 with tile 2: every wave must have read tile 0 first
-
   const std::integral_constant<bool, true> steady;
   const std::integral_constant<bool, false> draining;
-  int it = 0;
-  for (; it + 3 < nt; it += 2) {   // two steps per trip so the score registers swap roles without copies
-    step(steady, it, s0, s1);
-    step(steady, it + 1, s1, s0);
-  }
-  for (; it < nt; ++it) {          // at most three tiles left
-    step(draining, it, s0, s1);
+  f32x16 s0[NQB][KB], s1[NQB][KB];
+  for (int blk = 0; blk < a.n_blocks; ++blk) {
+    kpos = a.kpos[blk];
+    tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
+    na = tr.a1 - tr.a0;
+    nt = na + (tr.b1 - tr.b0);
+    if (nt == 0) continue;         // nothing of this block is visible to the query tile (workgroup-uniform)
+    kg = (const char*)a.k[blk] + kv_head_off;
+    vg = (const char*)a.v[blk] + kv_head_off;
+
+    // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0.  (Every step ends on a barrier, so the previous
+    //      block's last reads of these buffers are over.)
+    fetch(kg, 0, kreg);
+    fetch(vg, 0, vreg);
+    stash(kbuf, KSTR, kreg);
+    stash(vbuf, VSTR, vreg);
+    if (nt > 1) {
+      fetch(kg, 1, kreg);
+      stash(kbuf + KBYTES, KSTR, kreg);
+    }
+    __syncthreads();
+    qk(kbuf, s0);
+    __syncthreads();   // step 0 overwrites K buffer 0 with tile 2: every wave must have read tile 0 first
+
+    int it = 0;
+    for (; it + 3 < nt; it += 2) {   // two steps per trip so the score registers swap roles without copies
+      step(steady, it, s0, s1);
+      step(steady, it + 1, s1, s0);
+    }
+    for (; it < nt; ++it) {          // at most three tiles left
+      step(draining, it, s0, s1);
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
+      for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk) s0[qb][kbk] = s1[qb][kbk];
+        for (int kbk = 0; kbk < KB; ++kbk) s0[qb][kbk] = s1[qb][kbk];
+    }
   }
 
-  // ---- epilogue: normalise, write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
+  // ---- epilogue: normalise, write O (a row that saw no key at all: l = 0 -> O = 0, LSE = -inf)
+  // ---- write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const float l_tot = both_halves_sum(l_run[qb]);
@@ -398,9 +406,10 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < HS; ++e) { q[e] = qsrc[e]; o[e] = 0.f; }
   float m = -INFINITY, l = 0.f;
-  const TileRanges tr = visible_key_tiles<KT>(a.causal, a.qpos, a.kpos, a.Lk, row0, row1);
-  const float* kg = (const float*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
-  const float* vg = (const float*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
+  const PosDesc32 kpos = a.kpos[0];   // this instance takes one block per launch
+  const TileRanges tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, row0, row1);
+  const float* kg = (const float*)a.k[0] + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
+  const float* vg = (const float*)a.v[0] + ((size_t)b * a.Lk * a.hkv + kvh) * HS;
   const size_t stride = (size_t)a.hkv * HS;
   for (int pass = 0; pass < 2; ++pass) {
     const int j0 = pass ? tr.b0 : tr.a0, j1 = pass ? tr.b1 : tr.a1;
@@ -416,7 +425,7 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
       for (int r = 0; r < KT; ++r) {
         const int key = jt * KT + r;
         if (key >= a.Lk) break;
-        if (a.causal && pos_of(a.kpos, key) > qp) continue;
+        if (a.causal && pos_of(kpos, key) > qp) continue;
         float s = 0.f;
 #pragma unroll
         for (int e = 0; e < HS; ++e) s = __builtin_fmaf(q[e], ks[r][e], s);
@@ -443,7 +452,7 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
 template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
 int launch_mfma(AttnArgs a, hipStream_t stream) {
   constexpr int BM = NWAVES * NQB * 32;
-  constexpr int KSTR = HS * 2 + 16, VSTR = (HS == 128) ? 320 : 192;
+  constexpr int KSTR = HS * 2 + 48, VSTR = (HS == 128) ? 320 : 192;
   constexpr size_t lds = 2 * (size_t)KT * (KSTR + VSTR);
   a.n_qtiles = (a.Lq + BM - 1) / BM;
   const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs;
@@ -480,11 +489,22 @@ static int mfma_variant() {
   return v;
 }
 
-int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int bs, int64_t Lq,
-                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
-                          const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream) {
+int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                         const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
+                         int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
+                         int in_dtype, int o_dtype, hipStream_t stream) {
+  if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
+  if (in_dtype == USP_FP32 && n_blocks != 1) return USP_ERR_UNSUPPORTED;
   AttnArgs a;
-  a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  a.q = q; a.o = o; a.lse = lse;
+  for (int j = 0; j < kMaxBlocks; ++j) {
+    const int jj = j < n_blocks ? j : 0;
+    a.k[j] = k_blocks[jj];
+    a.v[j] = v_blocks[jj];
+    const usp_posdesc& kp = kpos_blocks[jj];
+    a.kpos[j] = PosDesc32{(int)kp.start0, (int)kp.len0, (int)kp.start1, (int)kp.len1};
+  }
+  a.n_blocks = n_blocks;
   a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
   a.Lq = (int)Lq; a.Lk = (int)Lk;
   a.n_qtiles = 0;
@@ -492,7 +512,6 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
   a.scale = scale;
   a.scale_log2 = scale * 1.4426950408889634f;
   a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
-  a.kpos = PosDesc32{(int)kpos.start0, (int)kpos.len0, (int)kpos.start1, (int)kpos.len1};
   if (in_dtype == USP_FP32) {
     if (hs == 128) return o_dtype == USP_FP32 ? launch_fp32<128, float>(a, stream) : launch_fp32<128, __bf16>(a, stream);
     return o_dtype == USP_FP32 ? launch_fp32<64, float>(a, stream) : launch_fp32<64, __bf16>(a, stream);
@@ -512,6 +531,13 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
 #undef USP_VARIANT
   if (o_dtype == USP_FP32) return launch_mfma<64, 1, 8, 64, 2, float>(a, stream);
   return launch_mfma<64, 1, 8, 64, 2, __bf16>(a, stream);
+}
+
+int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int bs, int64_t Lq,
+                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
+                          const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream) {
+  return launch_ring_attn_fwd(q, &k, &v, &kpos, 1, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal, qpos, in_dtype,
+                              o_dtype, stream);
 }
 
 }  // namespace usp

@@ -127,6 +127,36 @@ extern "C" int usp_block_attn_fwd(const void* q, const void* k, const void* v, v
                                in_dtype, o_dtype, (hipStream_t)stream);
 }
 
+extern "C" int usp_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                                 const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
+                                 int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
+                                 int in_dtype, int o_dtype, void* stream) {
+  if (!q || !k_blocks || !v_blocks || !o || !lse) return USP_ERR_NULL;
+  if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return USP_ERR_UNSUPPORTED;
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
+  if (hq % hkv) return USP_ERR_DEGREE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if (in_dtype != USP_BF16 || (o_dtype != USP_BF16 && o_dtype != USP_FP32)) return USP_ERR_DTYPE;
+  if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
+  if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  usp_posdesc qd = {0, Lq, 0, 0};
+  usp_posdesc kd[USP_MAX_RING_BLOCKS];
+  if (causal && (!qpos || !kpos_blocks)) return USP_ERR_NULL;
+  if (causal && !desc_ok(qpos, Lq)) return USP_ERR_SHAPE;
+  if (causal) qd = *qpos;
+  for (int j = 0; j < n_blocks; ++j) {
+    if (!k_blocks[j] || !v_blocks[j]) return USP_ERR_NULL;
+    kd[j] = usp_posdesc{0, Lk, 0, 0};
+    if (causal) {
+      if (!desc_ok(&kpos_blocks[j], Lk)) return USP_ERR_SHAPE;
+      kd[j] = kpos_blocks[j];
+    }
+  }
+  if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  return launch_ring_attn_fwd(q, k_blocks, v_blocks, kd, n_blocks, o, lse, bs, Lq, Lk, hq, hkv, hs, scale,
+                              causal ? 1 : 0, qd, in_dtype, o_dtype, (hipStream_t)stream);
+}
+
 extern "C" int usp_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                              float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
                              void* stream) {
@@ -171,6 +201,10 @@ void column_range(const usp_problem& p, int rb, int re, int* c0, int* c1) {
   }
 }
 
+// The ring loop of a rank runs as one launch (state in registers, no partials, no merge) when the kernel family
+// supports it: bf16 data and few enough blocks for the launch arguments.
+bool ring_in_one_launch(const usp_problem& p) { return p.dtype == USP_BF16 && p.ring <= USP_MAX_RING_BLOCKS; }
+
 FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   FwdPlan f;
   const size_t es = dtype_size(p.dtype);
@@ -185,8 +219,9 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   f.o_head = off; off += qb;
   f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.v_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
-  f.o_parts = off; off += p.ring > 1 ? f.part_o_bytes * p.ring : 0;
-  f.lse_parts = off; off += p.ring > 1 ? f.part_lse_bytes * p.ring : 0;
+  const bool parts = p.ring > 1 && !ring_in_one_launch(p);
+  f.o_parts = off; off += parts ? f.part_o_bytes * p.ring : 0;
+  f.lse_parts = off; off += parts ? f.part_lse_bytes * p.ring : 0;
   f.total = off;
   return f;
 }
@@ -262,6 +297,24 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
     usp_local_positions(p, r, u, nullptr, &qd);
     float* lse_rank = lse + (size_t)rank * p->bs * hq * Lq;
     // Step 5: the ring loop.  Step i visits block s = (r - i) mod R.
+    if (ring_in_one_launch(*p)) {
+      const void* kb[USP_MAX_RING_BLOCKS];
+      const void* vb[USP_MAX_RING_BLOCKS];
+      usp_posdesc kds[USP_MAX_RING_BLOCKS];
+      for (int i = 0; i < R; ++i) {
+        const int s = ((r - i) % R + R) % R;
+        usp_local_positions(p, s, u, nullptr, &kds[i]);
+        const size_t slot = ((size_t)s * (c1 - c0) + (u - c0)) * f.kv_block_bytes;
+        kb[i] = ws + f.k_head + slot;
+        vb[i] = ws + f.v_head + slot;
+      }
+      st = launch_ring_attn_fwd(ws + f.q_head, kb, vb, kds, R, ws + f.o_head, lse_rank, p->bs, Lq, Lq, hq, hkv, p->hs,
+                                scale, p->causal ? 1 : 0, qd, p->dtype, p->dtype, stream);
+      if (st != USP_OK) return st;
+      st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.o_head, o, rank, rank + 1, rank, stream);
+      if (st != USP_OK) return st;
+      continue;
+    }
     const void* o_ptrs[USP_MAX_MERGE_PARTS];
     const float* l_ptrs[USP_MAX_MERGE_PARTS];
     if (R > USP_MAX_MERGE_PARTS) return USP_ERR_UNSUPPORTED;
