@@ -77,6 +77,13 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     assert usp.usp_attn_fwd_workspace_bytes(p, 8) > one
     ring = usp.problem(1, 32768, 32, 8, 128, 1, 8, True)
     w = usp.usp_attn_fwd_workspace_bytes(ring, 1)
-    # + 8 fp32 partial O (64 MiB each) and 8 partial LSE (0.5 MiB each)
-    assert w == 2 * 32 * 2**20 + 2 * 8 * 8 * 2**20 + 8 * 64 * 2**20 + 8 * 2**19
+    # bf16, R <= 16: the ring loop is one launch, so only Q, O and the 8 K and 8 V blocks (8 MiB each)
+    assert w == 2 * 32 * 2**20 + 2 * 8 * 8 * 2**20
+    # fp32 data runs one launch per ring step: + 8 fp32 partial O and 8 partial LSE (elements are 4 bytes now)
+    ring32 = usp.problem(1, 32768, 32, 8, 128, 1, 8, True, usp.USP_SPLIT_ZIGZAG, usp.USP_FP32)
+    w32 = usp.usp_attn_fwd_workspace_bytes(ring32, 1)
+    assert w32 == 2 * 64 * 2**20 + 2 * 8 * 16 * 2**20 + 8 * 64 * 2**20 + 8 * 2**19
+    # more ring ranks than one launch takes blocks: partials again
+    long_ring = usp.problem(1, 32768, 32, 8, 128, 1, 32, True)
+    assert usp.usp_attn_fwd_workspace_bytes(long_ring, 1) == 2 * 8 * 2**20 + 2 * 2 * 32 * 2**20 + 32 * 16 * 2**20 + 32 * 2**17
     assert usp.usp_attn_fwd_workspace_bytes(p, 0) == 0

@@ -180,6 +180,7 @@ def test_usp_fwd_causal_gqa_all_factorisations(usp, U, R, zigzag):
     ("noncausal_visual_tokens", 1, 1536, 8, 4, 128, 2, 2, False),  # bidirectional, length not a power of two
     ("head_size_64", 2, 768, 8, 4, 64, 2, 2, True),
     ("gqa_group_of_eight", 1, 1024, 16, 2, 128, 2, 2, True),
+    ("ring_of_32_stepwise_path", 1, 2048, 4, 2, 128, 1, 32, True),  # more blocks than one launch takes: per-step launches + merge
 ])
 def test_usp_fwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
     prob = tl.Problem(300 + len(name), bs, L, hc, hk, hs, U, R, causal, True, tl.BF16)
