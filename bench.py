@@ -31,6 +31,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # rocprofv3 --pmc FETCH_SIZE (x2, the factor a plain copy of known size gives) + WRITE_SIZE, KiB -> bytes, per
 # launch of the block-attention kernel
 # (FETCH_SIZE 217999 KiB; copy calibration: a 524288 KiB copy reads FETCH_SIZE 262158, WRITE_SIZE 524288)
+MEASURED_CLOCK_GHZ = 2.07   # block_attn_fwd_mfma on the default workload, see profiles/clock_cycles_ulysses8_L32768.md
 MEASURED_TRAFFIC_BYTES = {"ulysses8_L32768": round((217999 * (524288 / 262158) + 36352 * (524288 / 524288)) * 1024.0)}
 
 WORKLOADS = {
@@ -65,6 +66,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="ulysses8_L32768", choices=sorted(WORKLOADS))
+    ap.add_argument("--rank", type=int, default=None,
+                    help="virtual rank to time (default: ring rank 0, Ulysses rank 0; ring rank R-1 has the same pair "
+                         "count but a different tile geometry)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-extras", action="store_true", help="skip the layout / merge bandwidth legs")
     ap.add_argument("--cpu-rows", type=int, default=16384, help="sampled query rows per head for the oracle leg")
@@ -87,6 +91,11 @@ def main():
     torch.cuda.set_device(0)
     bs, L, hc, hk, hs, U, R, rank = WORKLOADS[args.workload]
     N = U * R
+    if args.rank is not None:
+        if not 0 <= args.rank < N:
+            print(f"bench.py: --rank must be in [0, {N})", file=sys.stderr)
+            sys.exit(2)
+        rank = args.rank
     seed = 1001
     p = usp.problem(bs, L, hc, hk, hs, U, R, True, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
     r, u = divmod(rank, U)
@@ -179,6 +188,10 @@ def main():
                 "algorithmic_bytes": float(2 * qh.numel() * 2 + 2 * kh.numel() * 2 + bs * hq * Lq * 4)}
     if stepwise is not None:
         roofline["stepwise_ring"] = stepwise
+    # the same fraction against CUs x the clock the box sustained under this kernel (GRBM_GUI_ACTIVE / duration in
+    # profiles/clock_cycles_ulysses8_L32768.md) x 4096 bf16 MFMA flop per CU and cycle
+    roofline["frac_of_peak_at_measured_clock"] = round(attn_tflops / (256 * MEASURED_CLOCK_GHZ * 4096 / 1e3), 4)
+    roofline["measured_clock_ghz"] = MEASURED_CLOCK_GHZ
 
     out = {
         "metric": "one-rank USP attention TFLOP/s (bf16 causal fwd) + % MFMA peak; a2a GB/s",
@@ -287,6 +300,8 @@ def main():
         sample_pairs = float((rows_pos + 1).sum()) * hq * bs
         out["cpu_baseline"] = {"value": round(4.0 * hs * sample_pairs / cpu_s / 1e12, 5), "unit": "TFLOP/s",
                                "cores": int(cores), "kind": "oracle", "seconds": round(cpu_s, 2),
+                               "pairs_per_s": round(sample_pairs / cpu_s, 1),
+                               "extrapolated_full_step_seconds": round(cpu_s * (pairs * hq * bs) / sample_pairs, 1),
                                "sample": f"{rows_local.size} uniformly sampled query rows x {hq} heads of the timed rank, "
                                          f"all {L} keys, fp64 NumPy; same causal-effective flop accounting"}
         # parity of the timed step's output on the sampled rows (O comes back in seq layout: pick rank/rows)
