@@ -25,23 +25,32 @@ namespace {
 
 using namespace dev;
 
+constexpr int kMaxBlocks = USP_MAX_RING_BLOCKS;
+
+// One launch covers the n_blocks K/V blocks of a rank's ring loop (n_blocks = 1: a single ring step): the dQ
+// kernel walks them one after the other with its accumulator in registers, the dK/dV kernel spreads them over
+// the grid (each block has its own output accumulators).
 struct BwdArgs {
   const void* q;
-  const void* k;
-  const void* v;
+  const void* k[kMaxBlocks];
+  const void* v[kMaxBlocks];
   const void* d_o;
   const float* lse;     // [bs,hq,Lq]  final LSE (natural log)
   const float* delta;   // [bs,hq,Lq]  D_i
   float* dq;            // [bs,Lq,hq,hs]  fp32
-  float* dk;            // [bs,Lk,hkv,hs] fp32
-  float* dv;            // [bs,Lk,hkv,hs] fp32
+  float* dk[kMaxBlocks];   // [bs,Lk,hkv,hs] fp32 per block
+  float* dv[kMaxBlocks];
   int bs, hq, hkv, g;
   int Lq, Lk;
-  int n_tiles;          // query tiles (dq) or key tiles (dkdv)
+  int n_tiles;          // query tiles (dq) or key tiles per block (dkdv)
+  int n_blocks;
   int causal;
-  int accumulate;       // 0: overwrite the outputs, 1: add to them
+  int accumulate;       // dq: 0 overwrite, 1 add
+  int heads_per_wg;     // dkdv: query heads of a KV group walked by one workgroup (g: plain stores; else atomics)
+  int acc_dkdv[kMaxBlocks];   // dkdv with heads_per_wg == g: 0 overwrite the block's dK/dV, 1 add to them
   float scale, scale_log2;
-  PosDesc32 qpos, kpos;
+  PosDesc32 qpos;
+  PosDesc32 kpos[kMaxBlocks];
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -133,8 +142,9 @@ void bwd_dq_kernel(const BwdArgs a) {
   const int rr = min(qrow, a.Lq - 1);
   const int qp = a.causal ? pos_of(a.qpos, rr) : 0;
 
-  const char* kg = (const char*)((const __bf16*)a.k + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
-  const char* vg = (const char*)((const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
+  const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes
+  const char* kg = nullptr;   // per block, set at the top of the block loop
+  const char* vg = nullptr;
   const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
 
   bf16x8 qf[KSTEPS], dof[KSTEPS];
@@ -162,8 +172,9 @@ void bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
   for (int db = 0; db < DB; ++db) zero16(dq[db]);
 
-  const TileRanges tr = visible_key_tiles<KT>(a.causal, a.qpos, a.kpos, a.Lk, tile_row0, tile_row1);
-  const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
+  PosDesc32 kpos = a.kpos[0];
+  TileRanges tr = {0, 0, 0, 0};
+  int na = 0, nt = 0;
   auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
   const bool wave_live = wave_row0 < a.Lq;
   const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, min(a.Lq, wave_row0 + 32)) : 0;
@@ -193,10 +204,16 @@ void bwd_dq_kernel(const BwdArgs a) {
   const int tr_off = tr_lane_offset<USTR>(lane);
   const int row_off = l32 * USTR + hl * 16;
 
-  if (nt > 0) {
-    fetch(0);
-    stash(0);
-  }
+  for (int blk = 0; blk < a.n_blocks; ++blk) {
+  kpos = a.kpos[blk];
+  tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
+  na = tr.a1 - tr.a0;
+  nt = na + (tr.b1 - tr.b0);
+  if (nt == 0) continue;                   // workgroup-uniform
+  kg = (const char*)a.k[blk] + kv_head_off;
+  vg = (const char*)a.v[blk] + kv_head_off;
+  fetch(0);
+  stash(0);                                // the previous block's last step ended on a barrier
   __syncthreads();
   for (int it = 0; it < nt; ++it) {
     const bool more = it + 1 < nt;
@@ -220,14 +237,14 @@ void bwd_dq_kernel(const BwdArgs a) {
 
     const int key1 = min(a.Lk, key0 + KT);
     bool need_mask = key0 + KT > a.Lk;
-    if (a.causal && wave_live) need_mask = need_mask || (pos_max(a.kpos, key0, key1) > wave_qmin);
+    if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2));
     if (need_mask) {     // wave-uniform and rare: tiles on the causal boundary or the ragged tail
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int key = key0 + 8 * (i >> 2) + 4 * hl + (i & 3);
-        const bool vis = key < a.Lk && (!a.causal || pos_of(a.kpos, key) <= qp);
+        const bool vis = key < a.Lk && (!a.causal || pos_of(kpos, key) <= qp);
         s[i] = vis ? s[i] : 0.f;
       }
     }
@@ -248,6 +265,7 @@ void bwd_dq_kernel(const BwdArgs a) {
     if (more) stash((it + 1) & 1);
     __syncthreads();
   }
+  }   // blocks
 
   if (qrow < a.Lq) {
     float* dst = a.dq + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
@@ -291,15 +309,17 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   int w = blockIdx.x;
   const int n_groups = a.bs * a.hkv;
   const int group = w % n_groups; w /= n_groups;
-  const int hg = w % a.g;
-  const int ktile = w / a.g;               // ascending local index: keys seen by the most queries first
+  const int n_hsplit = a.g / a.heads_per_wg;   // workgroups that share a key tile's outputs (1: nobody else)
+  const int hg0 = (w % n_hsplit) * a.heads_per_wg; w /= n_hsplit;
+  const int ktile = w % a.n_tiles;         // ascending local index: keys seen by the most queries first
+  const int blk = w / a.n_tiles;           // K/V block of the ring loop
+  const PosDesc32 kpos = a.kpos[blk];
   const int b = group / a.hkv, kvh = group % a.hkv;
-  const int h = kvh * a.g + hg;
   const int tile_key0 = ktile * BN, tile_key1 = min(a.Lk, tile_key0 + BN);
   const int wave_key0 = tile_key0 + wave * 32;
   const int key = wave_key0 + l32;
   const int kk = min(key, a.Lk - 1);
-  const int kp = a.causal ? pos_of(a.kpos, kk) : 0;
+  const int kp = a.causal ? pos_of(kpos, kk) : 0;
   const bool key_ok = key < a.Lk;
 
   // B operands of S = Q K^T and dP = dO V^T: lane = key l32, dims 16 ks + 8 hl ..  The K fragments stay in
@@ -309,8 +329,8 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   {
     const size_t off = (((size_t)b * a.Lk + kk) * a.hkv + kvh) * HS + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8*)((const __bf16*)a.k + off + 16 * ks);
-    const char* vg = (const char*)((const __bf16*)a.v + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
+    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8*)((const __bf16*)a.k[blk] + off + 16 * ks);
+    const char* vg = (const char*)((const __bf16*)a.v[blk] + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
     const uint32_t v_row_bytes = (uint32_t)a.hkv * HS * 2;
 #pragma unroll
     for (int c = 0; c < BN * CPR / NT; ++c) {
@@ -329,14 +349,14 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     zero16(dv[db]);
   }
 
-  const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, a.kpos, a.Lq, tile_key0, tile_key1);
+  const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, kpos, a.Lq, tile_key0, tile_key1);
   const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
   // Query tiles are walked from the LAST one down: every workgroup of a head then starts on the same tile and
   // the ones running side by side on an XCD read the same Q / dO rows at about the same time (one L2 fill
   // serves them all); walking up from each workgroup's own diagonal would spread them over the sequence.
   auto tile_of = [&](int it) { const int j = nt - 1 - it; return j < na ? tr.a0 + j : tr.b0 + (j - na); };
   const bool wave_live = wave_key0 < a.Lk;
-  const int wave_kmax = (a.causal && wave_live) ? pos_max(a.kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
+  const int wave_kmax = (a.causal && wave_live) ? pos_max(kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
 
   const int st_row = tid / CPR, st_col = tid % CPR;
   const bool stager = st_row < QT;
@@ -346,9 +366,9 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   // min on the offset for rows past the last query (offsets grow with the row)
   const uint32_t row_bytes = (uint32_t)a.hq * HS * 2;
   const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
-  const char* qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
-  const char* og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
-  const float* stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
+  const char* qg = nullptr;      // per query head, set at the top of the head loop
+  const char* og = nullptr;
+  const float* stat_g = nullptr;
   const float inv_scale = 1.0f / a.scale;
   auto fetch = [&](int it) {
     const int q0 = tile_of(it) * QT;
@@ -390,9 +410,16 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)((hl == 0 && e < 3) ? 1.f : 0.f);
   if (tid < 4 * QT) *(u32x4*)(lds + (tid / QT) * (QT * USTR) + (tid % QT) * USTR + XOFF + 16) = u32x4{0, 0, 0, 0};
 
+  // The query heads of the KV group that this workgroup walks (all g of them when the grid is large enough
+  // without splitting them: then nobody else adds to these keys' dK/dV and the epilogue is a plain store).
+  for (int hh = 0; hh < a.heads_per_wg; ++hh) {
+  const int h = kvh * a.g + hg0 + hh;
+  qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
+  og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
+  stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
   if (nt > 0) {
     fetch(0);
-    stash(0);
+    stash(0);                              // the previous head's last step ended on a barrier
   }
   __syncthreads();
   for (int it = 0; it < nt; ++it) {
@@ -463,18 +490,41 @@ void bwd_dkdv_kernel(const BwdArgs a) {
     if (more) stash((it + 1) & 1);
     __syncthreads();
   }
+  }   // query heads
 
   if (key_ok) {
     const size_t off = (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
+    float* dkp = a.dk[blk] + off;
+    float* dvp = a.dv[blk] + off;
+    if (n_hsplit > 1) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-          atomicAdd(a.dk + off + db * 32 + j * 8 + tt, dk[db][4 * j + tt] * a.scale);
-          atomicAdd(a.dv + off + db * 32 + j * 8 + tt, dv[db][4 * j + tt]);
+          for (int tt = 0; tt < 4; ++tt) {
+            atomicAdd(dkp + db * 32 + j * 8 + tt, dk[db][4 * j + tt] * a.scale);
+            atomicAdd(dvp + db * 32 + j * 8 + tt, dv[db][4 * j + tt]);
+          }
+    } else {
+      const bool add = a.acc_dkdv[blk] != 0;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          f32x4 k4 = {dk[db][4 * j] * a.scale, dk[db][4 * j + 1] * a.scale, dk[db][4 * j + 2] * a.scale,
+                      dk[db][4 * j + 3] * a.scale};
+          f32x4 v4 = {dv[db][4 * j], dv[db][4 * j + 1], dv[db][4 * j + 2], dv[db][4 * j + 3]};
+          f32x4* kd = (f32x4*)(dkp + db * 32 + j * 8);
+          f32x4* vd = (f32x4*)(dvp + db * 32 + j * 8);
+          if (add) {
+            k4 += *kd;
+            v4 += *vd;
+          }
+          *kd = k4;
+          *vd = v4;
         }
+    }
   }
 }
 
@@ -528,13 +578,26 @@ int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64
   return launch_status();
 }
 
-int launch_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
-                          const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
-                          int hkv, int hs, float scale, int causal, const usp_posdesc& qpos, const usp_posdesc& kpos,
-                          int accumulate_dq, int accumulate_dkdv, hipStream_t stream) {
+int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                         const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
+                         const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,
+                         int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                         const usp_posdesc& qpos, int accumulate_dq, const int* accumulate_dkdv,
+                         hipStream_t stream) {
+  if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
   BwdArgs a;
-  a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.lse = lse; a.delta = delta;
-  a.dq = dq; a.dk = dk; a.dv = dv;
+  a.q = q; a.d_o = d_o; a.lse = lse; a.delta = delta;
+  a.dq = dq;
+  for (int j = 0; j < kMaxBlocks; ++j) {
+    const int jj = j < n_blocks ? j : 0;
+    a.k[j] = k_blocks[jj];
+    a.v[j] = v_blocks[jj];
+    a.dk[j] = dk_blocks[jj];
+    a.dv[j] = dv_blocks[jj];
+    const usp_posdesc& kp = kpos_blocks[jj];
+    a.kpos[j] = PosDesc32{(int)kp.start0, (int)kp.len0, (int)kp.start1, (int)kp.len1};
+  }
+  a.n_blocks = n_blocks;
   a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
   a.Lq = (int)Lq; a.Lk = (int)Lk;
   a.causal = causal;
@@ -542,7 +605,6 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
   a.scale = scale;
   a.scale_log2 = scale * kLog2e;
   a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
-  a.kpos = PosDesc32{(int)kpos.start0, (int)kpos.len0, (int)kpos.start1, (int)kpos.len1};
   {
     a.n_tiles = (a.Lq + 255) / 256;
     const int64_t grid = (int64_t)a.n_tiles * hq * bs;
@@ -555,22 +617,37 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
     if (st != USP_OK) return st;
   }
   {
-    // dK / dV meet through atomic adds: start from zero unless the caller accumulates
-    if (!accumulate_dkdv) {
+    a.n_tiles = (a.Lk + 255) / 256;
+    // One workgroup per (key tile, KV head) that walks all g query heads of the group writes its outputs with
+    // plain stores; when that grid would leave CUs idle, the heads are split over workgroups that meet through
+    // atomic adds, on accumulators that start from zero unless the caller accumulates.
+    const int64_t unsplit = (int64_t)a.n_tiles * hkv * bs * n_blocks;
+    a.heads_per_wg = unsplit >= 2 * 256 ? a.g : 1;
+    for (int j = 0; j < kMaxBlocks; ++j) a.acc_dkdv[j] = accumulate_dkdv[j < n_blocks ? j : 0];
+    if (a.heads_per_wg != a.g) {
       const size_t n4 = (size_t)bs * Lk * hkv * hs / 4;
       const size_t zg = (n4 + 255) / 256;
       if (zg > 0x7fffffffull) return USP_ERR_UNSUPPORTED;
-      hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dk, n4);
-      hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dv, n4);
+      for (int j = 0; j < n_blocks; ++j) {
+        if (accumulate_dkdv[j]) continue;
+        hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dk_blocks[j], n4);
+        hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dv_blocks[j], n4);
+      }
     }
-    a.accumulate = 1;
-    a.n_tiles = (a.Lk + 255) / 256;
-    const int64_t grid = (int64_t)a.n_tiles * hq * bs;
+    const int64_t grid = unsplit * (a.g / a.heads_per_wg);
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
     const int dk_st = hs == 128 ? launch_dkdv<128>(a, grid, stream) : launch_dkdv<64>(a, grid, stream);
     if (dk_st != USP_OK) return dk_st;
   }
   return launch_status();
+}
+
+int launch_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                          const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
+                          int hkv, int hs, float scale, int causal, const usp_posdesc& qpos, const usp_posdesc& kpos,
+                          int accumulate_dq, int accumulate_dkdv, hipStream_t stream) {
+  return launch_ring_attn_bwd(q, &k, &v, &kpos, 1, d_o, lse, delta, dq, &dk, &dv, bs, Lq, Lk, hq, hkv, hs, scale,
+                              causal, qpos, accumulate_dq, &accumulate_dkdv, stream);
 }
 
 int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream) {

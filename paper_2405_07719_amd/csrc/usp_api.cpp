@@ -465,19 +465,33 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
     usp_posdesc qd;
     usp_local_positions(p, r, u, nullptr, &qd);
     const float* lse_rank = lse + (size_t)rank * p->bs * hq * Lq;
-    for (int i = 0; i < R; ++i) {
-      const int s = ((r - i) % R + R) % R;
-      usp_posdesc kd;
-      usp_local_positions(p, s, u, nullptr, &kd);
-      const size_t sl = slot(s, u);
-      // dQ adds after the first ring step of this rank; dK/dV add after the first rank that touched the block
-      st = launch_block_attn_bwd(ws + f.q_head, ws + f.k_head + sl * f.kv_block_bytes,
-                                 ws + f.v_head + sl * f.kv_block_bytes, ws + f.do_head, lse_rank, delta,
-                                 (float*)(ws + f.dq_acc), (float*)(ws + f.dk_acc + sl * f.kv_acc_bytes),
-                                 (float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), p->bs, Lq, Lq, hq, hkv, p->hs, scale,
-                                 p->causal ? 1 : 0, qd, kd, i > 0 ? 1 : 0, touched[sl] ? 1 : 0, stream);
+    // The ring loop of this rank, step i on block s = (r - i) mod R: up to USP_MAX_RING_BLOCKS steps per launch
+    // pair (the dQ kernel keeps its accumulator in registers across them, the dK/dV kernel spreads them over
+    // its grid).  dQ adds after the first launch of this rank; a block's dK/dV add after the first rank that
+    // touched it.
+    for (int i0 = 0; i0 < R; i0 += USP_MAX_RING_BLOCKS) {
+      const int nb = R - i0 < USP_MAX_RING_BLOCKS ? R - i0 : USP_MAX_RING_BLOCKS;
+      const void* kb[USP_MAX_RING_BLOCKS];
+      const void* vb[USP_MAX_RING_BLOCKS];
+      float* dkb[USP_MAX_RING_BLOCKS];
+      float* dvb[USP_MAX_RING_BLOCKS];
+      usp_posdesc kds[USP_MAX_RING_BLOCKS];
+      int acc[USP_MAX_RING_BLOCKS];
+      for (int j = 0; j < nb; ++j) {
+        const int s = ((r - (i0 + j)) % R + R) % R;
+        usp_local_positions(p, s, u, nullptr, &kds[j]);
+        const size_t sl = slot(s, u);
+        kb[j] = ws + f.k_head + sl * f.kv_block_bytes;
+        vb[j] = ws + f.v_head + sl * f.kv_block_bytes;
+        dkb[j] = (float*)(ws + f.dk_acc + sl * f.kv_acc_bytes);
+        dvb[j] = (float*)(ws + f.dv_acc + sl * f.kv_acc_bytes);
+        acc[j] = touched[sl] ? 1 : 0;
+        touched[sl] = true;
+      }
+      st = launch_ring_attn_bwd(ws + f.q_head, kb, vb, kds, nb, ws + f.do_head, lse_rank, delta,
+                                (float*)(ws + f.dq_acc), dkb, dvb, p->bs, Lq, Lq, hq, hkv, p->hs, scale,
+                                p->causal ? 1 : 0, qd, i0 > 0 ? 1 : 0, acc, stream);
       if (st != USP_OK) return st;
-      touched[sl] = true;
     }
     // dQ of this rank: convert into the (now free) q_head region and send it back to the sequence layout
     st = launch_bwd_convert((const float*)(ws + f.dq_acc), ws + f.q_head, q_elems, p->dtype, stream);

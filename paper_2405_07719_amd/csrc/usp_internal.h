@@ -59,6 +59,11 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
 
 int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
                      hipStream_t stream);
+int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                         const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
+                         const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,
+                         int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                         const usp_posdesc& qpos, int accumulate_dq, const int* accumulate_dkdv, hipStream_t stream);
 int launch_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                           const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
                           int hkv, int hs, float scale, int causal, const usp_posdesc& qpos, const usp_posdesc& kpos,

@@ -25,6 +25,9 @@ BWD_CASES = [
     ("causal_ragged_gqa4", 2, 333, 333, 4, 1, 128, True, (0, 333), (0, 333), [0, 333]),
     ("zigzag_q_r1_all_keys", 1, 512, 2048, 4, 2, 128, True, (256, 256, 1536, 256), (0, 2048), [0, 700, 2048]),
     ("hs64", 1, 300, 300, 2, 2, 64, True, (0, 300), (0, 300), [0, 300]),
+    # enough (key tile, KV head, batch) units that one workgroup walks both query heads of a group and stores its
+    # dK/dV without atomics: first block overwrites, second block adds
+    ("many_kv_units_plain_stores", 4, 96, 8192, 16, 8, 128, True, (8100, 96), (0, 8192), [0, 4096, 8192]),
 ]
 
 
