@@ -162,11 +162,25 @@ int usp_attn_delta(const void* o, const void* d_o, float* delta, int bs, int64_t
  *   dq [bs,Lq,hq,hs]  (+)= scale * sum_j dS_ij k_j      dS_ij = P_ij (dO_i.v_j - delta_i)
  *   dk [bs,Lk,hkv,hs] (+)= scale * sum_i dS_ij q_i      (summed over the query heads of the KV head's group)
  *   dv [bs,Lk,hkv,hs] (+)= sum_i P_ij dO_i
- * dq, dk, dv are fp32; accumulate = 0 overwrites them, 1 adds to them (deterministic, no atomics). */
+ * dq, dk, dv are fp32; accumulate = 0 overwrites them, 1 adds to them.  dq is deterministic; dk and dv are
+ * summed over the query heads of a group either inside one workgroup (large grids) or by fp32 atomic adds of at
+ * most hq/hkv addends per element (small grids), whose rounding depends on their order. */
 int usp_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                        const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
                        int hkv, int hs, float scale, int causal, const usp_posdesc* qpos, const usp_posdesc* kpos,
                        int accumulate, void* stream);
+
+/* Backward of a rank's whole ring loop over its n_blocks resident K/V blocks in one launch pair (the backward
+ * counterpart of usp_ring_attn_fwd; same result as one usp_block_attn_bwd per block, up to rounding).
+ *   k_blocks, v_blocks, dk_blocks, dv_blocks: HOST arrays of n_blocks DEVICE pointers ([bs,Lk,hkv,hs]; bf16 inputs,
+ *   fp32 gradients); kpos_blocks: HOST array of n_blocks descriptors (may be NULL when causal == 0);
+ *   accumulate_dq: 0 overwrites dq, 1 adds; accumulate_dkdv: HOST array of n_blocks flags, per block.
+ *   1 <= n_blocks <= USP_MAX_RING_BLOCKS; the blocks' gradient buffers must not overlap. */
+int usp_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                      const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
+                      const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,
+                      int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                      const usp_posdesc* qpos, int accumulate_dq, const int* accumulate_dkdv, void* stream);
 
 /* Algorithm 1 backward (Sec. 3: the all-to-alls swap their scatter/gather roles) for virtual ranks
  * [rank_begin, rank_end); bf16 problems only.

@@ -71,11 +71,13 @@ def load():
     lib.usp_attn_delta.argtypes = [V, V, V, I, L, I, I, V]
     lib.usp_block_attn_bwd.argtypes = [V, V, V, V, V, V, V, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc), P(usp_posdesc),
                                        I, V]
+    lib.usp_ring_attn_bwd.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, V, V, P(V), P(V), I, L, L, I, I, I, F, I,
+                                      P(usp_posdesc), I, P(I), V]
     lib.usp_attn_bwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_bwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_bwd.argtypes = [P(usp_problem), V, V, V, V, V, V, V, V, V, I, I, V, C.c_size_t, V]
     lib.usp_calib_mfma.argtypes = [I, I, V, C.c_size_t, P(C.c_double), V]
-    for name in ("usp_ring_attn_fwd", "usp_calib_mfma", "usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
+    for name in ("usp_ring_attn_bwd", "usp_ring_attn_fwd", "usp_calib_mfma", "usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
                  "usp_attn_fwd", "usp_attn_bwd", "usp_attn_delta", "usp_block_attn_bwd"):
         getattr(lib, name).restype = I
     _lib = lib
@@ -187,6 +189,18 @@ def usp_calib_mfma(mode, iters, sink, stream=None):
     _check(load().usp_calib_mfma(mode, iters, _ptr(sink), sink.numel() * sink.element_size(), C.byref(flop),
                                  _stream(stream)), "usp_calib_mfma")
     return flop.value
+
+
+def usp_ring_attn_bwd(q, k_blocks, v_blocks, kpos_blocks, d_o, lse, delta, dq, dk_blocks, dv_blocks, bs, Lq, Lk, hq, hkv,
+                      hs, scale, causal, qpos, accumulate_dq, accumulate_dkdv, stream=None):
+    n = len(k_blocks)
+    arr = lambda xs: (C.c_void_p * n)(*[_ptr(x) for x in xs])
+    kd = (usp_posdesc * n)(*kpos_blocks) if kpos_blocks is not None else None
+    acc = (C.c_int * n)(*[int(bool(x)) for x in accumulate_dkdv])
+    _check(load().usp_ring_attn_bwd(_ptr(q), arr(k_blocks), arr(v_blocks), kd, n, _ptr(d_o), _ptr(lse), _ptr(delta),
+                                    _ptr(dq), arr(dk_blocks), arr(dv_blocks), bs, Lq, Lk, hq, hkv, hs, scale,
+                                    int(bool(causal)), C.byref(qpos) if qpos is not None else None,
+                                    int(bool(accumulate_dq)), acc, _stream(stream)), "usp_ring_attn_bwd")
 
 
 def usp_attn_bwd_workspace_bytes(p, n_ranks):

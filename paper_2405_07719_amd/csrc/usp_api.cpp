@@ -519,6 +519,41 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
   return USP_OK;
 }
 
+extern "C" int usp_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                                 const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
+                                 const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks,
+                                 int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                                 const usp_posdesc* qpos, int accumulate_dq, const int* accumulate_dkdv,
+                                 void* stream) {
+  if (!q || !k_blocks || !v_blocks || !d_o || !lse || !delta || !dq || !dk_blocks || !dv_blocks || !accumulate_dkdv)
+    return USP_ERR_NULL;
+  if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return USP_ERR_UNSUPPORTED;
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
+  if (hq % hkv) return USP_ERR_DEGREE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
+  if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  usp_posdesc qd = {0, Lq, 0, 0};
+  usp_posdesc kd[USP_MAX_RING_BLOCKS];
+  int acc[USP_MAX_RING_BLOCKS];
+  if (causal && (!qpos || !kpos_blocks)) return USP_ERR_NULL;
+  if (causal && !desc_ok(qpos, Lq)) return USP_ERR_SHAPE;
+  if (causal) qd = *qpos;
+  for (int j = 0; j < n_blocks; ++j) {
+    if (!k_blocks[j] || !v_blocks[j] || !dk_blocks[j] || !dv_blocks[j]) return USP_ERR_NULL;
+    kd[j] = usp_posdesc{0, Lk, 0, 0};
+    if (causal) {
+      if (!desc_ok(&kpos_blocks[j], Lk)) return USP_ERR_SHAPE;
+      kd[j] = kpos_blocks[j];
+    }
+    acc[j] = accumulate_dkdv[j] ? 1 : 0;
+  }
+  if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  return launch_ring_attn_bwd(q, k_blocks, v_blocks, kd, n_blocks, d_o, lse, delta, dq, dk_blocks, dv_blocks, bs, Lq,
+                              Lk, hq, hkv, hs, scale, causal ? 1 : 0, qd, accumulate_dq ? 1 : 0, acc,
+                              (hipStream_t)stream);
+}
+
 extern "C" int usp_calib_mfma(int mode, int iters, void* sink, size_t sink_bytes, double* flop, void* stream) {
   if (!sink || !flop) return USP_ERR_NULL;
   if (mode != 0 && mode != 1) return USP_ERR_UNSUPPORTED;

@@ -1,4 +1,4 @@
-"""GPU parity: the whole ring loop of one rank in ONE launch (usp_ring_attn_fwd) against the oracle's plain
+"""GPU parity: the whole ring loop of one rank in ONE launch (usp_ring_attn_fwd, and its backward usp_ring_attn_bwd) against the oracle's plain
 attention over the concatenated blocks, and against the stepwise path (one usp_block_attn_fwd per block, then
 usp_lse_merge), through the C ABI.  Tolerances as for the block kernel: O 2e-2, LSE 1e-3 (max-abs)."""
 import numpy as np
@@ -108,3 +108,45 @@ def test_ring_attn_fwd_rejects_bad_arguments(usp):
                               tl.BF16, tl.BF16)
     with pytest.raises(usp.UspError):                       # causal without descriptors
         usp.usp_ring_attn_fwd(x, [x], [x], None, x, l, 1, 8, 8, 1, 1, 128, 0.0, True, qd, tl.BF16, tl.BF16)
+
+
+def test_ring_attn_bwd_matches_per_block_calls(usp):
+    """The ring loop's backward in one launch pair against one usp_block_attn_bwd per block (same kernels, so the
+    agreement is tight: only the order of the fp32 additions into dQ and the atomics differ)."""
+    bs, L, hq, hkv, hs, R, r = 1, 2048, 4, 2, 128, 4, 2
+    order = (2, 1, 0, 3)
+    q, kb, vb, kd, qd, _, _ = _ring_case(usp, 91, bs, L, hq, hkv, hs, R, r, True, True, order)
+    Lq = L // R
+    d_o = torch.randn((bs, Lq, hq, hs), device="cuda").bfloat16()
+    o = torch.empty_like(q)
+    lse = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
+    usp.usp_ring_attn_fwd(q, kb, vb, kd, o, lse, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, tl.BF16, tl.BF16)
+    delta = torch.empty_like(lse)
+    usp.usp_attn_delta(o, d_o, delta, bs, Lq, hq, hs)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    dq = torch.full((bs, Lq, hq, hs), float("nan"), **f32)
+    dk = [torch.full((bs, Lq, hkv, hs), float("nan"), **f32) for _ in order]
+    dv = [torch.full((bs, Lq, hkv, hs), float("nan"), **f32) for _ in order]
+    usp.usp_ring_attn_bwd(q, kb, vb, kd, d_o, lse, delta, dq, dk, dv, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, False,
+                          [False] * len(order))
+    dq2 = torch.full_like(dq, float("nan"))
+    # the single-block call has one flag for all three outputs: dq adds from the second block on, so the later
+    # blocks' (fresh) dk/dv buffers start at zero, the first block's at NaN to show that it is overwritten
+    dk2 = [torch.full_like(x, float("nan") if i == 0 else 0.0) for i, x in enumerate(dk)]
+    dv2 = [torch.full_like(x, float("nan") if i == 0 else 0.0) for i, x in enumerate(dv)]
+    for i in range(len(order)):
+        usp.usp_block_attn_bwd(q, kb[i], vb[i], d_o, lse, delta, dq2, dk2[i], dv2[i], bs, Lq, Lq, hq, hkv, hs, 0.0, True,
+                               qd, kd[i], i > 0)
+    torch.cuda.synchronize()
+    assert torch.allclose(dq, dq2, atol=2e-5, rtol=1e-5)
+    for a, b in zip(dk + dv, dk2 + dv2):
+        assert not torch.isnan(a).any()
+        assert torch.allclose(a, b, atol=2e-5, rtol=1e-5)
+    # a second launch that adds doubles dK/dV and dQ
+    usp.usp_ring_attn_bwd(q, kb, vb, kd, d_o, lse, delta, dq, dk, dv, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, True,
+                          [True] * len(order))
+    torch.cuda.synchronize()
+    assert torch.allclose(dq, 2 * dq2, atol=4e-5, rtol=1e-5)
+    assert torch.allclose(dk[1], 2 * dk2[1], atol=4e-5, rtol=1e-5)
+    with pytest.raises(usp.UspError):
+        usp.usp_ring_attn_bwd(q, [], [], [], d_o, lse, delta, dq, [], [], bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, False, [])
