@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # rocprofv3 --pmc FETCH_SIZE (x2, the factor a plain copy of known size gives) + WRITE_SIZE, KiB -> bytes, per
 # launch of the block-attention kernel
 # (FETCH_SIZE 217999 KiB; copy calibration: a 524288 KiB copy reads FETCH_SIZE 262158, WRITE_SIZE 524288)
-MEASURED_CLOCK_GHZ = 2.07   # block_attn_fwd_mfma on the default workload, see profiles/clock_cycles_ulysses8_L32768.md
-MEASURED_TRAFFIC_BYTES = {"ulysses8_L32768": round((217999 * (524288 / 262158) + 36352 * (524288 / 524288)) * 1024.0)}
+MEASURED_CLOCK_GHZ = 2.06   # block_attn_fwd_mfma on the default workload, see profiles/clock_cycles_ulysses8_L32768.md
+MEASURED_TRAFFIC_BYTES = {"ulysses8_L32768": round((218596 * (524288 / 262158) + 33280 * (524288 / 524288)) * 1024.0)}
 
 WORKLOADS = {
     # name: (bs, L, hc, hk, hs, U, R, timed rank)

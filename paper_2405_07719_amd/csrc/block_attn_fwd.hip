@@ -479,16 +479,6 @@ int launch_fp32(AttnArgs a, hipStream_t stream) {
 
 }  // namespace
 
-// Tile configuration of the bf16 instance; the environment variable is a tuning aid for sweeps.
-static int mfma_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("USP_ATTN_VARIANT");
-    v = e ? atoi(e) : 0;
-  }
-  return v;
-}
-
 int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
@@ -516,19 +506,10 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
     if (hs == 128) return o_dtype == USP_FP32 ? launch_fp32<128, float>(a, stream) : launch_fp32<128, __bf16>(a, stream);
     return o_dtype == USP_FP32 ? launch_fp32<64, float>(a, stream) : launch_fp32<64, __bf16>(a, stream);
   }
-  const int var = mfma_variant();
-#define USP_VARIANT(id, NQB, NW, KT, WPE)                                                       \
-  if (var == id)                                                                                \
-    return o_dtype == USP_FP32 ? launch_mfma<128, NQB, NW, KT, WPE, float>(a, stream)           \
-                               : launch_mfma<128, NQB, NW, KT, WPE, __bf16>(a, stream);
-  if (hs == 128) {
-    USP_VARIANT(2, 1, 4, 64, 1)   // 128-row tiles, one wave per SIMD
-    USP_VARIANT(3, 1, 4, 64, 2)   // 128-row tiles, two workgroups per CU
-    USP_VARIANT(5, 1, 8, 32, 2)   // 32-key tiles
+  // 256 query rows per workgroup (8 waves x 32), 64-key tiles, two waves per SIMD
+  if (hs == 128)
     return o_dtype == USP_FP32 ? launch_mfma<128, 1, 8, 64, 2, float>(a, stream)
                                : launch_mfma<128, 1, 8, 64, 2, __bf16>(a, stream);
-  }
-#undef USP_VARIANT
   if (o_dtype == USP_FP32) return launch_mfma<64, 1, 8, 64, 2, float>(a, stream);
   return launch_mfma<64, 1, 8, 64, 2, __bf16>(a, stream);
 }
