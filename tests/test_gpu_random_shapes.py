@@ -1,0 +1,105 @@
+"""GPU parity on randomly drawn shapes and position descriptors (seeded): ragged lengths, arbitrary two-run
+descriptors whose runs are not aligned to any tile size and may be out of order, GQA groups, both head sizes,
+one to five K/V blocks per launch.  Forward against the oracle's plain attention, backward against its gradient.
+Tolerances as everywhere: O 2e-2, LSE 1e-3, gradients 5e-2 (max-abs)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import usp_oracle as orc
+from paper_2405_07719_amd import inputs
+from tests import usp_testlib as tl
+
+pytestmark = pytest.mark.gpu
+
+
+def _random_desc(rng, usp, n, span):
+    """n local indices in one or two ascending runs placed anywhere in [0, span) without overlap."""
+    if n == 1 or rng.random() < 0.3:
+        s0 = int(rng.integers(0, span - n + 1))
+        return usp.usp_posdesc(s0, n, 0, 0)
+    n0 = int(rng.integers(1, n))
+    n1 = n - n0
+    # two disjoint intervals, in either order
+    lo_len, hi_len = (n0, n1) if rng.random() < 0.5 else (n1, n0)
+    lo = int(rng.integers(0, span - n + 1))
+    hi = int(rng.integers(lo + lo_len, span - hi_len + 1))
+    if lo_len == n0 and rng.random() < 0.7:
+        return usp.usp_posdesc(lo, n0, hi, n1)          # ascending overall (the Algorithm-2 case)
+    return usp.usp_posdesc(hi, hi_len, lo, lo_len) if hi_len == n0 else usp.usp_posdesc(lo, n0, hi, n1)
+
+
+def _draw(rng, usp, max_len):
+    hs = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 3]))
+    g = int(rng.choice([1, 2, 4]))
+    bs = int(rng.choice([1, 2]))
+    Lq = int(rng.integers(1, max_len))
+    Lk = int(rng.integers(1, max_len))
+    nb = int(rng.integers(1, 6))
+    causal = bool(rng.random() < 0.8)
+    span = 4 * max_len
+    qd = _random_desc(rng, usp, Lq, span)
+    kds = [_random_desc(rng, usp, Lk, span) for _ in range(nb)]
+    return bs, Lq, Lk, hkv * g, hkv, hs, nb, causal, qd, kds
+
+
+def _tensors(seed, bs, Lq, Lk, hq, hkv, hs, nb):
+    qs, qv = tl.gen(seed, inputs.TENSOR_Q, bs, np.arange(Lq), np.arange(hq), hs, tl.BF16)
+    ks, kv = tl.gen(seed, inputs.TENSOR_K, bs, np.arange(nb * Lk), np.arange(hkv), hs, tl.BF16)
+    vs, vv = tl.gen(seed, inputs.TENSOR_V, bs, np.arange(nb * Lk), np.arange(hkv), hs, tl.BF16)
+    return qs, qv, ks, kv, vs, vv
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_ring_fwd_random_shapes(usp, seed):
+    rng = np.random.default_rng(1000 + seed)
+    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = _draw(rng, usp, 700)
+    qs, qv, ks, kv, vs, vv = _tensors(seed, bs, Lq, Lk, hq, hkv, hs, nb)
+    qpos = np.array(qd.positions()) if causal else np.arange(Lq)
+    kpos = np.concatenate([np.array(d.positions()) for d in kds]) if causal else np.arange(nb * Lk)
+    ref_o, ref_l = orc.block_attention(qv, kv, vv, qpos, kpos, causal, None)
+    q = tl.to_device(qs, tl.BF16)
+    kb = [tl.to_device(ks[:, j * Lk:(j + 1) * Lk], tl.BF16) for j in range(nb)]
+    vb = [tl.to_device(vs[:, j * Lk:(j + 1) * Lk], tl.BF16) for j in range(nb)]
+    o = torch.full((bs, Lq, hq, hs), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((bs, hq, Lq), float("nan"), dtype=torch.float32, device="cuda")
+    usp.usp_ring_attn_fwd(q, kb, vb, kds if causal else None, o, lse, bs, Lq, Lk, hq, hkv, hs, 0.0, causal,
+                          qd if causal else None, tl.BF16, tl.FP32)
+    torch.cuda.synchronize()
+    got_o, got_l = tl.to_f64(o), tl.to_f64(lse)
+    assert not np.isnan(got_o).any() and not np.isnan(got_l).any()
+    tl.assert_lse_close(got_l, ref_l, 1e-3)
+    assert tl.max_abs(got_o, ref_o) <= 2e-2
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_ring_bwd_random_shapes(usp, seed):
+    rng = np.random.default_rng(5000 + seed)
+    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = _draw(rng, usp, 400)
+    qs, qv, ks, kv, vs, vv = _tensors(100 + seed, bs, Lq, Lk, hq, hkv, hs, nb)
+    gs, gv = tl.gen(100 + seed, inputs.TENSOR_DO, bs, np.arange(Lq), np.arange(hq), hs, tl.BF16)
+    qpos = np.array(qd.positions()) if causal else np.arange(Lq)
+    kpos = np.concatenate([np.array(d.positions()) for d in kds]) if causal else np.arange(nb * Lk)
+    ref_dq, ref_dk, ref_dv = orc.attention_backward(qv, kv, vv, gv, causal, None, qpos, kpos)
+    q, d_o = tl.to_device(qs, tl.BF16), tl.to_device(gs, tl.BF16)
+    kb = [tl.to_device(ks[:, j * Lk:(j + 1) * Lk], tl.BF16) for j in range(nb)]
+    vb = [tl.to_device(vs[:, j * Lk:(j + 1) * Lk], tl.BF16) for j in range(nb)]
+    o = torch.empty((bs, Lq, hq, hs), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
+    usp.usp_ring_attn_fwd(q, kb, vb, kds if causal else None, o, lse, bs, Lq, Lk, hq, hkv, hs, 0.0, causal,
+                          qd if causal else None, tl.BF16, tl.BF16)
+    delta = torch.empty_like(lse)
+    usp.usp_attn_delta(o, d_o, delta, bs, Lq, hq, hs)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    dq = torch.full((bs, Lq, hq, hs), float("nan"), **f32)
+    dk = [torch.full((bs, Lk, hkv, hs), float("nan"), **f32) for _ in range(nb)]
+    dv = [torch.full((bs, Lk, hkv, hs), float("nan"), **f32) for _ in range(nb)]
+    usp.usp_ring_attn_bwd(q, kb, vb, kds if causal else None, d_o, lse, delta, dq, dk, dv, bs, Lq, Lk, hq, hkv, hs, 0.0,
+                          causal, qd if causal else None, False, [False] * nb)
+    torch.cuda.synchronize()
+    got_dk = np.concatenate([tl.to_f64(x) for x in dk], axis=1)
+    got_dv = np.concatenate([tl.to_f64(x) for x in dv], axis=1)
+    for name, got, ref in (("dq", tl.to_f64(dq), ref_dq), ("dk", got_dk, ref_dk), ("dv", got_dv, ref_dv)):
+        assert not np.isnan(got).any(), name
+        assert tl.max_abs(got, ref) <= 5e-2, name
