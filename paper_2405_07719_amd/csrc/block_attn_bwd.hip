@@ -9,9 +9,11 @@
 // Two kernels, both on v_mfma_f32_32x32x16_bf16 with fp32 accumulation:
 //   dq_kernel    a workgroup owns 256 query rows, walks the visible key tiles:  S^T = K Q^T, dP^T = V dO^T
 //                (lane = query, so L_i and D_i are per-lane scalars), dQ^T += K^T dS^T.  Deterministic.
-//   dkdv_kernel  a workgroup owns 256 keys of one KV head and one query head, walks the visible query
-//                tiles:  S = Q K^T, dP = dO V^T (lane = key; L_i, D_i read from LDS), dV^T += dO^T P,
-//                dK^T += Q^T dS; the query heads of a group are summed with fp32 atomic adds.
+//   dkdv_kernel  a workgroup owns 256 keys of one KV head and walks the visible query tiles of one query
+//                head, or of all query heads of the group when the grid is large enough without splitting them:
+//                S = Q K^T, dP = dO V^T (lane = key; L_i and D_i enter through one extra MFMA k-step),
+//                dV^T += dO^T P, dK^T += Q^T dS; split heads meet through fp32 atomic adds.
+// Both take up to USP_MAX_RING_BLOCKS K/V blocks per launch (the ring loop of one rank).
 // In both, the accumulator layout of the first product is the B-operand layout of the second, and the
 // transposed A operands come from LDS transpose reads of the same tile copy: a row stride of 2*hs + 48 bytes is
 // free of bank conflicts for the 16 B row reads and for the transpose reads alike.

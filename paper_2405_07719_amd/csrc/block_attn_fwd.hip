@@ -1,6 +1,6 @@
-// One ring step of blockwise attention (Sec. 2: SP-Ring's blockwise loop; Eq. 1 restricted to
-// one K/V block): S = scale * Q K^T -> position mask -> online softmax over key tiles -> P V,
-// returning the partial O and the per-row log-sum-exp.
+// Blockwise attention (Sec. 2: SP-Ring's blockwise loop; Eq. 1 restricted to the K/V blocks given):
+// S = scale * Q K^T -> position mask -> online softmax over key tiles -> P V, returning O (the partial O of
+// one ring step, or the final O when the launch covers the whole ring loop) and the per-row log-sum-exp.
 //
 // gfx950 design (bf16 instance)
 //   * MFMA v_mfma_f32_32x32x16_bf16, fp32 accumulation.  The score tile is computed TRANSPOSED,
