@@ -63,8 +63,9 @@ def event_ms(fn, iters):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30,
+                    help="untimed steps first: the clock of an idle chip needs a few tens of ms of load to settle")
     ap.add_argument("--workload", default="ulysses8_L32768", choices=sorted(WORKLOADS))
     ap.add_argument("--rank", type=int, default=None,
                     help="virtual rank to time (default: ring rank 0, Ulysses rank 0; ring rank R-1 has the same pair "

@@ -51,7 +51,19 @@ struct AttnArgs {
   float scale_log2;   // scale * log2(e)
   PosDesc32 qpos;
   PosDesc32 kpos[kMaxBlocks];
+  // Where Q rows are read and O rows written.  seq_n == 0: dense [bs,Lq,hq,hs] (the layout after the forward
+  // all-to-all).  seq_n > 0: straight from / to the sequence-layout shards of the rank's Ulysses group,
+  // [U][bs][seq_n][seq_heads][hs] with this rank's heads at seq_head0: the all-to-all of Q (Algorithm 1 step 2)
+  // and of O (step 6) folded into the one read of Q and the one write of O that the kernel does anyway.
+  int seq_n, seq_heads, seq_head0;
 };
+
+// element offset of (batch b, local row, local head h) in the Q / O tensor
+__device__ inline size_t qo_offset(const AttnArgs& a, int b, int row, int h, int hs) {
+  if (a.seq_n == 0) return (((size_t)b * a.Lq + row) * a.hq + h) * hs;
+  const int shard = row / a.seq_n, s = row - shard * a.seq_n;
+  return ((((size_t)shard * a.bs + b) * a.seq_n + s) * a.seq_heads + a.seq_head0 + h) * hs;
+}
 
 // -------------------------------------------------------------------------------------------
 // bf16 MFMA kernel, software pipelined: while the softmax of key tile j runs on the vector ALU,
@@ -108,7 +120,7 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     qrow[qb] = wave_row0 + qb * 32 + l32;
     const int rr = min(qrow[qb], a.Lq - 1);
     qp[qb] = a.causal ? pos_of(a.qpos, rr) : 0;
-    const __bf16* src = qg + (((size_t)b * a.Lq + rr) * a.hq + h) * HS + 8 * hl;
+    const __bf16* src = qg + qo_offset(a, b, rr, h, HS) + 8 * hl;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
   }
@@ -357,7 +369,7 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     const float l_tot = both_halves_sum(l_run[qb]);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (qrow[qb] < a.Lq) {
-      OutT* dst = (OutT*)a.o + (((size_t)b * a.Lq + qrow[qb]) * a.hq + h) * HS + 4 * hl;
+      OutT* dst = (OutT*)a.o + qo_offset(a, b, qrow[qb], h, HS) + 4 * hl;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -482,10 +494,13 @@ int launch_fp32(AttnArgs a, hipStream_t stream) {
 int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
-                         int in_dtype, int o_dtype, hipStream_t stream) {
+                         int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq) {
   if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
-  if (in_dtype == USP_FP32 && n_blocks != 1) return USP_ERR_UNSUPPORTED;
+  if (in_dtype == USP_FP32 && (n_blocks != 1 || seq)) return USP_ERR_UNSUPPORTED;
   AttnArgs a;
+  a.seq_n = seq ? seq->rows_per_shard : 0;
+  a.seq_heads = seq ? seq->heads : 0;
+  a.seq_head0 = seq ? seq->head0 : 0;
   a.q = q; a.o = o; a.lse = lse;
   for (int j = 0; j < kMaxBlocks; ++j) {
     const int jj = j < n_blocks ? j : 0;

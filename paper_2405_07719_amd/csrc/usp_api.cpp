@@ -280,7 +280,6 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
   const int hq = p->hc / U, hkv = p->hk / U;
   const float scale = p->scale == 0.0f ? 1.0f / sqrtf((float)p->hs) : p->scale;
 
-  (void)es;
 
   // Steps 3-4 of Algorithm 1 for every K/V block the ranks in range will visit.  The workspace slot of
   // block (r, u) is r * n_cols + (u - c0): with all U columns that is the rank order (one launch per
@@ -290,9 +289,11 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
 
   for (int rank = rank_begin; rank < rank_end; ++rank) {
     const int r = rank / U, u = rank % U;
-    // Step 2: Q of this rank to head layout.
-    st = launch_layout_a2a(*p, p->hc, USP_SEQ_TO_HEAD, q, ws + f.q_head, rank, rank + 1, rank, stream);
-    if (st != USP_OK) return st;
+    // Step 2: Q of this rank to head layout (the one-launch ring loop reads the shards itself).
+    if (!ring_in_one_launch(*p)) {
+      st = launch_layout_a2a(*p, p->hc, USP_SEQ_TO_HEAD, q, ws + f.q_head, rank, rank + 1, rank, stream);
+      if (st != USP_OK) return st;
+    }
     usp_posdesc qd;
     usp_local_positions(p, r, u, nullptr, &qd);
     float* lse_rank = lse + (size_t)rank * p->bs * hq * Lq;
@@ -308,10 +309,12 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
         kb[i] = ws + f.k_head + slot;
         vb[i] = ws + f.v_head + slot;
       }
-      st = launch_ring_attn_fwd(ws + f.q_head, kb, vb, kds, R, ws + f.o_head, lse_rank, p->bs, Lq, Lq, hq, hkv, p->hs,
-                                scale, p->causal ? 1 : 0, qd, p->dtype, p->dtype, stream);
-      if (st != USP_OK) return st;
-      st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.o_head, o, rank, rank + 1, rank, stream);
+      // Steps 2 and 6 for Q and O ride on the kernel's own accesses: it reads each Q row once and writes each O
+      // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
+      const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
+      const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * es;
+      st = launch_ring_attn_fwd((const char*)q + group_off, kb, vb, kds, R, (char*)o + group_off, lse_rank, p->bs, Lq,
+                                Lq, hq, hkv, p->hs, scale, p->causal ? 1 : 0, qd, p->dtype, p->dtype, stream, &seq);
       if (st != USP_OK) return st;
       continue;
     }
