@@ -78,8 +78,8 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   constexpr int DB = HS / 32;              // 32-wide head-dim blocks of O^T
   constexpr int KB = KT / 32;              // 32-key blocks of S^T
   constexpr int PS = KT / 16;              // MFMA k-steps of P V
-  constexpr int KSTR = HS * 2 + 48;        // LDS row stride of K in bytes: conflict-free 16 B row reads (measured)
-  constexpr int VSTR = KSTR;                // the same stride is conflict-free for the transpose reads of V (measured)
+  constexpr int KSTR = HS * 2 + 48;        // LDS row stride of K in bytes: an odd number of 16 B chunks, no bank conflicts on the row reads
+  constexpr int VSTR = HS * 2 + 64;        // V rows: an odd multiple of 64 B, no bank conflicts on the transpose reads
   constexpr int KBYTES = KT * KSTR, VBYTES = KT * VSTR;
   constexpr int CHUNKS = KT * HS / 8;      // 16 B chunks per tile (K and V alike)
   constexpr int CPT = CHUNKS / NT;         // chunks per thread
@@ -464,7 +464,7 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
 template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
 int launch_mfma(AttnArgs a, hipStream_t stream) {
   constexpr int BM = NWAVES * NQB * 32;
-  constexpr int KSTR = HS * 2 + 48, VSTR = KSTR;
+  constexpr int KSTR = HS * 2 + 48, VSTR = HS * 2 + 64;
   constexpr size_t lds = 2 * (size_t)KT * (KSTR + VSTR);
   a.n_qtiles = (a.Lq + BM - 1) / BM;
   const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs;
