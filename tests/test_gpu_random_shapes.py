@@ -103,3 +103,46 @@ def test_ring_bwd_random_shapes(usp, seed):
     for name, got, ref in (("dq", tl.to_f64(dq), ref_dq), ("dk", got_dk, ref_dk), ("dv", got_dv, ref_dv)):
         assert not np.isnan(got).any(), name
         assert tl.max_abs(got, ref) <= 5e-2, name
+
+
+@pytest.mark.parametrize("gain", [8.0, 0.015625])
+def test_ring_fwd_bwd_extreme_logit_scales(usp, gain):
+    """Logits with a standard deviation of ~64 (sharp softmax, exp of the raw scores would overflow) and of ~2e-4
+    (flat softmax): the running-maximum handling and the statistics of the backward must hold up.  K is scaled by an
+    exact power of two, so the bf16 inputs stay exact."""
+    bs, Lq, Lk, hq, hkv, hs, nb = 1, 520, 384, 4, 2, 128, 3
+    qs, qv, ks, kv, vs, vv = _tensors(9, bs, Lq, Lk, hq, hkv, hs, nb)
+    gs, gv = tl.gen(9, inputs.TENSOR_DO, bs, np.arange(Lq), np.arange(hq), hs, tl.BF16)
+    scale_q = gain * 8.0 if gain > 1 else 1.0
+    qv, kv = qv * scale_q, kv * gain
+    q = (tl.to_device(qs, tl.BF16).float() * scale_q).bfloat16()
+    k_all = (tl.to_device(ks, tl.BF16).float() * gain).bfloat16()
+    d_o = tl.to_device(gs, tl.BF16)
+    qd = usp.usp_posdesc(700, Lq, 0, 0)
+    kds = [usp.usp_posdesc(j * Lk, Lk, 0, 0) for j in range(nb)]
+    qpos = np.array(qd.positions())
+    kpos = np.concatenate([np.array(d.positions()) for d in kds])
+    ref_o, ref_l = orc.block_attention(qv, kv, vv, qpos, kpos, True, None)
+    ref_dq, ref_dk, ref_dv = orc.attention_backward(qv, kv, vv, gv, True, None, qpos, kpos)
+    kb = [k_all[:, j * Lk:(j + 1) * Lk].contiguous() for j in range(nb)]
+    vb = [tl.to_device(vs[:, j * Lk:(j + 1) * Lk], tl.BF16) for j in range(nb)]
+    o = torch.empty((bs, Lq, hq, hs), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
+    usp.usp_ring_attn_fwd(q, kb, vb, kds, o, lse, bs, Lq, Lk, hq, hkv, hs, 0.0, True, qd, tl.BF16, tl.BF16)
+    delta = torch.empty_like(lse)
+    usp.usp_attn_delta(o, d_o, delta, bs, Lq, hq, hs)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    dq = torch.full((bs, Lq, hq, hs), float("nan"), **f32)
+    dk = [torch.full((bs, Lk, hkv, hs), float("nan"), **f32) for _ in range(nb)]
+    dv = [torch.full((bs, Lk, hkv, hs), float("nan"), **f32) for _ in range(nb)]
+    usp.usp_ring_attn_bwd(q, kb, vb, kds, d_o, lse, delta, dq, dk, dv, bs, Lq, Lk, hq, hkv, hs, 0.0, True, qd, False,
+                          [False] * nb)
+    torch.cuda.synchronize()
+    tl.assert_lse_close(tl.to_f64(lse), ref_l, 1e-3 * max(1.0, float(np.max(np.abs(ref_l[np.isfinite(ref_l)]))) / 16))
+    assert tl.max_abs(tl.to_f64(o), ref_o) <= 2e-2
+    got_dk = np.concatenate([tl.to_f64(x) for x in dk], axis=1)
+    got_dv = np.concatenate([tl.to_f64(x) for x in dv], axis=1)
+    # gradients scale with the inputs' magnitudes: tolerance relative to the largest reference entry
+    for name, got, ref in (("dq", tl.to_f64(dq), ref_dq), ("dk", got_dk, ref_dk), ("dv", got_dv, ref_dv)):
+        assert not np.isnan(got).any(), name
+        assert tl.max_abs(got, ref) <= 5e-2 * max(1.0, float(np.max(np.abs(ref)))), name
