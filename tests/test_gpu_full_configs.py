@@ -111,3 +111,42 @@ def test_full_size_training_rank_config5(usp):
     assert np.max(np.abs(dk_sum)) <= 2e-3 * dk_abs
     # nothing outside this rank's slices was written
     assert float(dq[:, :, :, case.hq:].abs().max()) == 0.0 and float(dk[:, :, :, case.hkv:].abs().max()) == 0.0
+
+
+def test_full_size_backward_ulysses_rank_config2(usp):
+    """The backward that bench.py times on its default workload: the Ulysses-8 rank of L = 32768 (one KV head per
+    rank, so the dK/dV workgroups split the four query heads of the group and meet through atomic adds)."""
+    L, U, R, rank = 32768, 8, 1, 0
+    case = tl.OneRankCase(usp, 1002, 1, L, 32, 8, 128, U, R, rank, with_do=True)
+    case.forward()
+    rng = np.random.default_rng(2)
+    rows = case.sample_rows(rng, 48)
+    kv, vv = _check_forward_rows(case, rows)
+    p = case.p
+    dq, dk, dv = torch.zeros_like(case.q), torch.zeros_like(case.k), torch.zeros_like(case.v)
+    ws = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, 1), dtype=torch.uint8, device="cuda")
+    usp.usp_attn_bwd(p, case.q, case.k, case.v, case.o, case.lse, case.d_o, dq, dk, dv, rank, rank + 1, ws)
+    torch.cuda.synchronize()
+    qs = slice(case.u * case.hq, (case.u + 1) * case.hq)
+    ks = slice(case.u * case.hkv, (case.u + 1) * case.hkv)
+    allpos = np.arange(L)
+    pos = case.block_pos[rows]
+    qv = case.values(inputs.TENSOR_Q, pos, case.q_heads)
+    gv = case.values(inputs.TENSOR_DO, pos, case.q_heads)
+    ref_dq, _, _ = orc.attention_backward(qv, kv, vv, gv, True, None, pos, allpos)
+    assert tl.max_abs(case.seq_rows(dq, rows, qs), ref_dq) <= GRAD_TOL
+    # dK, dV of the last 128 keys: only the last 128 queries see them, and with R = 1 the rank holds every query
+    last = np.arange(L - 128, L)
+    ql = case.values(inputs.TENSOR_Q, last, case.q_heads)
+    gl = case.values(inputs.TENSOR_DO, last, case.q_heads)
+    _, ref_dk, ref_dv = orc.attention_backward(ql, kv, vv, gl, True, None, last, allpos)
+    assert tl.max_abs(tl.to_f64(dk[U - 1, :, -128:, ks, :]), ref_dk[:, -128:]) <= GRAD_TOL
+    assert tl.max_abs(tl.to_f64(dv[U - 1, :, -128:, ks, :]), ref_dv[:, -128:]) <= GRAD_TOL
+    # sum_j dV_j = sum_i dO_i over the group's heads; sum_j dK_j = 0 (exact in real arithmetic)
+    g = case.hq // case.hkv
+    dv_sum = dv[:, :, :, ks, :].double().sum(dim=(0, 2)).cpu().numpy()
+    do_sum = case.d_o[:, :, :, qs, :].double().sum(dim=(0, 2)).cpu().numpy().reshape(1, case.hkv, g, case.hs).sum(axis=2)
+    assert np.max(np.abs(dv_sum - do_sum)) <= 0.02 * np.sqrt(case.Lq * g)
+    dk_sum = dk[:, :, :, ks, :].double().sum(dim=(0, 2)).cpu().numpy()
+    dk_abs = float(dk[:, :, :, ks, :].double().abs().sum(dim=(0, 2)).max())
+    assert np.max(np.abs(dk_sum)) <= 2e-3 * dk_abs
