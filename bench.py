@@ -9,8 +9,8 @@ Default workload (the configuration the headline metric is quoted on): the Ulyss
 of a LLaMA-3-8B-shaped attention, bs=1, L=32768, 32 Q heads / 8 KV heads, head size 128, bf16,
 causal, Ulysses 8 x ring 1: rank 0 holds 4 Q heads + 1 KV head over the full sequence.
 
-Prints ONE JSON line: whole-step throughput in causal-effective TFLOP/s (4*hs flop per visible
-(query, key) pair), the dominant kernel's roofline (block attention vs the bf16 dense MFMA peak),
+Prints ONE JSON line: whole-step throughput in TFLOP/s (4*hs flop per visible (query, key) pair:
+causal-effective under the mask), the dominant kernel's roofline (block attention vs the bf16 dense MFMA peak),
 the HBM-bound kernels' GB/s, and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -36,16 +36,24 @@ MEASURED_CLOCK_GHZ = 2.06   # block_attn_fwd_mfma on the default workload, see p
 MEASURED_TRAFFIC_BYTES = {"ulysses8_L32768": round((218596 * (524288 / 262158) + 33280 * (524288 / 524288)) * 1024.0)}
 
 WORKLOADS = {
-    # name: (bs, L, hc, hk, hs, U, R, timed rank)
-    "ulysses8_L32768": (1, 32768, 32, 8, 128, 8, 1, 0),
-    "ring8_L32768": (1, 32768, 32, 8, 128, 1, 8, 0),
-    "hybrid_u8r2_L212992": (1, 212992, 32, 8, 128, 8, 2, 0),
-    "train_u2r4_L65536": (1, 65536, 32, 8, 128, 2, 4, 0),
+    # name: (bs, L, hc, hk, hs, U, R, timed rank, causal)
+    "ulysses8_L32768": (1, 32768, 32, 8, 128, 8, 1, 0, True),
+    "ring8_L32768": (1, 32768, 32, 8, 128, 1, 8, 0, True),
+    "hybrid_u8r2_L212992": (1, 212992, 32, 8, 128, 8, 2, 0, True),
+    "train_u2r4_L65536": (1, 65536, 32, 8, 128, 2, 4, 0, True),
+    # the other head structures of the paper's benchmarks (parity cases with a throughput figure beside them)
+    "mha_u8_L32768": (1, 32768, 32, 32, 128, 8, 1, 0, True),         # LLAMA2-7B-like: every Q head has its own KV head
+    "mqa_ring8_L32768": (1, 32768, 32, 1, 128, 1, 8, 0, True),       # one KV head: Ulysses cannot split it, ring only
+    "noncausal_u8_L32768": (1, 32768, 32, 8, 128, 8, 1, 0, False),   # bidirectional (DiT-style) attention
+    "hs64_u8_L32768": (1, 32768, 32, 8, 64, 8, 1, 0, True),          # head size 64
 }
 
 
-def causal_pairs_per_head(L, R):
-    """Visible (query, key) pairs of one ring rank's rows under the zigzag split: c^2 (2R-1) + c (c+1)."""
+def pairs_per_head(L, R, causal):
+    """Visible (query, key) pairs of one ring rank's rows: every key without a mask, c^2 (2R-1) + c (c+1) under
+    the causal mask with the zigzag split."""
+    if not causal:
+        return (L // R) * L
     c = L // (2 * R)
     return c * c * (2 * R - 1) + c * (c + 1)
 
@@ -90,7 +98,7 @@ def main():
 
     usp.load()   # no fallback: raises if the HIP library is missing
     torch.cuda.set_device(0)
-    bs, L, hc, hk, hs, U, R, rank = WORKLOADS[args.workload]
+    bs, L, hc, hk, hs, U, R, rank, causal = WORKLOADS[args.workload]
     N = U * R
     if args.rank is not None:
         if not 0 <= args.rank < N:
@@ -98,7 +106,7 @@ def main():
             sys.exit(2)
         rank = args.rank
     seed = 1001
-    p = usp.problem(bs, L, hc, hk, hs, U, R, True, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
+    p = usp.problem(bs, L, hc, hk, hs, U, R, causal, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
     r, u = divmod(rank, U)
     hq, hkv, Lq, n = hc // U, hk // U, L // R, L // N
 
@@ -142,7 +150,7 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    pairs = causal_pairs_per_head(L, R)
+    pairs = pairs_per_head(L, R, causal)
     flop = 4.0 * hs * pairs * hq * bs
     value = flop / (ms_per_step * 1e-3) / 1e12
 
@@ -163,7 +171,7 @@ def main():
     v_blocks = [vh[(r - i) % R] for i in range(R)]
 
     def attn_only():      # what the step launches: the rank's whole ring loop, R resident blocks, one launch
-        usp.usp_ring_attn_fwd(qh, k_blocks, v_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd,
+        usp.usp_ring_attn_fwd(qh, k_blocks, v_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, causal, qd,
                               usp.USP_BF16, usp.USP_BF16)
 
     for _ in range(args.warmup):
@@ -179,7 +187,7 @@ def main():
         def attn_stepwise():
             for i in range(R):
                 usp.usp_block_attn_fwd(qh, k_blocks[i], v_blocks[i], o_parts[i], l_parts[i], bs, Lq, Lq, hq, hkv, hs,
-                                       0.0, True, qd, kds[i], usp.USP_BF16, usp.USP_FP32)
+                                       0.0, causal, qd, kds[i], usp.USP_BF16, usp.USP_FP32)
             usp.usp_lse_merge(o_parts, l_parts, o_ring, l_ring, bs, Lq, hq, hs, usp.USP_FP32, usp.USP_BF16)
         attn_stepwise()
         sms = event_ms(attn_stepwise, max(3, args.steps // 2))
@@ -207,7 +215,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "prewarm_ms": PREWARM_MS, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "bs": bs, "L": L, "hc": hc, "hk": hk, "hs": hs, "ulysses": U, "ring": R,
-                   "causal": True, "split": "zigzag", "timed_rank": rank, "flop_per_step": flop},
+                   "causal": causal, "split": "zigzag", "timed_rank": rank, "flop_per_step": flop},
         "roofline": roofline,
     }
 
@@ -303,15 +311,15 @@ def main():
         kg = inputs.from_bf16_bits(inputs.to_bf16_bits(inputs.tensor_at(seed, inputs.TENSOR_K, bs, allpos, kv_heads, hs)))
         vg = inputs.from_bf16_bits(inputs.to_bf16_bits(inputs.tensor_at(seed, inputs.TENSOR_V, bs, allpos, kv_heads, hs)))
         t0 = time.perf_counter()
-        ref_o, ref_l = orc.attention_rows(qs, rows_pos, kg, vg, True)
+        ref_o, ref_l = orc.attention_rows(qs, rows_pos, kg, vg, causal)
         cpu_s = time.perf_counter() - t0
-        sample_pairs = float((rows_pos + 1).sum()) * hq * bs
+        sample_pairs = (float((rows_pos + 1).sum()) if causal else float(rows_pos.size) * L) * hq * bs
         out["cpu_baseline"] = {"value": round(4.0 * hs * sample_pairs / cpu_s / 1e12, 5), "unit": "TFLOP/s",
                                "cores": int(cores), "kind": "oracle", "seconds": round(cpu_s, 2),
                                "pairs_per_s": round(sample_pairs / cpu_s, 1),
                                "extrapolated_full_step_seconds": round(cpu_s * (pairs * hq * bs) / sample_pairs, 1),
                                "sample": f"{rows_local.size} uniformly sampled query rows x {hq} heads of the timed rank, "
-                                         f"all {L} keys, fp64 NumPy; same causal-effective flop accounting"}
+                                         f"all {L} keys, fp64 NumPy; same flop accounting (4*hs per visible pair)"}
         # parity of the timed step's output on the sampled rows (O comes back in seq layout: pick rank/rows)
         o_host = o.cpu().view(torch.int16).numpy().view(np.uint16)            # [N][bs][n][hc][hs]
         got = inputs.from_bf16_bits(o_host).reshape(N, bs, n, hc, hs)

@@ -622,9 +622,16 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     a.n_tiles = (a.Lk + 255) / 256;
     // One workgroup per (key tile, KV head) that walks all g query heads of the group writes its outputs with
     // plain stores; when that grid would leave CUs idle, the heads are split over workgroups that meet through
-    // atomic adds, on accumulators that start from zero unless the caller accumulates.
+    // atomic adds, on accumulators that start from zero unless the caller accumulates.  The split is the coarsest
+    // one that still gives every CU about four workgroups (a wide group, as in multi-query attention, would
+    // otherwise pay for g-fold atomic traffic), else one head per workgroup.
     const int64_t unsplit = (int64_t)a.n_tiles * hkv * bs * n_blocks;
-    a.heads_per_wg = unsplit >= 2 * 256 ? a.g : 1;
+    a.heads_per_wg = a.g;
+    if (unsplit < 2 * 256) {
+      a.heads_per_wg = 1;
+      for (int h = a.g - 1; h > 1; --h)
+        if (a.g % h == 0 && unsplit * (a.g / h) >= 4 * 256) { a.heads_per_wg = h; break; }
+    }
     for (int j = 0; j < kMaxBlocks; ++j) a.acc_dkdv[j] = accumulate_dkdv[j < n_blocks ? j : 0];
     if (a.heads_per_wg != a.g) {
       const size_t n4 = (size_t)bs * Lk * hkv * hs / 4;

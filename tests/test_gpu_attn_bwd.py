@@ -28,6 +28,9 @@ BWD_CASES = [
     # enough (key tile, KV head, batch) units that one workgroup walks both query heads of a group and stores its
     # dK/dV without atomics: first block overwrites, second block adds
     ("many_kv_units_plain_stores", 4, 96, 8192, 16, 8, 128, True, (8100, 96), (0, 8192), [0, 4096, 8192]),
+    # multi-query group of 32 heads over 64 (key tile, batch) units: the heads are split 16 ways, two per workgroup,
+    # and the workgroups of a key tile meet through atomic adds
+    ("mqa_partial_head_split", 2, 64, 8192, 32, 1, 128, True, (8100, 64), (0, 8192), [0, 8192]),
 ]
 
 
