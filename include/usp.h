@@ -13,7 +13,12 @@
  *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream);
  *   - arguments are validated on the host BEFORE any launch; on error nothing is enqueued;
  *   - no device memory is allocated: scratch comes from the caller (`workspace`), its
- *     size from the matching *_workspace_bytes query (host only, works without a GPU).
+ *     size from the matching *_workspace_bytes query (host only, works without a GPU);
+ *   - calls may be issued from several host threads and on several streams.  One limit: the
+ *     bf16 attention forward kernels hand out their work through counters in an 8 KiB static
+ *     device array, 256 sets used in rotation, each set back at zero when its launch ends.  Two
+ *     such launches that EXECUTE at the same time (different streams) must therefore be fewer
+ *     than 256 attention launches apart in issue order; launches on one stream never overlap.
  *
  * Notation (Sec. 2, notation table): L sequence length, hc head count, hs head size,
  * bs batch.  Added: hk = KV head count (GQA), U = Ulysses degree, R = ring degree,

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace usp {
 namespace dev {
 
@@ -18,6 +20,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Position descriptor narrowed to 32 bits (the host checks L < 2^31): fewer registers in the mask path.
+// fourth word of a raw (unstructured, bounds-checked by byte extent) buffer descriptor on gfx9-family chips:
+// 32-bit data format, everything else zero
+constexpr int kRawBufferFlags = 0x00020000;
+
 struct PosDesc32 { int start0, len0, start1, len1; };
 __device__ inline int pos_of(const PosDesc32& d, int i) { return i < d.len0 ? d.start0 + i : d.start1 + (i - d.len0); }
 __device__ inline int pos_min(const PosDesc32& d, int a, int b) {
@@ -125,5 +131,87 @@ __device__ inline float both_halves_sum(float x) {
   return __builtin_bit_cast(float, lo) + __builtin_bit_cast(float, hi);
 }
 
+// ---- persistent workgroups that draw their work items from counters ------------------------------------------
+// The hardware deals the workgroups of a grid to the eight XCDs round robin, i.e. every XCD gets the same share,
+// but the XCDs do not run at one speed (each settles at its own clock under the power limit: per-tile times
+// differ by 4-8 % between the XCDs of one chip), and a CU whose workgroup has ended waits tens of microseconds
+// for the dispatcher to start the next one.  So the attention kernels launch one workgroup per CU, and each
+// draws work items, in heavy-first order, from counters in device memory until the items run out.
+//
+// The kernels number their items with the KV head (times batch: `n_groups` values) fastest.  The CUs of one XCD
+// share an L2, and workgroups that read the same K/V walk its tiles at about the same time: with eight KV heads
+// mixed on an XCD the L2 serves four CUs per tile instead of thirty-two, which costs more than an idle tail does.
+// So the items are dealt to n_queues = gcd(8, n_groups) queues (item w to queue w mod n_queues: a queue holds the
+// same KV heads throughout; ONE queue when there is one KV head, eight when there are eight), a workgroup on XCD x
+// draws from queue x mod n_queues while that has items, and from the next queues round the ring after that.  It
+// ends when it has found all queues empty.
+//
+// Every launch uses one of kTicketSlots sets of counters (the host hands them out in rotation).  Queue q of a
+// launch of n_wgs workgroups over n_q items is drawn from exactly n_q + n_wgs times (each workgroup finds it empty
+// once and never asks again); the workgroup that makes the last draw puts the counter back to zero, so it is zero
+// again at the next launch, graph replays included.  Two launches may share a set only if they do not execute at
+// the same time; with the rotation that takes kTicketSlots launches issued between the two.
+constexpr int kTicketSlots = 256;
+constexpr int kMaxItemQueues = 8;
+constexpr unsigned kNoDraw = ~0u;
+static __device__ unsigned g_work_ticket[kTicketSlots * kMaxItemQueues];
+
+// the XCD (accelerator complex die) this wave runs on, 0..7
+__device__ inline int xcd_id() { return (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u); }   // XCC_ID[3:0]
+
+// What a launch's workgroups need to draw items (all of it workgroup-uniform).
+struct ItemQueues {
+  int slot, n_items, n_wgs, n_queues;
+  __device__ unsigned* counter(int q) const { return &g_work_ticket[slot * kMaxItemQueues + q]; }
+  __device__ unsigned items_of(int q) const { return (unsigned)(max(0, n_items - q + n_queues - 1) / n_queues); }   // q, q + n_queues, ...
+  __device__ int own() const { return xcd_id() % n_queues; }
+
+  // First half of a draw, by one thread of the workgroup: asks the workgroup's own queue, unless it is known to be
+  // empty.  The answer is only needed in finish(), so the caller can put work between the two.
+  __device__ unsigned begin(unsigned empty) const {
+    const int q = own();
+    if ((empty >> q) & 1u) return kNoDraw;
+    return __hip_atomic_fetch_add(counter(q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // One draw's bookkeeping: the item, or -1 when the queue was empty (then recorded in `empty`).
+  __device__ int settle(int q, unsigned ticket, unsigned& empty) const {
+    const unsigned n_q = items_of(q);
+    if (ticket == n_q + (unsigned)n_wgs - 1u) __hip_atomic_store(counter(q), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ticket < n_q) return q + n_queues * (int)ticket;
+    empty |= 1u << q;
+    return -1;
+  }
+  // Second half: the next item, or n_items when none is left.  `empty` is the workgroup's record (one bit per
+  // queue) of the queues it has found empty.
+  __device__ int finish(unsigned own_ticket, unsigned& empty) const {
+    const int q0 = own();
+    if (own_ticket != kNoDraw) {
+      const int item = settle(q0, own_ticket, empty);
+      if (item >= 0) return item;
+    }
+    for (int k = 1; k < n_queues; ++k) {
+      const int q = (q0 + k) % n_queues;
+      if ((empty >> q) & 1u) continue;
+      const unsigned t = __hip_atomic_fetch_add(counter(q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int item = settle(q, t, empty);
+      if (item >= 0) return item;
+    }
+    return n_items;
+  }
+};
+
 }  // namespace dev
+
+// host side: CUs of the current device, and the counter the next launch uses
+inline int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+    return 256;
+  return n;
+}
+inline int next_ticket_slot() {
+  static std::atomic<unsigned> issued{0};
+  return (int)(issued.fetch_add(1, std::memory_order_relaxed) % dev::kTicketSlots);
+}
+
 }  // namespace usp

@@ -18,9 +18,11 @@
 //   * exp2 with log2(e) folded into the scale; masks only on tiles that straddle the causal
 //     boundary or the ragged tail; key tiles that are invisible to the whole query tile are
 //     never loaded; the O accumulator is rescaled only when some row maximum moved.
-//   * Work order: heaviest query tiles first (descending local index under a causal mask), KV
-//     group fastest so that workgroups sharing K/V land on the same XCD's L2 when the number of
-//     groups is a multiple of the 8 XCDs.
+//   * One workgroup per CU, persistent: work items (query tile x head x batch) are drawn from
+//     counters in device memory, heaviest query tiles first (descending local index under a
+//     causal mask), KV group fastest; a workgroup prefers the items whose KV heads its XCD's L2
+//     already serves (attn_device.h).  K/V tiles are fetched through buffer descriptors.
+#include <numeric>
 #include <type_traits>
 
 #include "attn_device.h"
@@ -56,10 +58,29 @@ struct AttnArgs {
   // [U][bs][seq_n][seq_heads][hs] with this rank's heads at seq_head0: the all-to-all of Q (Algorithm 1 step 2)
   // and of O (step 6) folded into the one read of Q and the one write of O that the kernel does anyway.
   int seq_n, seq_heads, seq_head0;
+  int ticket_slot;   // counter the workgroups draw their work items from (MFMA kernel)
+  int n_items;       // work items of the launch: query tiles x heads x batch
+  int n_queues;      // gcd(8, batch x KV heads): item w waits in queue w mod n_queues
+};
+
+// The scalar arguments as one work item of the MFMA kernel sees them (read anew for every item, see the kernel).
+struct ItemArgs {
+  const void* q;
+  void* o;
+  float* lse;
+  int bs, hq, hkv, g;
+  int Lq, Lk;
+  int n_qtiles;
+  int n_blocks;
+  int causal;
+  float scale, scale_log2;
+  PosDesc32 qpos;
+  int seq_n, seq_heads, seq_head0;
 };
 
 // element offset of (batch b, local row, local head h) in the Q / O tensor
-__device__ inline size_t qo_offset(const AttnArgs& a, int b, int row, int h, int hs) {
+template <typename Args>
+__device__ inline size_t qo_offset(const Args& a, int b, int row, int h, int hs) {
   if (a.seq_n == 0) return (((size_t)b * a.Lq + row) * a.hq + h) * hs;
   const int shard = row / a.seq_n, s = row - shard * a.seq_n;
   return ((((size_t)shard * a.bs + b) * a.seq_n + s) * a.seq_heads + a.seq_head0 + h) * hs;
@@ -71,7 +92,7 @@ __device__ inline size_t qo_offset(const AttnArgs& a, int b, int row, int h, int
 // -------------------------------------------------------------------------------------------
 template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
 __global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64), amdgpu_waves_per_eu(WPE, WPE)))
-void block_attn_fwd_mfma(const AttnArgs a) {
+void block_attn_fwd_mfma(const AttnArgs) {
   constexpr int NT = NWAVES * 64;
   constexpr int BM = NWAVES * NQB * 32;
   constexpr int KSTEPS = HS / 16;          // MFMA k-steps of Q K^T
@@ -90,13 +111,51 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   char* const kbuf = smem;                  // [2][KBYTES]
   char* const vbuf = smem + 2 * KBYTES;     // [2][VBYTES]
 
-  const int tid = threadIdx.x, lane = tid & 63;
+  // ---- persistent workgroups: one per CU, each draws work items until none is left.  Item order: KV group
+  //      fastest, then head within group, then query tile (heavy first).
+  // The next item is drawn when the current one reaches its epilogue (not earlier: an item taken long before it is
+  // started is no longer the next one in line when it starts, which is what balances the CUs): thread 0 asks at
+  // the start of the epilogue and reads the answer after it, so the latency of the draw hides behind the stores
+  // of O.  The item's number waits in LDS, two slots in turn: the next number may be written while slower waves
+  // still read the current one.
+  __shared__ int next_item[2];
+  __shared__ unsigned empty_queues;   // thread 0's record of the item queues it has found empty
+  int turn = 0;
+  if (threadIdx.x == 0) {
+    auto ap0 = (const __attribute__((address_space(4))) AttnArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    const ItemQueues queues = {ap0->ticket_slot, ap0->n_items, (int)gridDim.x, ap0->n_queues};
+    unsigned empty = 0;
+    next_item[0] = queues.finish(queues.begin(empty), empty);
+    empty_queues = empty;
+  }
+  for (;;) {
+  // The kernel arguments are read anew for every item, through a pointer to the argument segment that the
+  // compiler cannot see through.  Read once, everything derived from them (reciprocals of the item decode, strides,
+  // flags) would be hoisted out of the item loop and held in scalar registers across it; there are not enough,
+  // and the overflow goes to lanes of a vector register that the tile loop cannot spare.
+  auto ap = (const __attribute__((address_space(4))) AttnArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(ap));
+  const int n_items = ap->n_items;
+  __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
+  int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
+  turn ^= 1;
+  if (w >= n_items) break;
+  ItemArgs a;
+  a.q = ap->q; a.o = ap->o; a.lse = ap->lse;
+  a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
+  a.Lq = ap->Lq; a.Lk = ap->Lk;
+  a.n_qtiles = ap->n_qtiles; a.n_blocks = ap->n_blocks; a.causal = ap->causal;
+  a.scale = ap->scale; a.scale_log2 = ap->scale_log2;
+  a.qpos = PosDesc32{ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
+  a.seq_n = ap->seq_n; a.seq_heads = ap->seq_heads; a.seq_head0 = ap->seq_head0;
+  const int n_groups = a.bs * a.hkv;
+  // The lane constants are derived anew for every item from a thread index the compiler cannot see through:
+  // hoisted out of the item loop they would stay in registers across it, and the tile loop has none to spare.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
   const int l32 = lane & 31, hl = lane >> 5;
-
-  // ---- work item decode: KV group fastest, then head within group, then query tile (heavy first)
-  const int n_groups = a.bs * a.hkv;
-  int w = blockIdx.x;
   const int group = w % n_groups; w /= n_groups;
   const int hg = w % a.g;
   const int t = w / a.g;
@@ -113,13 +172,9 @@ void block_attn_fwd_mfma(const AttnArgs a) {
 
   // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
   bf16x8 qf[NQB][KSTEPS];
-  int qrow[NQB];
-  int qp[NQB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    qrow[qb] = wave_row0 + qb * 32 + l32;
-    const int rr = min(qrow[qb], a.Lq - 1);
-    qp[qb] = a.causal ? pos_of(a.qpos, rr) : 0;
+    const int rr = min(wave_row0 + qb * 32 + l32, a.Lq - 1);
     const __bf16* src = qg + qo_offset(a, b, rr, h, HS) + 8 * hl;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
@@ -128,21 +183,23 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   // per-block state of the tile walk (workgroup-uniform), set at the top of the block loop
   const char* kg = nullptr;
   const char* vg = nullptr;
-  PosDesc32 kpos = a.kpos[0];
+  PosDesc32 kpos = {0, 0, 0, 0};
   TileRanges tr = {0, 0, 0, 0};
   int na = 0, nt = 0;
   auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
 
   f32x16 oacc[NQB][DB];
   float m_run[NQB], l_run[NQB];
+  float zero = 0.f;
+  asm volatile("" : "+v"(zero));   // not a constant to the compiler: it would share one zeroed register tuple between items
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
+    l_run[qb] = zero;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[qb][db][i] = 0.f;
+      for (int i = 0; i < 16; ++i) oacc[qb][db][i] = zero;
   }
 
   // wave-level bounds for the mask decision
@@ -154,9 +211,10 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   const int st_row = tid / (HS / 8), st_col = tid % (HS / 8);
   constexpr int ROWS_PER_PASS = NT / (HS / 8);
   u32x4 kreg[CPT], vreg[CPT];
-  // A tile's base address is wave-uniform (scalar registers); each thread adds a 32-bit byte offset that is the
-  // same for every tile.  Rows past the last key (ragged final tile only) are clamped by a min on the offset:
-  // offsets grow with the row, and (last row, this column) is the largest valid one not beyond this thread's.
+  // Tiles are read through a buffer descriptor built per tile in scalar registers: base = the tile's first row
+  // (this KV head), extent = up to the end of its last valid row.  Each thread adds a 32-bit byte offset that is
+  // the same for every tile; rows past the last key (ragged final tile only) lie beyond the extent and read as
+  // zeros (the mask hides those keys).  No 64-bit address arithmetic on the vector ALU, no clamping.
   const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
   uint32_t st_off[CPT];
 #pragma unroll
@@ -164,9 +222,11 @@ void block_attn_fwd_mfma(const AttnArgs a) {
   auto fetch = [&](const char* base, int it, u32x4* reg) {
     const int key0 = tile_of(it) * KT;
     const char* tb = base + (size_t)key0 * row_bytes;
-    const uint32_t lim = (uint32_t)min(a.Lk - 1 - key0, KT - 1) * row_bytes + st_col * 16;
+    const int rows = min(a.Lk - key0, KT);
+    const __amdgpu_buffer_rsrc_t tile = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)tb, 0, (rows - 1) * (int)row_bytes + HS * 2, kRawBufferFlags);
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) reg[c] = *(const u32x4*)(tb + min(st_off[c], lim));
+    for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile, (int)st_off[c], 0, 0);
   };
   auto stash = [&](char* buf, int stride, const u32x4* reg) {
 #pragma unroll
@@ -214,6 +274,9 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     bool need_mask = key0 + KT > a.Lk;
     if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
     if (need_mask) {
+      int qp[NQB];   // the lane's query position: derived here, where it is rarely needed, rather than kept in a register
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) qp[qb] = a.causal ? pos_of(a.qpos, min(wave_row0 + qb * 32 + l32, a.Lq - 1)) : 0;
 #pragma unroll
       for (int kbk = 0; kbk < KB; ++kbk)
 #pragma unroll
@@ -324,15 +387,14 @@ void block_attn_fwd_mfma(const AttnArgs a) {
 
   const std::integral_constant<bool, true> steady;
   const std::integral_constant<bool, false> draining;
-  f32x16 s0[NQB][KB], s1[NQB][KB];
   for (int blk = 0; blk < a.n_blocks; ++blk) {
-    kpos = a.kpos[blk];
+    kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
     tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
     na = tr.a1 - tr.a0;
     nt = na + (tr.b1 - tr.b0);
     if (nt == 0) continue;         // nothing of this block is visible to the query tile (workgroup-uniform)
-    kg = (const char*)a.k[blk] + kv_head_off;
-    vg = (const char*)a.v[blk] + kv_head_off;
+    kg = (const char*)ap->k[blk] + kv_head_off;
+    vg = (const char*)ap->v[blk] + kv_head_off;
 
     // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0.  (Every step ends on a barrier, so the previous
     //      block's last reads of these buffers are over.)
@@ -345,6 +407,14 @@ void block_attn_fwd_mfma(const AttnArgs a) {
       stash(kbuf + KBYTES, KSTR, kreg);
     }
     __syncthreads();
+    f32x16 s0[NQB][KB], s1[NQB][KB];   // scores of the current and of the next tile
+    // s1 starts undefined and says so: an empty asm "defines" it.  Otherwise the compiler carries its stale value
+    // from the previous block and item around every loop (the draining steps below may leave it untouched), as a
+    // zero-initialised 32-register tuple that it keeps in scratch.
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int kbk = 0; kbk < KB; ++kbk) asm volatile("" : "=v"(s1[qb][kbk]));
     qk(kbuf, s0);
     __syncthreads();   // step 0 overwrites K buffer 0 with tile 2: every wave must have read tile 0 first
 
@@ -355,21 +425,27 @@ void block_attn_fwd_mfma(const AttnArgs a) {
     }
     for (; it < nt; ++it) {          // at most three tiles left
       step(draining, it, s0, s1);
+      if (it + 1 < nt) {             // (the last step leaves s1 undefined: nothing may read it)
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb)
+        for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-        for (int kbk = 0; kbk < KB; ++kbk) s0[qb][kbk] = s1[qb][kbk];
+          for (int kbk = 0; kbk < KB; ++kbk) s0[qb][kbk] = s1[qb][kbk];
+      }
     }
   }
 
+  const ItemQueues queues = {ap->ticket_slot, n_items, (int)gridDim.x, ap->n_queues};
+  unsigned own_ticket = kNoDraw;
+  if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
   // ---- epilogue: normalise, write O (a row that saw no key at all: l = 0 -> O = 0, LSE = -inf)
   // ---- write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const float l_tot = both_halves_sum(l_run[qb]);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    if (qrow[qb] < a.Lq) {
-      OutT* dst = (OutT*)a.o + qo_offset(a, b, qrow[qb], h, HS) + 4 * hl;
+    const int qrow = wave_row0 + qb * 32 + l32;
+    if (qrow < a.Lq) {
+      OutT* dst = (OutT*)a.o + qo_offset(a, b, qrow, h, HS) + 4 * hl;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -386,10 +462,16 @@ void block_attn_fwd_mfma(const AttnArgs a) {
         }
       if (hl == 0) {
         const float lse = l_tot > 0.f ? m_run[qb] * a.scale + __logf(l_tot) : -INFINITY;
-        a.lse[((size_t)b * a.hq + h) * a.Lq + qrow[qb]] = lse;
+        a.lse[((size_t)b * a.hq + h) * a.Lq + qrow] = lse;
       }
     }
   }
+  if (threadIdx.x == 0) {   // waits for the draw only: the stores were issued after it
+    unsigned empty = empty_queues;
+    next_item[turn] = queues.finish(own_ticket, empty);
+    empty_queues = empty;
+  }
+  }   // next work item
 }
 
 // -------------------------------------------------------------------------------------------
@@ -476,7 +558,12 @@ int launch_mfma(AttnArgs a, hipStream_t stream) {
       return USP_ERR_LAUNCH;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NWAVES * 64), lds, stream, a);
+  // one workgroup per CU (its registers and LDS fill a CU), fewer when there are fewer items
+  a.ticket_slot = next_ticket_slot();
+  a.n_items = (int)grid;
+  a.n_queues = std::gcd(dev::kMaxItemQueues, a.bs * a.hkv);
+  const int n_wgs = (int)std::min<int64_t>(grid, compute_units());
+  hipLaunchKernelGGL(kern, dim3((unsigned)n_wgs), dim3(NWAVES * 64), lds, stream, a);
   return launch_status();
 }
 
@@ -513,6 +600,9 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
   a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
   a.Lq = (int)Lq; a.Lk = (int)Lk;
   a.n_qtiles = 0;
+  a.ticket_slot = 0;
+  a.n_items = 0;
+  a.n_queues = 1;
   a.causal = causal;
   a.scale = scale;
   a.scale_log2 = scale * 1.4426950408889634f;

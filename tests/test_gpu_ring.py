@@ -150,3 +150,33 @@ def test_ring_attn_bwd_matches_per_block_calls(usp):
     assert torch.allclose(dk[1], 2 * dk2[1], atol=4e-5, rtol=1e-5)
     with pytest.raises(usp.UspError):
         usp.usp_ring_attn_bwd(q, [], [], [], d_o, lse, delta, dq, [], [], bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, False, [])
+
+
+def test_many_launches_leave_the_item_counters_clean(usp):
+    """The forward kernel's workgroups draw their work items from per-launch counters that the last draw of a
+    launch puts back to zero, and the launches take the counter sets in rotation: more launches than there are
+    sets, of two alternating shapes (one with fewer items than CUs, one with more items than CUs and eight KV
+    heads, i.e. eight item queues), must all give the first launch's result, bit for bit."""
+    shapes = [(1, 300, 3, 1, 64), (2, 2500, 16, 8, 128)]   # bs, L, hq, hkv, hs -> 6 items / 320 items
+    runs = []
+    for bs, L, hq, hkv, hs in shapes:
+        qs, _ = tl.gen(77, inputs.TENSOR_Q, bs, np.arange(L), np.arange(hq), hs, tl.BF16)
+        ks, _ = tl.gen(77, inputs.TENSOR_K, bs, np.arange(L), np.arange(hkv), hs, tl.BF16)
+        vs, _ = tl.gen(77, inputs.TENSOR_V, bs, np.arange(L), np.arange(hkv), hs, tl.BF16)
+        q, k, v = (tl.to_device(x, tl.BF16) for x in (qs, ks, vs))
+        d = usp.usp_posdesc(0, L, 0, 0)
+        o = torch.empty_like(q)
+        lse = torch.empty((bs, hq, L), dtype=torch.float32, device="cuda")
+        runs.append((q, k, v, d, o, lse, bs, L, hq, hkv, hs))
+    first = []
+    for i in range(2 * 300):
+        q, k, v, d, o, lse, bs, L, hq, hkv, hs = runs[i % 2]
+        o.fill_(float("nan"))
+        usp.usp_block_attn_fwd(q, k, v, o, lse, bs, L, L, hq, hkv, hs, 0.0, True, d, d, tl.BF16, tl.BF16)
+        if i < 2:
+            torch.cuda.synchronize()
+            first.append((o.clone(), lse.clone()))
+        elif i % 97 < 2 or i >= 2 * 300 - 2:
+            torch.cuda.synchronize()
+            assert torch.equal(o.view(torch.int16), first[i % 2][0].view(torch.int16)), i
+            assert torch.equal(lse, first[i % 2][1]), i
