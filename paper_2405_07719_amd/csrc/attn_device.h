@@ -146,57 +146,75 @@ __device__ inline float both_halves_sum(float x) {
 // draws from queue x mod n_queues while that has items, and from the next queues round the ring after that.  It
 // ends when it has found all queues empty.
 //
-// Every launch uses one of kTicketSlots sets of counters (the host hands them out in rotation).  Queue q of a
-// launch of n_wgs workgroups over n_q items is drawn from exactly n_q + n_wgs times (each workgroup finds it empty
-// once and never asks again); the workgroup that makes the last draw puts the counter back to zero, so it is zero
-// again at the next launch, graph replays included.  Two launches may share a set only if they do not execute at
-// the same time; with the rotation that takes kTicketSlots launches issued between the two.
+// Every launch uses one of kTicketSlots sets of counters (the host hands them out in rotation): one per queue, and
+// one that counts the workgroups that have left.  A workgroup leaves when it finds no item, and says so; the one
+// that leaves last (nobody draws after it) puts the whole set back to zero, so it is zero again at the next launch,
+// graph replays included.  Two launches may share a set only if they do not execute at the same time; with the
+// rotation that takes kTicketSlots launches issued between the two.
 constexpr int kTicketSlots = 256;
 constexpr int kMaxItemQueues = 8;
+constexpr int kSlotStride = 16;          // counters per set: eight queues, "left", padding to 64 bytes
 constexpr unsigned kNoDraw = ~0u;
-static __device__ unsigned g_work_ticket[kTicketSlots * kMaxItemQueues];
+static __device__ unsigned g_work_ticket[kTicketSlots * kSlotStride];
 
 // the XCD (accelerator complex die) this wave runs on, 0..7
 __device__ inline int xcd_id() { return (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u); }   // XCC_ID[3:0]
 
-// What a launch's workgroups need to draw items (all of it workgroup-uniform).
+// What a launch's workgroups need to draw items (all of it workgroup-uniform).  Every function here is for ONE
+// thread of the workgroup; `empty` is that thread's record (one bit per queue) of the queues it has found empty.
 struct ItemQueues {
   int slot, n_items, n_wgs, n_queues;
-  __device__ unsigned* counter(int q) const { return &g_work_ticket[slot * kMaxItemQueues + q]; }
-  __device__ unsigned items_of(int q) const { return (unsigned)(max(0, n_items - q + n_queues - 1) / n_queues); }   // q, q + n_queues, ...
+  __device__ unsigned* counter(int q) const { return &g_work_ticket[slot * kSlotStride + q]; }
+  __device__ unsigned* left() const { return &g_work_ticket[slot * kSlotStride + kMaxItemQueues]; }
+  // Queue q holds items q, q + n_queues, ...  The first n_wgs items of the launch are not drawn: workgroup b starts
+  // with item b (the hardware puts workgroup b on XCD b mod 8, so that is an item of its own queue), which saves
+  // every launch the latency of a first draw.  Draw number t from queue q is therefore item q + n_queues (given(q) + t).
+  __device__ unsigned given(int q) const { return (unsigned)(max(0, n_wgs - q + n_queues - 1) / n_queues); }
+  __device__ unsigned items_of(int q) const {
+    return (unsigned)(max(0, n_items - q + n_queues - 1) / n_queues) - given(q);   // n_wgs <= n_items: never negative
+  }
+  __device__ int item(int q, unsigned t) const { return q + n_queues * (int)(given(q) + t); }
   __device__ int own() const { return xcd_id() % n_queues; }
+  __device__ static unsigned add1(unsigned* c) { return __hip_atomic_fetch_add(c, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-  // First half of a draw, by one thread of the workgroup: asks the workgroup's own queue, unless it is known to be
-  // empty.  The answer is only needed in finish(), so the caller can put work between the two.
+  // First half of a draw: asks the workgroup's own queue, unless that is known to be empty.  The answer is only
+  // needed in finish(), so the caller can put work between the two.
   __device__ unsigned begin(unsigned empty) const {
     const int q = own();
-    if ((empty >> q) & 1u) return kNoDraw;
-    return __hip_atomic_fetch_add(counter(q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return ((empty >> q) & 1u) ? kNoDraw : add1(counter(q));
   }
-  // One draw's bookkeeping: the item, or -1 when the queue was empty (then recorded in `empty`).
-  __device__ int settle(int q, unsigned ticket, unsigned& empty) const {
-    const unsigned n_q = items_of(q);
-    if (ticket == n_q + (unsigned)n_wgs - 1u) __hip_atomic_store(counter(q), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (ticket < n_q) return q + n_queues * (int)ticket;
-    empty |= 1u << q;
-    return -1;
-  }
-  // Second half: the next item, or n_items when none is left.  `empty` is the workgroup's record (one bit per
-  // queue) of the queues it has found empty.
+  // Second half: the next item, or n_items when none is left.
   __device__ int finish(unsigned own_ticket, unsigned& empty) const {
     const int q0 = own();
     if (own_ticket != kNoDraw) {
-      const int item = settle(q0, own_ticket, empty);
-      if (item >= 0) return item;
+      if (own_ticket < items_of(q0)) return item(q0, own_ticket);
+      empty |= 1u << q0;
     }
-    for (int k = 1; k < n_queues; ++k) {
-      const int q = (q0 + k) % n_queues;
-      if ((empty >> q) & 1u) continue;
-      const unsigned t = __hip_atomic_fetch_add(counter(q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const int item = settle(q, t, empty);
-      if (item >= 0) return item;
+    while (n_queues > 1) {
+      // a look at the other queues (a hint; the draw decides): the first one round the ring that still has items
+      int best = -1, best_away = kMaxItemQueues;
+#pragma unroll
+      for (int q = 0; q < kMaxItemQueues; ++q) {
+        if (q >= n_queues || ((empty >> q) & 1u)) continue;
+        const unsigned drawn = __hip_atomic_load(counter(q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int away = (q - q0 + n_queues) % n_queues;
+        if (drawn < items_of(q) && away < best_away) { best = q; best_away = away; }
+      }
+      if (best < 0) break;
+      const unsigned t = add1(counter(best));
+      if (t < items_of(best)) return item(best, t);
+      empty |= 1u << best;
     }
     return n_items;
+  }
+  // The workgroup has found no item and ends.  Its draws are complete (their answers were read) before this count,
+  // all of them go to the same place (agent-scope atomics), so whoever counts last also writes last.
+  __device__ void leave() const {
+    if (add1(left()) == (unsigned)n_wgs - 1u) {
+#pragma unroll
+      for (int q = 0; q <= kMaxItemQueues; ++q)
+        __hip_atomic_store(&g_work_ticket[slot * kSlotStride + q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 };
 

@@ -122,11 +122,8 @@ void block_attn_fwd_mfma(const AttnArgs) {
   __shared__ unsigned empty_queues;   // thread 0's record of the item queues it has found empty
   int turn = 0;
   if (threadIdx.x == 0) {
-    auto ap0 = (const __attribute__((address_space(4))) AttnArgs*)__builtin_amdgcn_kernarg_segment_ptr();
-    const ItemQueues queues = {ap0->ticket_slot, ap0->n_items, (int)gridDim.x, ap0->n_queues};
-    unsigned empty = 0;
-    next_item[0] = queues.finish(queues.begin(empty), empty);
-    empty_queues = empty;
+    next_item[0] = blockIdx.x;   // the first item is given, not drawn (ItemQueues::given)
+    empty_queues = 0;
   }
   for (;;) {
   // The kernel arguments are read anew for every item, through a pointer to the argument segment that the
@@ -139,7 +136,10 @@ void block_attn_fwd_mfma(const AttnArgs) {
   __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
   int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
   turn ^= 1;
-  if (w >= n_items) break;
+  if (w >= n_items) {
+    if (threadIdx.x == 0) ItemQueues{ap->ticket_slot, n_items, (int)gridDim.x, ap->n_queues}.leave();
+    break;
+  }
   ItemArgs a;
   a.q = ap->q; a.o = ap->o; a.lse = ap->lse;
   a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
