@@ -180,3 +180,34 @@ def test_many_launches_leave_the_item_counters_clean(usp):
             torch.cuda.synchronize()
             assert torch.equal(o.view(torch.int16), first[i % 2][0].view(torch.int16)), i
             assert torch.equal(lse, first[i % 2][1]), i
+
+
+def test_launches_that_overlap_on_two_streams(usp):
+    """Forward launches issued alternately on two streams (default priority) may execute at the same time; each uses
+    its own set of item counters, so both streams' results must equal the single-stream ones, bit for bit."""
+    bs, L, hq, hkv, hs = 1, 6000, 8, 2, 128          # 24 query tiles x 8 heads = 192 items: half the chip per launch
+    qs, _ = tl.gen(78, inputs.TENSOR_Q, bs, np.arange(L), np.arange(hq), hs, tl.BF16)
+    ks, _ = tl.gen(78, inputs.TENSOR_K, bs, np.arange(L), np.arange(hkv), hs, tl.BF16)
+    vs, _ = tl.gen(78, inputs.TENSOR_V, bs, np.arange(L), np.arange(hkv), hs, tl.BF16)
+    q, k, v = (tl.to_device(x, tl.BF16) for x in (qs, ks, vs))
+    d = usp.usp_posdesc(0, L, 0, 0)
+    ref_o = torch.empty_like(q)
+    ref_l = torch.empty((bs, hq, L), dtype=torch.float32, device="cuda")
+    usp.usp_block_attn_fwd(q, k, v, ref_o, ref_l, bs, L, L, hq, hkv, hs, 0.0, True, d, d, tl.BF16, tl.BF16)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [(torch.empty_like(q), torch.empty_like(ref_l)) for _ in range(2)]
+    for i in range(40):
+        o, lse = outs[i % 2]
+        usp.usp_block_attn_fwd(q, k, v, o, lse, bs, L, L, hq, hkv, hs, 0.0, True, d, d, tl.BF16, tl.BF16,
+                               stream=streams[i % 2])
+    for s in streams:
+        s.synchronize()
+    for o, lse in outs:
+        assert torch.equal(o.view(torch.int16), ref_o.view(torch.int16))
+        assert torch.equal(lse, ref_l)
+    # and the counters are clean afterwards
+    o2 = torch.empty_like(q)
+    usp.usp_block_attn_fwd(q, k, v, o2, ref_l.clone(), bs, L, L, hq, hkv, hs, 0.0, True, d, d, tl.BF16, tl.BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(o2.view(torch.int16), ref_o.view(torch.int16))
