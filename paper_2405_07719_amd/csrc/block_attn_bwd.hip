@@ -19,6 +19,9 @@
 // free of bank conflicts for the 16 B row reads and for the transpose reads alike.
 // Outputs are fp32 accumulators (overwrite or add), so ring steps and ranks can be summed before the
 // final conversion to the problem dtype.
+#include <algorithm>
+#include <numeric>
+
 #include "attn_device.h"
 #include "usp_internal.h"
 
@@ -53,6 +56,22 @@ struct BwdArgs {
   float scale, scale_log2;
   PosDesc32 qpos;
   PosDesc32 kpos[kMaxBlocks];
+  // dq: its workgroups are persistent and draw their work items (attn_device.h)
+  int ticket_slot, n_items, n_queues;
+};
+
+// The scalar arguments as one work item of the dQ kernel sees them (read anew for every item, see the kernel).
+struct DqItemArgs {
+  const void* q;
+  const void* d_o;
+  const float* lse;
+  const float* delta;
+  float* dq;
+  int bs, hq, hkv, g;
+  int Lq, Lk;
+  int n_tiles, n_blocks, causal, accumulate;
+  float scale, scale_log2;
+  PosDesc32 qpos;
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -118,7 +137,7 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* o, const _
 // -------------------------------------------------------------------------------------------------
 template <int HS>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
-void bwd_dq_kernel(const BwdArgs a) {
+void bwd_dq_kernel(const BwdArgs) {
   constexpr int NT = 512, BM = 256, KT = 32;
   constexpr int KSTEPS = HS / 16, DB = HS / 32;
   constexpr int USTR = HS * 2 + 48;                 // conflict-free for 16 B row reads and for transpose reads
@@ -127,11 +146,42 @@ void bwd_dq_kernel(const BwdArgs a) {
   static_assert(KT * CPR <= NT, "one chunk per thread and tensor");
   __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
 
-  const int tid = threadIdx.x, lane = tid & 63;
+  // Persistent workgroups, one per CU, that draw their work items as the forward kernel's do (same item order:
+  // KV group fastest, then head within group, then query tile, heavy first; the next item is asked for at the start
+  // of the epilogue and the answer read after the stores).
+  __shared__ int next_item[2];
+  __shared__ unsigned empty_queues;
+  int turn = 0;
+  if (threadIdx.x == 0) {
+    next_item[0] = blockIdx.x;   // the first item is given, not drawn
+    empty_queues = 0;
+  }
+  for (;;) {
+  // arguments and lane constants are read / derived anew for every item, so that nothing derived from them is
+  // carried in registers across the item loop
+  auto ap = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(ap));
+  const ItemQueues queues = {ap->ticket_slot, ap->n_items, (int)gridDim.x, ap->n_queues};
+  __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
+  int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
+  turn ^= 1;
+  if (w >= queues.n_items) {
+    if (threadIdx.x == 0) queues.leave();
+    break;
+  }
+  DqItemArgs a;
+  a.q = ap->q; a.d_o = ap->d_o; a.lse = ap->lse; a.delta = ap->delta; a.dq = ap->dq;
+  a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
+  a.Lq = ap->Lq; a.Lk = ap->Lk;
+  a.n_tiles = ap->n_tiles; a.n_blocks = ap->n_blocks; a.causal = ap->causal; a.accumulate = ap->accumulate;
+  a.scale = ap->scale; a.scale_log2 = ap->scale_log2;
+  a.qpos = PosDesc32{ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
   const int l32 = lane & 31, hl = lane >> 5;
   const int n_groups = a.bs * a.hkv;
-  int w = blockIdx.x;
   const int group = w % n_groups; w /= n_groups;
   const int hg = w % a.g;
   const int t = w / a.g;
@@ -174,7 +224,7 @@ void bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
   for (int db = 0; db < DB; ++db) zero16(dq[db]);
 
-  PosDesc32 kpos = a.kpos[0];
+  PosDesc32 kpos = {0, 0, 0, 0};
   TileRanges tr = {0, 0, 0, 0};
   int na = 0, nt = 0;
   auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
@@ -207,13 +257,13 @@ void bwd_dq_kernel(const BwdArgs a) {
   const int row_off = l32 * USTR + hl * 16;
 
   for (int blk = 0; blk < a.n_blocks; ++blk) {
-  kpos = a.kpos[blk];
+  kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
   tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
   na = tr.a1 - tr.a0;
   nt = na + (tr.b1 - tr.b0);
   if (nt == 0) continue;                   // workgroup-uniform
-  kg = (const char*)a.k[blk] + kv_head_off;
-  vg = (const char*)a.v[blk] + kv_head_off;
+  kg = (const char*)ap->k[blk] + kv_head_off;
+  vg = (const char*)ap->v[blk] + kv_head_off;
   fetch(0);
   stash(0);                                // the previous block's last step ended on a barrier
   __syncthreads();
@@ -269,6 +319,8 @@ void bwd_dq_kernel(const BwdArgs a) {
   }
   }   // blocks
 
+  unsigned own_ticket = kNoDraw;
+  if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
   if (qrow < a.Lq) {
     float* dst = a.dq + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
 #pragma unroll
@@ -282,6 +334,12 @@ void bwd_dq_kernel(const BwdArgs a) {
         *d = v4;
       }
   }
+  if (threadIdx.x == 0) {
+    unsigned empty = empty_queues;
+    next_item[turn] = queues.finish(own_ticket, empty);
+    empty_queues = empty;
+  }
+  }   // next work item
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -611,10 +669,15 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     a.n_tiles = (a.Lq + 255) / 256;
     const int64_t grid = (int64_t)a.n_tiles * hq * bs;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
+    // one workgroup per CU (256 VGPRs x 8 waves fill it), fewer when there are fewer items
+    a.ticket_slot = next_ticket_slot();
+    a.n_items = (int)grid;
+    a.n_queues = std::gcd(dev::kMaxItemQueues, bs * hkv);
+    const unsigned n_wgs = (unsigned)std::min<int64_t>(grid, compute_units());
     if (hs == 128)
-      hipLaunchKernelGGL((bwd_dq_kernel<128>), dim3((unsigned)grid), dim3(512), 0, stream, a);
+      hipLaunchKernelGGL((bwd_dq_kernel<128>), dim3(n_wgs), dim3(512), 0, stream, a);
     else
-      hipLaunchKernelGGL((bwd_dq_kernel<64>), dim3((unsigned)grid), dim3(512), 0, stream, a);
+      hipLaunchKernelGGL((bwd_dq_kernel<64>), dim3(n_wgs), dim3(512), 0, stream, a);
     const int st = launch_status();
     if (st != USP_OK) return st;
   }
