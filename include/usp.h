@@ -19,6 +19,8 @@
  *     device arrays, 256 sets used in rotation, each set back at zero when its launch ends.  Two
  *     such launches that EXECUTE at the same time (different streams) must therefore be fewer
  *     than 256 attention launches apart in issue order; launches on one stream never overlap.
+ *     A launch captured into a HIP graph keeps its set for every replay: replay a graph on one
+ *     stream at a time.
  *
  * Notation (Sec. 2, notation table): L sequence length, hc head count, hs head size,
  * bs batch.  Added: hk = KV head count (GQA), U = Ulysses degree, R = ring degree,

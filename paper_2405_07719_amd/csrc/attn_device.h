@@ -222,9 +222,14 @@ struct ItemQueues {
 
 // host side: CUs of the current device, and the counter the next launch uses
 inline int compute_units() {
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-    return 256;
+  static std::atomic<int> known[64];   // per device, asked once: later calls may come during stream capture
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = known[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    known[dev].store(n, std::memory_order_relaxed);
+  }
   return n;
 }
 inline int next_ticket_slot() {

@@ -211,3 +211,32 @@ def test_launches_that_overlap_on_two_streams(usp):
     usp.usp_block_attn_fwd(q, k, v, o2, ref_l.clone(), bs, L, L, hq, hkv, hs, 0.0, True, d, d, tl.BF16, tl.BF16)
     torch.cuda.synchronize()
     assert torch.equal(o2.view(torch.int16), ref_o.view(torch.int16))
+
+
+def test_ring_attn_fwd_in_a_hip_graph(usp):
+    """The one-launch ring forward captured into a HIP graph and replayed: every replay, with eager launches and
+    synchronisations between the replays, must reproduce the eager result bit for bit (the kernel's item counters
+    are back at zero after each run, and a captured launch keeps its set of counters)."""
+    q, kb, vb, kd, qd, _, _ = _ring_case(usp, 61, 1, 4096, 8, 4, 128, 4, 1, True, True, [1, 0, 3, 2])
+    bs, Lq, hq, hkv, hs = 1, 1024, 8, 4, 128
+    o_ref = torch.empty_like(q)
+    l_ref = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
+
+    def launch(o, lse):
+        usp.usp_ring_attn_fwd(q, kb, vb, kd, o, lse, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, tl.BF16, tl.BF16)
+    launch(o_ref, l_ref)            # eager first: one-time kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    o_g, l_g = torch.empty_like(q), torch.empty_like(l_ref)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        launch(o_g, l_g)
+    o_e, l_e = torch.empty_like(q), torch.empty_like(l_ref)
+    for rep in range(4):
+        o_g.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_g.view(torch.int16), o_ref.view(torch.int16)), rep
+        assert torch.equal(l_g, l_ref), rep
+        launch(o_e, l_e)            # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(o_e.view(torch.int16), o_ref.view(torch.int16)), rep
