@@ -157,188 +157,188 @@ void bwd_dq_kernel(const BwdArgs) {
     empty_queues = 0;
   }
   for (;;) {
-  // arguments and lane constants are read / derived anew for every item, so that nothing derived from them is
-  // carried in registers across the item loop
-  auto ap = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
-  asm volatile("" : "+s"(ap));
-  const ItemQueues queues = {ap->ticket_slot, ap->n_items, (int)gridDim.x, ap->n_queues};
-  __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
-  int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
-  turn ^= 1;
-  if (w >= queues.n_items) {
-    if (threadIdx.x == 0) queues.leave();
-    break;
-  }
-  DqItemArgs a;
-  a.q = ap->q; a.d_o = ap->d_o; a.lse = ap->lse; a.delta = ap->delta; a.dq = ap->dq;
-  a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
-  a.Lq = ap->Lq; a.Lk = ap->Lk;
-  a.n_tiles = ap->n_tiles; a.n_blocks = ap->n_blocks; a.causal = ap->causal; a.accumulate = ap->accumulate;
-  a.scale = ap->scale; a.scale_log2 = ap->scale_log2;
-  a.qpos = PosDesc32{ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
-  int tid = threadIdx.x;
-  asm volatile("" : "+v"(tid));
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
-  const int l32 = lane & 31, hl = lane >> 5;
-  const int n_groups = a.bs * a.hkv;
-  const int group = w % n_groups; w /= n_groups;
-  const int hg = w % a.g;
-  const int t = w / a.g;
-  const int qtile = a.causal ? a.n_tiles - 1 - t : t;
-  const int b = group / a.hkv, kvh = group % a.hkv;
-  const int h = kvh * a.g + hg;
-  const int tile_row0 = qtile * BM, tile_row1 = min(a.Lq, tile_row0 + BM);
-  const int wave_row0 = tile_row0 + wave * 32;
-  const int qrow = wave_row0 + l32;
-  const int rr = min(qrow, a.Lq - 1);
-  const int qp = a.causal ? pos_of(a.qpos, rr) : 0;
-
-  const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes
-  const char* kg = nullptr;   // per block, set at the top of the block loop
-  const char* vg = nullptr;
-  const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
-
-  bf16x8 qf[KSTEPS], dof[KSTEPS];
-  {
-    const size_t off = (((size_t)b * a.Lq + rr) * a.hq + h) * HS + 8 * hl;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      qf[ks] = *(const bf16x8*)((const __bf16*)a.q + off + 16 * ks);
-      dof[ks] = *(const bf16x8*)((const __bf16*)a.d_o + off + 16 * ks);
+    // arguments and lane constants are read / derived anew for every item, so that nothing derived from them is
+    // carried in registers across the item loop
+    auto ap = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+    const ItemQueues queues = {ap->ticket_slot, ap->n_items, (int)gridDim.x, ap->n_queues};
+    __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
+    int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
+    turn ^= 1;
+    if (w >= queues.n_items) {
+      if (threadIdx.x == 0) queues.leave();
+      break;
     }
-  }
-  const size_t stat = ((size_t)b * a.hq + h) * a.Lq + rr;
-  const float lse = a.lse[stat];
-  float dlt = a.delta[stat];
-  float l2 = (lse == -INFINITY) ? INFINITY : lse * kLog2e;   // a row that saw nothing: P = 0
+    DqItemArgs a;
+    a.q = ap->q; a.d_o = ap->d_o; a.lse = ap->lse; a.delta = ap->delta; a.dq = ap->dq;
+    a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
+    a.Lq = ap->Lq; a.Lk = ap->Lk;
+    a.n_tiles = ap->n_tiles; a.n_blocks = ap->n_blocks; a.causal = ap->causal; a.accumulate = ap->accumulate;
+    a.scale = ap->scale; a.scale_log2 = ap->scale_log2;
+    a.qpos = PosDesc32{ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
+    const int l32 = lane & 31, hl = lane >> 5;
+    const int n_groups = a.bs * a.hkv;
+    const int group = w % n_groups; w /= n_groups;
+    const int hg = w % a.g;
+    const int t = w / a.g;
+    const int qtile = a.causal ? a.n_tiles - 1 - t : t;
+    const int b = group / a.hkv, kvh = group % a.hkv;
+    const int h = kvh * a.g + hg;
+    const int tile_row0 = qtile * BM, tile_row1 = min(a.Lq, tile_row0 + BM);
+    const int wave_row0 = tile_row0 + wave * 32;
+    const int qrow = wave_row0 + l32;
+    const int rr = min(qrow, a.Lq - 1);
+    const int qp = a.causal ? pos_of(a.qpos, rr) : 0;
+
+    const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes
+    const char* kg = nullptr;   // per block, set at the top of the block loop
+    const char* vg = nullptr;
+    const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
+
+    bf16x8 qf[KSTEPS], dof[KSTEPS];
+    {
+      const size_t off = (((size_t)b * a.Lq + rr) * a.hq + h) * HS + 8 * hl;
 #pragma unroll
-  for (int ks = 0; ks < KSTEPS; ++ks) {
-    settle(qf[ks]);
-    settle(dof[ks]);
-  }
-  settle(l2);
-  settle(dlt);
-
-  f32x16 dq[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db) zero16(dq[db]);
-
-  PosDesc32 kpos = {0, 0, 0, 0};
-  TileRanges tr = {0, 0, 0, 0};
-  int na = 0, nt = 0;
-  auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
-  const bool wave_live = wave_row0 < a.Lq;
-  const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, min(a.Lq, wave_row0 + 32)) : 0;
-
-  // staging: one 16 B chunk of K and of V per thread and tile; the tile base is wave-uniform, the per-thread
-  // byte offset constant, rows past the last key clamped by a min on the offset
-  const int st_row = tid / CPR, st_col = tid % CPR;
-  const bool stager = st_row < KT;
-  const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
-  u32x4 kreg, vreg;
-  auto fetch = [&](int it) {
-    if (stager) {
-      const int key0 = tile_of(it) * KT;
-      const uint32_t lim = (uint32_t)min(a.Lk - 1 - key0, KT - 1) * row_bytes + st_col * 16;
-      const uint32_t off = min(st_off, lim);
-      kreg = *(const u32x4*)(kg + (size_t)key0 * row_bytes + off);
-      vreg = *(const u32x4*)(vg + (size_t)key0 * row_bytes + off);
-    }
-  };
-  auto stash = [&](int buf) {
-    if (stager) {
-      char* base = lds + buf * STAGE;
-      *(u32x4*)(base + st_row * USTR + st_col * 16) = kreg;
-      *(u32x4*)(base + KT * USTR + st_row * USTR + st_col * 16) = vreg;
-    }
-  };
-  const int tr_off = tr_lane_offset<USTR>(lane);
-  const int row_off = l32 * USTR + hl * 16;
-
-  for (int blk = 0; blk < a.n_blocks; ++blk) {
-  kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
-  tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
-  na = tr.a1 - tr.a0;
-  nt = na + (tr.b1 - tr.b0);
-  if (nt == 0) continue;                   // workgroup-uniform
-  kg = (const char*)ap->k[blk] + kv_head_off;
-  vg = (const char*)ap->v[blk] + kv_head_off;
-  fetch(0);
-  stash(0);                                // the previous block's last step ended on a barrier
-  __syncthreads();
-  for (int it = 0; it < nt; ++it) {
-    const bool more = it + 1 < nt;
-    if (more) fetch(it + 1);
-    __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
-    const char* k_s = lds + (it & 1) * STAGE;
-    const char* v_s = k_s + KT * USTR;
-    const int key0 = tile_of(it) * KT;
-
-    // S^T = K Q^T and dP^T = V dO^T   (rows = keys, cols = queries)
-    f32x16 s, dp;
-    zero16(s);
-    zero16(dp);
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      const bf16x8 kf = *(const bf16x8*)(k_s + row_off + ks * 32);
-      const bf16x8 vf = *(const bf16x8*)(v_s + row_off + ks * 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dp, 0, 0, 0);
-    }
-
-    const int key1 = min(a.Lk, key0 + KT);
-    bool need_mask = key0 + KT > a.Lk;
-    if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2));
-    if (need_mask) {     // wave-uniform and rare: tiles on the causal boundary or the ragged tail
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = key0 + 8 * (i >> 2) + 4 * hl + (i & 3);
-        const bool vis = key < a.Lk && (!a.causal || pos_of(kpos, key) <= qp);
-        s[i] = vis ? s[i] : 0.f;
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        qf[ks] = *(const bf16x8*)((const __bf16*)a.q + off + 16 * ks);
+        dof[ks] = *(const bf16x8*)((const __bf16*)a.d_o + off + 16 * ks);
       }
     }
-    float ds[16];
+    const size_t stat = ((size_t)b * a.hq + h) * a.Lq + rr;
+    const float lse = a.lse[stat];
+    float dlt = a.delta[stat];
+    float l2 = (lse == -INFINITY) ? INFINITY : lse * kLog2e;   // a row that saw nothing: P = 0
 #pragma unroll
-    for (int i = 0; i < 16; ++i) ds[i] = s[i] * (dp[i] - dlt);
-    bf16x8 dsf[2];
-    pack_b_operand(ds, dsf[0], dsf[1]);
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      settle(qf[ks]);
+      settle(dof[ks]);
+    }
+    settle(l2);
+    settle(dlt);
 
-    // dQ^T += K^T dS^T   (rows = head dims, cols = queries, k = keys)
+    f32x16 dq[DB];
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 kt = tr_read<USTR>(k_s + tr_off + (16 * st) * USTR + db * 64);
-        dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf[st], dq[db], 0, 0, 0);
+    for (int db = 0; db < DB; ++db) zero16(dq[db]);
+
+    PosDesc32 kpos = {0, 0, 0, 0};
+    TileRanges tr = {0, 0, 0, 0};
+    int na = 0, nt = 0;
+    auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
+    const bool wave_live = wave_row0 < a.Lq;
+    const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, min(a.Lq, wave_row0 + 32)) : 0;
+
+    // staging: one 16 B chunk of K and of V per thread and tile; the tile base is wave-uniform, the per-thread
+    // byte offset constant, rows past the last key clamped by a min on the offset
+    const int st_row = tid / CPR, st_col = tid % CPR;
+    const bool stager = st_row < KT;
+    const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
+    u32x4 kreg, vreg;
+    auto fetch = [&](int it) {
+      if (stager) {
+        const int key0 = tile_of(it) * KT;
+        const uint32_t lim = (uint32_t)min(a.Lk - 1 - key0, KT - 1) * row_bytes + st_col * 16;
+        const uint32_t off = min(st_off, lim);
+        kreg = *(const u32x4*)(kg + (size_t)key0 * row_bytes + off);
+        vreg = *(const u32x4*)(vg + (size_t)key0 * row_bytes + off);
       }
-    if (more) stash((it + 1) & 1);
+    };
+    auto stash = [&](int buf) {
+      if (stager) {
+        char* base = lds + buf * STAGE;
+        *(u32x4*)(base + st_row * USTR + st_col * 16) = kreg;
+        *(u32x4*)(base + KT * USTR + st_row * USTR + st_col * 16) = vreg;
+      }
+    };
+    const int tr_off = tr_lane_offset<USTR>(lane);
+    const int row_off = l32 * USTR + hl * 16;
+
+    for (int blk = 0; blk < a.n_blocks; ++blk) {
+    kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
+    tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
+    na = tr.a1 - tr.a0;
+    nt = na + (tr.b1 - tr.b0);
+    if (nt == 0) continue;                   // workgroup-uniform
+    kg = (const char*)ap->k[blk] + kv_head_off;
+    vg = (const char*)ap->v[blk] + kv_head_off;
+    fetch(0);
+    stash(0);                                // the previous block's last step ended on a barrier
     __syncthreads();
-  }
-  }   // blocks
+    for (int it = 0; it < nt; ++it) {
+      const bool more = it + 1 < nt;
+      if (more) fetch(it + 1);
+      __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
+      const char* k_s = lds + (it & 1) * STAGE;
+      const char* v_s = k_s + KT * USTR;
+      const int key0 = tile_of(it) * KT;
 
-  unsigned own_ticket = kNoDraw;
-  if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
-  if (qrow < a.Lq) {
-    float* dst = a.dq + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
+      // S^T = K Q^T and dP^T = V dO^T   (rows = keys, cols = queries)
+      f32x16 s, dp;
+      zero16(s);
+      zero16(dp);
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4 v4 = {dq[db][4 * j] * a.scale, dq[db][4 * j + 1] * a.scale, dq[db][4 * j + 2] * a.scale,
-                    dq[db][4 * j + 3] * a.scale};
-        f32x4* d = (f32x4*)(dst + db * 32 + j * 8);
-        if (a.accumulate) v4 += *d;
-        *d = v4;
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const bf16x8 kf = *(const bf16x8*)(k_s + row_off + ks * 32);
+        const bf16x8 vf = *(const bf16x8*)(v_s + row_off + ks * 32);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dp, 0, 0, 0);
       }
-  }
-  if (threadIdx.x == 0) {
-    unsigned empty = empty_queues;
-    next_item[turn] = queues.finish(own_ticket, empty);
-    empty_queues = empty;
-  }
+
+      const int key1 = min(a.Lk, key0 + KT);
+      bool need_mask = key0 + KT > a.Lk;
+      if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2));
+      if (need_mask) {     // wave-uniform and rare: tiles on the causal boundary or the ragged tail
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = key0 + 8 * (i >> 2) + 4 * hl + (i & 3);
+          const bool vis = key < a.Lk && (!a.causal || pos_of(kpos, key) <= qp);
+          s[i] = vis ? s[i] : 0.f;
+        }
+      }
+      float ds[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) ds[i] = s[i] * (dp[i] - dlt);
+      bf16x8 dsf[2];
+      pack_b_operand(ds, dsf[0], dsf[1]);
+
+      // dQ^T += K^T dS^T   (rows = head dims, cols = queries, k = keys)
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 kt = tr_read<USTR>(k_s + tr_off + (16 * st) * USTR + db * 64);
+          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf[st], dq[db], 0, 0, 0);
+        }
+      if (more) stash((it + 1) & 1);
+      __syncthreads();
+    }
+    }   // blocks
+
+    unsigned own_ticket = kNoDraw;
+    if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
+    if (qrow < a.Lq) {
+      float* dst = a.dq + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          f32x4 v4 = {dq[db][4 * j] * a.scale, dq[db][4 * j + 1] * a.scale, dq[db][4 * j + 2] * a.scale,
+                      dq[db][4 * j + 3] * a.scale};
+          f32x4* d = (f32x4*)(dst + db * 32 + j * 8);
+          if (a.accumulate) v4 += *d;
+          *d = v4;
+        }
+    }
+    if (threadIdx.x == 0) {
+      unsigned empty = empty_queues;
+      next_item[turn] = queues.finish(own_ticket, empty);
+      empty_queues = empty;
+    }
   }   // next work item
 }
 

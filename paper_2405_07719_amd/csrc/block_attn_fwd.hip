@@ -126,351 +126,351 @@ void block_attn_fwd_mfma(const AttnArgs) {
     empty_queues = 0;
   }
   for (;;) {
-  // The kernel arguments are read anew for every item, through a pointer to the argument segment that the
-  // compiler cannot see through.  Read once, everything derived from them (reciprocals of the item decode, strides,
-  // flags) would be hoisted out of the item loop and held in scalar registers across it; there are not enough,
-  // and the overflow goes to lanes of a vector register that the tile loop cannot spare.
-  auto ap = (const __attribute__((address_space(4))) AttnArgs*)__builtin_amdgcn_kernarg_segment_ptr();
-  asm volatile("" : "+s"(ap));
-  const int n_items = ap->n_items;
-  __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
-  int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
-  turn ^= 1;
-  if (w >= n_items) {
-    if (threadIdx.x == 0) ItemQueues{ap->ticket_slot, n_items, (int)gridDim.x, ap->n_queues}.leave();
-    break;
-  }
-  ItemArgs a;
-  a.q = ap->q; a.o = ap->o; a.lse = ap->lse;
-  a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
-  a.Lq = ap->Lq; a.Lk = ap->Lk;
-  a.n_qtiles = ap->n_qtiles; a.n_blocks = ap->n_blocks; a.causal = ap->causal;
-  a.scale = ap->scale; a.scale_log2 = ap->scale_log2;
-  a.qpos = PosDesc32{ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
-  a.seq_n = ap->seq_n; a.seq_heads = ap->seq_heads; a.seq_head0 = ap->seq_head0;
-  const int n_groups = a.bs * a.hkv;
-  // The lane constants are derived anew for every item from a thread index the compiler cannot see through:
-  // hoisted out of the item loop they would stay in registers across it, and the tile loop has none to spare.
-  int tid = threadIdx.x;
-  asm volatile("" : "+v"(tid));
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
-  const int l32 = lane & 31, hl = lane >> 5;
-  const int group = w % n_groups; w /= n_groups;
-  const int hg = w % a.g;
-  const int t = w / a.g;
-  const int qtile = a.causal ? a.n_qtiles - 1 - t : t;
-  const int b = group / a.hkv, kvh = group % a.hkv;
-  const int h = kvh * a.g + hg;
-
-  const int tile_row0 = qtile * BM;
-  const int tile_row1 = min(a.Lq, tile_row0 + BM);
-  const int wave_row0 = tile_row0 + wave * (NQB * 32);
-
-  const __bf16* qg = (const __bf16*)a.q;
-  const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes; + key * hkv * HS * 2
-
-  // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
-  bf16x8 qf[NQB][KSTEPS];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int rr = min(wave_row0 + qb * 32 + l32, a.Lq - 1);
-    const __bf16* src = qg + qo_offset(a, b, rr, h, HS) + 8 * hl;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
-  }
-
-  // per-block state of the tile walk (workgroup-uniform), set at the top of the block loop
-  const char* kg = nullptr;
-  const char* vg = nullptr;
-  PosDesc32 kpos = {0, 0, 0, 0};
-  TileRanges tr = {0, 0, 0, 0};
-  int na = 0, nt = 0;
-  auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
-
-  f32x16 oacc[NQB][DB];
-  float m_run[NQB], l_run[NQB];
-  float zero = 0.f;
-  asm volatile("" : "+v"(zero));   // not a constant to the compiler: it would share one zeroed register tuple between items
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_run[qb] = zero;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[qb][db][i] = zero;
-  }
-
-  // wave-level bounds for the mask decision
-  const int wave_row1 = min(a.Lq, wave_row0 + NQB * 32);
-  const bool wave_live = wave_row0 < a.Lq;
-  const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, wave_row1) : 0;
-
-  // ---- staging: each thread moves CPT 16 B chunks of a K tile and of a V tile
-  const int st_row = tid / (HS / 8), st_col = tid % (HS / 8);
-  constexpr int ROWS_PER_PASS = NT / (HS / 8);
-  u32x4 kreg[CPT], vreg[CPT];
-  // Tiles are read through a buffer descriptor built per tile in scalar registers: base = the tile's first row
-  // (this KV head), extent = up to the end of its last valid row.  Each thread adds a 32-bit byte offset that is
-  // the same for every tile; rows past the last key (ragged final tile only) lie beyond the extent and read as
-  // zeros (the mask hides those keys).  No 64-bit address arithmetic on the vector ALU, no clamping.
-  const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
-  uint32_t st_off[CPT];
-#pragma unroll
-  for (int c = 0; c < CPT; ++c) st_off[c] = (uint32_t)(st_row + c * ROWS_PER_PASS) * row_bytes + st_col * 16;
-  auto fetch = [&](const char* base, int it, u32x4* reg) {
-    const int key0 = tile_of(it) * KT;
-    const char* tb = base + (size_t)key0 * row_bytes;
-    const int rows = min(a.Lk - key0, KT);
-    const __amdgpu_buffer_rsrc_t tile = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)tb, 0, (rows - 1) * (int)row_bytes + HS * 2, kRawBufferFlags);
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile, (int)st_off[c], 0, 0);
-  };
-  auto stash = [&](char* buf, int stride, const u32x4* reg) {
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) *(u32x4*)(buf + (st_row + c * ROWS_PER_PASS) * stride + st_col * 16) = reg[c];
-  };
-
-  // ---- S^T = K Q^T for the tile in K buffer kb_ (rows = keys, cols = queries)
-  auto qk = [&](const char* kb_, f32x16 (&sacc)[NQB][KB]) {
-    const char* krow = kb_ + l32 * KSTR + hl * 16;
-    // k-step outermost: consecutive MFMAs go to different accumulators (no back-to-back dependence)
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-#pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk) {
-        const bf16x8 kf = *(const bf16x8*)(krow + kbk * 32 * KSTR + ks * 32);
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-          if (ks == 0) {
-            f32x16 z;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) z[i] = 0.f;
-            sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], z, 0, 0, 0);
-          } else {
-            sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][kbk], 0, 0, 0);
-          }
-        }
-      }
+    // The kernel arguments are read anew for every item, through a pointer to the argument segment that the
+    // compiler cannot see through.  Read once, everything derived from them (reciprocals of the item decode, strides,
+    // flags) would be hoisted out of the item loop and held in scalar registers across it; there are not enough,
+    // and the overflow goes to lanes of a vector register that the tile loop cannot spare.
+    auto ap = (const __attribute__((address_space(4))) AttnArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+    const int n_items = ap->n_items;
+    __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
+    int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
+    turn ^= 1;
+    if (w >= n_items) {
+      if (threadIdx.x == 0) ItemQueues{ap->ticket_slot, n_items, (int)gridDim.x, ap->n_queues}.leave();
+      break;
     }
-  };
+    ItemArgs a;
+    a.q = ap->q; a.o = ap->o; a.lse = ap->lse;
+    a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
+    a.Lq = ap->Lq; a.Lk = ap->Lk;
+    a.n_qtiles = ap->n_qtiles; a.n_blocks = ap->n_blocks; a.causal = ap->causal;
+    a.scale = ap->scale; a.scale_log2 = ap->scale_log2;
+    a.qpos = PosDesc32{ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
+    a.seq_n = ap->seq_n; a.seq_heads = ap->seq_heads; a.seq_head0 = ap->seq_head0;
+    const int n_groups = a.bs * a.hkv;
+    // The lane constants are derived anew for every item from a thread index the compiler cannot see through:
+    // hoisted out of the item loop they would stay in registers across it, and the tile loop has none to spare.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
+    const int l32 = lane & 31, hl = lane >> 5;
+    const int group = w % n_groups; w /= n_groups;
+    const int hg = w % a.g;
+    const int t = w / a.g;
+    const int qtile = a.causal ? a.n_qtiles - 1 - t : t;
+    const int b = group / a.hkv, kvh = group % a.hkv;
+    const int h = kvh * a.g + hg;
 
-  // One pipeline step on tile `it` whose scores are in s_cur.  Unless LAST, the scores of tile it+1
-  // are produced into s_next while the softmax of s_cur runs.
-  const int grp = lane >> 4, j16 = lane & 15;
-  const int v_lane_off = (4 * hl + (j16 >> 2)) * VSTR + (16 * (grp & 1) + 4 * (j16 & 3)) * 2;
-  auto step = [&](auto steady_tag, int it, f32x16 (&s_cur)[NQB][KB], f32x16 (&s_next)[NQB][KB]) {
-    // steady state (tag true): a next tile and a tile after that exist, no branches in the main block;
-    // otherwise the two conditions are evaluated at run time (the last up-to-three tiles)
-    constexpr bool STEADY = decltype(steady_tag)::value;
-    const bool has1 = STEADY || it + 1 < nt;
-    const bool has2 = STEADY || it + 2 < nt;
-    const int key0 = tile_of(it) * KT;
+    const int tile_row0 = qtile * BM;
+    const int tile_row1 = min(a.Lq, tile_row0 + BM);
+    const int wave_row0 = tile_row0 + wave * (NQB * 32);
 
-    // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave
-    const int key1 = min(a.Lk, key0 + KT);
-    bool need_mask = key0 + KT > a.Lk;
-    if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
-    if (need_mask) {
-      int qp[NQB];   // the lane's query position: derived here, where it is rarely needed, rather than kept in a register
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) qp[qb] = a.causal ? pos_of(a.qpos, min(wave_row0 + qb * 32 + l32, a.Lq - 1)) : 0;
-#pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = key0 + kbk * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
-          const bool inb = key < a.Lk;
-          const int kp = a.causal ? pos_of(kpos, key) : 0;
-#pragma unroll
-          for (int qb = 0; qb < NQB; ++qb) {
-            const bool vis = inb && (!a.causal || kp <= qp[qb]);
-            s_cur[qb][kbk][i] = vis ? s_cur[qb][kbk][i] : -INFINITY;
-          }
-        }
-    }
+    const __bf16* qg = (const __bf16*)a.q;
+    const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes; + key * hkv * HS * 2
 
-    // ---- row maxima; the running maximum only moves when a row grew by more than the threshold, so the
-    //      accumulator rescale is rare (P is then bounded by 2^threshold instead of 1)
-    float mc[NQB];
-    bool grow = false;
-    float mx[NQB];
+    // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
+    bf16x8 qf[NQB][KSTEPS];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      float x = -INFINITY;
+      const int rr = min(wave_row0 + qb * 32 + l32, a.Lq - 1);
+      const __bf16* src = qg + qo_offset(a, b, rr, h, HS) + 8 * hl;
 #pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x = fmaxf(x, s_cur[qb][kbk][i]);
-      x = both_halves_max(x);
-      mx[qb] = x;
-      // first visible key of a row (m_run = -inf) always takes the branch: inf > threshold
-      grow = grow || ((x - m_run[qb]) * a.scale_log2 > kRescaleThreshold);
+      for (int ks = 0; ks < KSTEPS; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
     }
-    if (__any(grow)) {
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        const float m_new = fmaxf(m_run[qb], mx[qb]);
-        const float mcn = (m_new == -INFINITY) ? 0.f : m_new * a.scale_log2;
-        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] * a.scale_log2 - mcn);   // m_run = -inf -> 0
-        m_run[qb] = m_new;
-        l_run[qb] *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
-      }
-    }
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) mc[qb] = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb] * a.scale_log2;
 
-    // ---- global prefetch: K two tiles ahead, V one tile ahead
-    if (has2) fetch(kg, it + 2, kreg);
-    if (has1) fetch(vg, it + 1, vreg);
-    // keep the loads up here: left alone, the scheduler sinks them to just before the LDS stores below to
-    // save registers, and every step then waits out a full global-memory latency
-    __builtin_amdgcn_sched_barrier(0);
+    // per-block state of the tile walk (workgroup-uniform), set at the top of the block loop
+    const char* kg = nullptr;
+    const char* vg = nullptr;
+    PosDesc32 kpos = {0, 0, 0, 0};
+    TileRanges tr = {0, 0, 0, 0};
+    int na = 0, nt = 0;
+    auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
 
-    // ---- main block: scores of the next tile on the matrix core, softmax of this tile on the vector ALU
-    if (has1) qk(kbuf + ((it + 1) & 1) * KBYTES, s_next);
-
-    bf16x8 pf[NQB][PS];
+    f32x16 oacc[NQB][DB];
+    float m_run[NQB], l_run[NQB];
+    float zero = 0.f;
+    asm volatile("" : "+v"(zero));   // not a constant to the compiler: it would share one zeroed register tuple between items
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      float rs = l_run[qb];
-#pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk) {
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          u32x4 pk;
-#pragma unroll
-          for (int pr = 0; pr < 4; ++pr) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][kbk][half * 8 + 2 * pr], a.scale_log2, -mc[qb]));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][kbk][half * 8 + 2 * pr + 1], a.scale_log2, -mc[qb]));
-            f32x2 pp = {p0, p1};
-            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-            rs += p0 + p1;
-            pk[pr] = __builtin_bit_cast(uint32_t, pb);
-          }
-          pf[qb][kbk * 2 + half] = __builtin_bit_cast(bf16x8, pk);
-        }
-      }
-      l_run[qb] = rs;
-    }
-
-    // ---- O^T += V^T P^T   (rows = head dims, cols = queries, k = keys)
-    // MFMA k index e of lane half hl in step s is key 16 s + 8 (e / 4) + 4 hl + (e % 4): the
-    // accumulator layout of S^T.  The transpose read returns, for a 16-lane group whose lane j
-    // points at (key base + j / 4, dim base + 4 (j % 4)), the 4 keys of dim base + j to lane j.
-    const char* vlane = vbuf + (it & 1) * VBYTES + v_lane_off;
-#pragma unroll
-    for (int s = 0; s < PS; ++s) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const char* p0 = vlane + (16 * s) * VSTR + db * 64;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-          oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][s], oacc[qb][db], 0, 0, 0);
-      }
-    }
-
-    // ---- hand the prefetched tiles to LDS: K(it+2) replaces K(it), V(it+1) replaces V(it-1)
-    if (has2) stash(kbuf + (it & 1) * KBYTES, KSTR, kreg);
-    if (has1) stash(vbuf + ((it + 1) & 1) * VBYTES, VSTR, vreg);
-    __syncthreads();
-  };
-
-  const std::integral_constant<bool, true> steady;
-  const std::integral_constant<bool, false> draining;
-  for (int blk = 0; blk < a.n_blocks; ++blk) {
-    kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
-    tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
-    na = tr.a1 - tr.a0;
-    nt = na + (tr.b1 - tr.b0);
-    if (nt == 0) continue;         // nothing of this block is visible to the query tile (workgroup-uniform)
-    kg = (const char*)ap->k[blk] + kv_head_off;
-    vg = (const char*)ap->v[blk] + kv_head_off;
-
-    // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0.  (Every step ends on a barrier, so the previous
-    //      block's last reads of these buffers are over.)
-    fetch(kg, 0, kreg);
-    fetch(vg, 0, vreg);
-    stash(kbuf, KSTR, kreg);
-    stash(vbuf, VSTR, vreg);
-    if (nt > 1) {
-      fetch(kg, 1, kreg);
-      stash(kbuf + KBYTES, KSTR, kreg);
-    }
-    __syncthreads();
-    f32x16 s0[NQB][KB], s1[NQB][KB];   // scores of the current and of the next tile
-    // s1 starts undefined and says so: an empty asm "defines" it.  Otherwise the compiler carries its stale value
-    // from the previous block and item around every loop (the draining steps below may leave it untouched), as a
-    // zero-initialised 32-register tuple that it keeps in scratch.
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-      for (int kbk = 0; kbk < KB; ++kbk) asm volatile("" : "=v"(s1[qb][kbk]));
-    qk(kbuf, s0);
-    __syncthreads();   // step 0 overwrites K buffer 0 with tile 2: every wave must have read tile 0 first
-
-    int it = 0;
-    for (; it + 3 < nt; it += 2) {   // two steps per trip so the score registers swap roles without copies
-      step(steady, it, s0, s1);
-      step(steady, it + 1, s1, s0);
-    }
-    for (; it < nt; ++it) {          // at most three tiles left
-      step(draining, it, s0, s1);
-      if (it + 1 < nt) {             // (the last step leaves s1 undefined: nothing may read it)
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-          for (int kbk = 0; kbk < KB; ++kbk) s0[qb][kbk] = s1[qb][kbk];
-      }
-    }
-  }
-
-  const ItemQueues queues = {ap->ticket_slot, n_items, (int)gridDim.x, ap->n_queues};
-  unsigned own_ticket = kNoDraw;
-  if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
-  // ---- epilogue: normalise, write O (a row that saw no key at all: l = 0 -> O = 0, LSE = -inf)
-  // ---- write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const float l_tot = both_halves_sum(l_run[qb]);
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    const int qrow = wave_row0 + qb * 32 + l32;
-    if (qrow < a.Lq) {
-      OutT* dst = (OutT*)a.o + qo_offset(a, b, qrow, h, HS) + 4 * hl;
+      m_run[qb] = -INFINITY;
+      l_run[qb] = zero;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          f32x4 v4 = {oacc[qb][db][4 * j] * inv, oacc[qb][db][4 * j + 1] * inv, oacc[qb][db][4 * j + 2] * inv,
-                      oacc[qb][db][4 * j + 3] * inv};
-          OutT* d = dst + db * 32 + j * 8;
-          if constexpr (sizeof(OutT) == 4) {
-            *(f32x4*)d = v4;
-          } else {
-            u32x2 pk = {pack_bf16(v4[0], v4[1]), pack_bf16(v4[2], v4[3])};
-            *(u32x2*)d = pk;
+        for (int i = 0; i < 16; ++i) oacc[qb][db][i] = zero;
+    }
+
+    // wave-level bounds for the mask decision
+    const int wave_row1 = min(a.Lq, wave_row0 + NQB * 32);
+    const bool wave_live = wave_row0 < a.Lq;
+    const int wave_qmin = (a.causal && wave_live) ? pos_min(a.qpos, wave_row0, wave_row1) : 0;
+
+    // ---- staging: each thread moves CPT 16 B chunks of a K tile and of a V tile
+    const int st_row = tid / (HS / 8), st_col = tid % (HS / 8);
+    constexpr int ROWS_PER_PASS = NT / (HS / 8);
+    u32x4 kreg[CPT], vreg[CPT];
+    // Tiles are read through a buffer descriptor built per tile in scalar registers: base = the tile's first row
+    // (this KV head), extent = up to the end of its last valid row.  Each thread adds a 32-bit byte offset that is
+    // the same for every tile; rows past the last key (ragged final tile only) lie beyond the extent and read as
+    // zeros (the mask hides those keys).  No 64-bit address arithmetic on the vector ALU, no clamping.
+    const uint32_t row_bytes = (uint32_t)a.hkv * HS * 2;
+    uint32_t st_off[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) st_off[c] = (uint32_t)(st_row + c * ROWS_PER_PASS) * row_bytes + st_col * 16;
+    auto fetch = [&](const char* base, int it, u32x4* reg) {
+      const int key0 = tile_of(it) * KT;
+      const char* tb = base + (size_t)key0 * row_bytes;
+      const int rows = min(a.Lk - key0, KT);
+      const __amdgpu_buffer_rsrc_t tile = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)tb, 0, (rows - 1) * (int)row_bytes + HS * 2, kRawBufferFlags);
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile, (int)st_off[c], 0, 0);
+    };
+    auto stash = [&](char* buf, int stride, const u32x4* reg) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) *(u32x4*)(buf + (st_row + c * ROWS_PER_PASS) * stride + st_col * 16) = reg[c];
+    };
+
+    // ---- S^T = K Q^T for the tile in K buffer kb_ (rows = keys, cols = queries)
+    auto qk = [&](const char* kb_, f32x16 (&sacc)[NQB][KB]) {
+      const char* krow = kb_ + l32 * KSTR + hl * 16;
+      // k-step outermost: consecutive MFMAs go to different accumulators (no back-to-back dependence)
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+#pragma unroll
+        for (int kbk = 0; kbk < KB; ++kbk) {
+          const bf16x8 kf = *(const bf16x8*)(krow + kbk * 32 * KSTR + ks * 32);
+#pragma unroll
+          for (int qb = 0; qb < NQB; ++qb) {
+            if (ks == 0) {
+              f32x16 z;
+#pragma unroll
+              for (int i = 0; i < 16; ++i) z[i] = 0.f;
+              sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], z, 0, 0, 0);
+            } else {
+              sacc[qb][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][kbk], 0, 0, 0);
+            }
           }
         }
-      if (hl == 0) {
-        const float lse = l_tot > 0.f ? m_run[qb] * a.scale + __logf(l_tot) : -INFINITY;
-        a.lse[((size_t)b * a.hq + h) * a.Lq + qrow] = lse;
+      }
+    };
+
+    // One pipeline step on tile `it` whose scores are in s_cur.  Unless LAST, the scores of tile it+1
+    // are produced into s_next while the softmax of s_cur runs.
+    const int grp = lane >> 4, j16 = lane & 15;
+    const int v_lane_off = (4 * hl + (j16 >> 2)) * VSTR + (16 * (grp & 1) + 4 * (j16 & 3)) * 2;
+    auto step = [&](auto steady_tag, int it, f32x16 (&s_cur)[NQB][KB], f32x16 (&s_next)[NQB][KB]) {
+      // steady state (tag true): a next tile and a tile after that exist, no branches in the main block;
+      // otherwise the two conditions are evaluated at run time (the last up-to-three tiles)
+      constexpr bool STEADY = decltype(steady_tag)::value;
+      const bool has1 = STEADY || it + 1 < nt;
+      const bool has2 = STEADY || it + 2 < nt;
+      const int key0 = tile_of(it) * KT;
+
+      // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave
+      const int key1 = min(a.Lk, key0 + KT);
+      bool need_mask = key0 + KT > a.Lk;
+      if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
+      if (need_mask) {
+        int qp[NQB];   // the lane's query position: derived here, where it is rarely needed, rather than kept in a register
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) qp[qb] = a.causal ? pos_of(a.qpos, min(wave_row0 + qb * 32 + l32, a.Lq - 1)) : 0;
+#pragma unroll
+        for (int kbk = 0; kbk < KB; ++kbk)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = key0 + kbk * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
+            const bool inb = key < a.Lk;
+            const int kp = a.causal ? pos_of(kpos, key) : 0;
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) {
+              const bool vis = inb && (!a.causal || kp <= qp[qb]);
+              s_cur[qb][kbk][i] = vis ? s_cur[qb][kbk][i] : -INFINITY;
+            }
+          }
+      }
+
+      // ---- row maxima; the running maximum only moves when a row grew by more than the threshold, so the
+      //      accumulator rescale is rare (P is then bounded by 2^threshold instead of 1)
+      float mc[NQB];
+      bool grow = false;
+      float mx[NQB];
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        float x = -INFINITY;
+#pragma unroll
+        for (int kbk = 0; kbk < KB; ++kbk)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) x = fmaxf(x, s_cur[qb][kbk][i]);
+        x = both_halves_max(x);
+        mx[qb] = x;
+        // first visible key of a row (m_run = -inf) always takes the branch: inf > threshold
+        grow = grow || ((x - m_run[qb]) * a.scale_log2 > kRescaleThreshold);
+      }
+      if (__any(grow)) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+          const float m_new = fmaxf(m_run[qb], mx[qb]);
+          const float mcn = (m_new == -INFINITY) ? 0.f : m_new * a.scale_log2;
+          const float alpha = __builtin_amdgcn_exp2f(m_run[qb] * a.scale_log2 - mcn);   // m_run = -inf -> 0
+          m_run[qb] = m_new;
+          l_run[qb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
+        }
+      }
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) mc[qb] = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb] * a.scale_log2;
+
+      // ---- global prefetch: K two tiles ahead, V one tile ahead
+      if (has2) fetch(kg, it + 2, kreg);
+      if (has1) fetch(vg, it + 1, vreg);
+      // keep the loads up here: left alone, the scheduler sinks them to just before the LDS stores below to
+      // save registers, and every step then waits out a full global-memory latency
+      __builtin_amdgcn_sched_barrier(0);
+
+      // ---- main block: scores of the next tile on the matrix core, softmax of this tile on the vector ALU
+      if (has1) qk(kbuf + ((it + 1) & 1) * KBYTES, s_next);
+
+      bf16x8 pf[NQB][PS];
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        float rs = l_run[qb];
+#pragma unroll
+        for (int kbk = 0; kbk < KB; ++kbk) {
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            u32x4 pk;
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][kbk][half * 8 + 2 * pr], a.scale_log2, -mc[qb]));
+              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][kbk][half * 8 + 2 * pr + 1], a.scale_log2, -mc[qb]));
+              f32x2 pp = {p0, p1};
+              const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+              rs += p0 + p1;
+              pk[pr] = __builtin_bit_cast(uint32_t, pb);
+            }
+            pf[qb][kbk * 2 + half] = __builtin_bit_cast(bf16x8, pk);
+          }
+        }
+        l_run[qb] = rs;
+      }
+
+      // ---- O^T += V^T P^T   (rows = head dims, cols = queries, k = keys)
+      // MFMA k index e of lane half hl in step s is key 16 s + 8 (e / 4) + 4 hl + (e % 4): the
+      // accumulator layout of S^T.  The transpose read returns, for a 16-lane group whose lane j
+      // points at (key base + j / 4, dim base + 4 (j % 4)), the 4 keys of dim base + j to lane j.
+      const char* vlane = vbuf + (it & 1) * VBYTES + v_lane_off;
+#pragma unroll
+      for (int s = 0; s < PS; ++s) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const char* p0 = vlane + (16 * s) * VSTR + db * 64;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+          for (int qb = 0; qb < NQB; ++qb)
+            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][s], oacc[qb][db], 0, 0, 0);
+        }
+      }
+
+      // ---- hand the prefetched tiles to LDS: K(it+2) replaces K(it), V(it+1) replaces V(it-1)
+      if (has2) stash(kbuf + (it & 1) * KBYTES, KSTR, kreg);
+      if (has1) stash(vbuf + ((it + 1) & 1) * VBYTES, VSTR, vreg);
+      __syncthreads();
+    };
+
+    const std::integral_constant<bool, true> steady;
+    const std::integral_constant<bool, false> draining;
+    for (int blk = 0; blk < a.n_blocks; ++blk) {
+      kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
+      tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
+      na = tr.a1 - tr.a0;
+      nt = na + (tr.b1 - tr.b0);
+      if (nt == 0) continue;         // nothing of this block is visible to the query tile (workgroup-uniform)
+      kg = (const char*)ap->k[blk] + kv_head_off;
+      vg = (const char*)ap->v[blk] + kv_head_off;
+
+      // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0.  (Every step ends on a barrier, so the previous
+      //      block's last reads of these buffers are over.)
+      fetch(kg, 0, kreg);
+      fetch(vg, 0, vreg);
+      stash(kbuf, KSTR, kreg);
+      stash(vbuf, VSTR, vreg);
+      if (nt > 1) {
+        fetch(kg, 1, kreg);
+        stash(kbuf + KBYTES, KSTR, kreg);
+      }
+      __syncthreads();
+      f32x16 s0[NQB][KB], s1[NQB][KB];   // scores of the current and of the next tile
+      // s1 starts undefined and says so: an empty asm "defines" it.  Otherwise the compiler carries its stale value
+      // from the previous block and item around every loop (the draining steps below may leave it untouched), as a
+      // zero-initialised 32-register tuple that it keeps in scratch.
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+        for (int kbk = 0; kbk < KB; ++kbk) asm volatile("" : "=v"(s1[qb][kbk]));
+      qk(kbuf, s0);
+      __syncthreads();   // step 0 overwrites K buffer 0 with tile 2: every wave must have read tile 0 first
+
+      int it = 0;
+      for (; it + 3 < nt; it += 2) {   // two steps per trip so the score registers swap roles without copies
+        step(steady, it, s0, s1);
+        step(steady, it + 1, s1, s0);
+      }
+      for (; it < nt; ++it) {          // at most three tiles left
+        step(draining, it, s0, s1);
+        if (it + 1 < nt) {             // (the last step leaves s1 undefined: nothing may read it)
+#pragma unroll
+          for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+            for (int kbk = 0; kbk < KB; ++kbk) s0[qb][kbk] = s1[qb][kbk];
+        }
       }
     }
-  }
-  if (threadIdx.x == 0) {   // waits for the draw only: the stores were issued after it
-    unsigned empty = empty_queues;
-    next_item[turn] = queues.finish(own_ticket, empty);
-    empty_queues = empty;
-  }
+
+    const ItemQueues queues = {ap->ticket_slot, n_items, (int)gridDim.x, ap->n_queues};
+    unsigned own_ticket = kNoDraw;
+    if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
+    // ---- epilogue: normalise, write O (a row that saw no key at all: l = 0 -> O = 0, LSE = -inf)
+    // ---- write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      const float l_tot = both_halves_sum(l_run[qb]);
+      const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+      const int qrow = wave_row0 + qb * 32 + l32;
+      if (qrow < a.Lq) {
+        OutT* dst = (OutT*)a.o + qo_offset(a, b, qrow, h, HS) + 4 * hl;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            f32x4 v4 = {oacc[qb][db][4 * j] * inv, oacc[qb][db][4 * j + 1] * inv, oacc[qb][db][4 * j + 2] * inv,
+                        oacc[qb][db][4 * j + 3] * inv};
+            OutT* d = dst + db * 32 + j * 8;
+            if constexpr (sizeof(OutT) == 4) {
+              *(f32x4*)d = v4;
+            } else {
+              u32x2 pk = {pack_bf16(v4[0], v4[1]), pack_bf16(v4[2], v4[3])};
+              *(u32x2*)d = pk;
+            }
+          }
+        if (hl == 0) {
+          const float lse = l_tot > 0.f ? m_run[qb] * a.scale + __logf(l_tot) : -INFINITY;
+          a.lse[((size_t)b * a.hq + h) * a.Lq + qrow] = lse;
+        }
+      }
+    }
+    if (threadIdx.x == 0) {   // waits for the draw only: the stores were issued after it
+      unsigned empty = empty_queues;
+      next_item[turn] = queues.finish(own_ticket, empty);
+      empty_queues = empty;
+    }
   }   // next work item
 }
 
