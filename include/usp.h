@@ -15,7 +15,7 @@
  *   - no device memory is allocated: scratch comes from the caller (`workspace`), its
  *     size from the matching *_workspace_bytes query (host only, works without a GPU);
  *   - calls may be issued from several host threads and on several streams.  One limit: the
- *     bf16 attention kernels (forward, dQ) hand out their work through counters in 16 KiB static
+ *     bf16 attention kernels (forward, dQ, dK/dV) hand out their work through counters in 16 KiB static
  *     device arrays, 256 sets used in rotation, each set back at zero when its launch ends.  Two
  *     such launches that EXECUTE at the same time (different streams) must therefore be fewer
  *     than 256 attention launches apart in issue order; launches on one stream never overlap.

@@ -56,7 +56,7 @@ struct BwdArgs {
   float scale, scale_log2;
   PosDesc32 qpos;
   PosDesc32 kpos[kMaxBlocks];
-  // dq: its workgroups are persistent and draw their work items (attn_device.h)
+  // the workgroups of both kernels are persistent and draw their work items (attn_device.h); set per launch
   int ticket_slot, n_items, n_queues;
 };
 
@@ -70,6 +70,19 @@ struct DqItemArgs {
   int bs, hq, hkv, g;
   int Lq, Lk;
   int n_tiles, n_blocks, causal, accumulate;
+  float scale, scale_log2;
+  PosDesc32 qpos;
+};
+
+// ... and of the dK/dV kernel.
+struct DkdvItemArgs {
+  const void* q;
+  const void* d_o;
+  const float* lse;
+  const float* delta;
+  int bs, hq, hkv, g;
+  int Lq, Lk;
+  int n_tiles, causal, heads_per_wg;
   float scale, scale_log2;
   PosDesc32 qpos;
 };
@@ -350,7 +363,7 @@ void bwd_dq_kernel(const BwdArgs) {
 // -------------------------------------------------------------------------------------------------
 template <int HS>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
-void bwd_dkdv_kernel(const BwdArgs a) {
+void bwd_dkdv_kernel(const BwdArgs) {
   constexpr int NT = 512, BN = 256, QT = 32;
   constexpr int KSTEPS = HS / 16, DB = HS / 32;
   constexpr int USTR = HS * 2 + 48;        // one row stride that is conflict-free for 16 B row reads AND transpose reads
@@ -363,229 +376,272 @@ void bwd_dkdv_kernel(const BwdArgs a) {
   char* const v_s = smem;                  // [BN][USTR]: the workgroup's V rows, resident for the whole kernel
   char* const lds = smem + BN * USTR;      // [2][STAGE]
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
-  const int l32 = lane & 31, hl = lane >> 5;
-  int w = blockIdx.x;
-  const int n_groups = a.bs * a.hkv;
-  const int group = w % n_groups; w /= n_groups;
-  const int n_hsplit = a.g / a.heads_per_wg;   // workgroups that share a key tile's outputs (1: nobody else)
-  const int hg0 = (w % n_hsplit) * a.heads_per_wg; w /= n_hsplit;
-  const int ktile = w % a.n_tiles;         // ascending local index: keys seen by the most queries first
-  const int blk = w / a.n_tiles;           // K/V block of the ring loop
-  const PosDesc32 kpos = a.kpos[blk];
-  const int b = group / a.hkv, kvh = group % a.hkv;
-  const int tile_key0 = ktile * BN, tile_key1 = min(a.Lk, tile_key0 + BN);
-  const int wave_key0 = tile_key0 + wave * 32;
-  const int key = wave_key0 + l32;
-  const int kk = min(key, a.Lk - 1);
-  const int kp = a.causal ? pos_of(kpos, kk) : 0;
-  const bool key_ok = key < a.Lk;
+  // the upper 16 bytes of the A rows' extra k-step (see stash below) are zeroed once: nothing else writes them
+  if (threadIdx.x < 4 * QT)
+    *(u32x4*)(lds + (threadIdx.x / QT) * (QT * USTR) + (threadIdx.x % QT) * USTR + XOFF + 16) = u32x4{0, 0, 0, 0};
 
-  // B operands of S = Q K^T and dP = dO V^T: lane = key l32, dims 16 ks + 8 hl ..  The K fragments stay in
-  // registers; the V fragments are read from LDS every step (both in registers next to the two accumulators
-  // do not fit 256 VGPRs: the spills' reloads share the counter of the prefetch loads and stall on them).
-  bf16x8 kf[KSTEPS];
-  {
-    const size_t off = (((size_t)b * a.Lk + kk) * a.hkv + kvh) * HS + 8 * hl;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8*)((const __bf16*)a.k[blk] + off + 16 * ks);
-    const char* vg = (const char*)((const __bf16*)a.v[blk] + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
-    const uint32_t v_row_bytes = (uint32_t)a.hkv * HS * 2;
-#pragma unroll
-    for (int c = 0; c < BN * CPR / NT; ++c) {
-      const int r = (tid + c * NT) / CPR, col = (tid + c * NT) % CPR;
-      const int krow = min(tile_key0 + r, a.Lk - 1);
-      *(u32x4*)(v_s + r * USTR + col * 16) = *(const u32x4*)(vg + (size_t)krow * v_row_bytes + col * 16);
-    }
+  // Persistent workgroups, one per CU, that draw their work items as the forward kernel's do.  Item order: KV
+  // group fastest, then the head split, then the key tile (ascending: keys seen by the most queries first), then
+  // the K/V block of the ring loop.
+  __shared__ int next_item[2];
+  __shared__ unsigned empty_queues;
+  int turn = 0;
+  if (threadIdx.x == 0) {
+    next_item[0] = blockIdx.x;   // the first item is given, not drawn
+    empty_queues = 0;
   }
-  const char* v_row = v_s + (wave * 32 + l32) * USTR + hl * 16;
-#pragma unroll
-  for (int ks = 0; ks < KSTEPS; ++ks) settle(kf[ks]);
-  f32x16 dk[DB], dv[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db) {
-    zero16(dk[db]);
-    zero16(dv[db]);
-  }
-
-  const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, kpos, a.Lq, tile_key0, tile_key1);
-  const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
-  // Query tiles are walked from the LAST one down: every workgroup of a head then starts on the same tile and
-  // the ones running side by side on an XCD read the same Q / dO rows at about the same time (one L2 fill
-  // serves them all); walking up from each workgroup's own diagonal would spread them over the sequence.
-  auto tile_of = [&](int it) { const int j = nt - 1 - it; return j < na ? tr.a0 + j : tr.b0 + (j - na); };
-  const bool wave_live = wave_key0 < a.Lk;
-  const int wave_kmax = (a.causal && wave_live) ? pos_max(kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
-
-  const int st_row = tid / CPR, st_col = tid % CPR;
-  const bool stager = st_row < QT;
-  u32x4 qreg, oreg;
-  float streg = 0.f;
-  // tile base addresses are wave-uniform; the per-thread byte offset is the same for every tile, clamped by a
-  // min on the offset for rows past the last query (offsets grow with the row)
-  const uint32_t row_bytes = (uint32_t)a.hq * HS * 2;
-  const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
-  const char* qg = nullptr;      // per query head, set at the top of the head loop
-  const char* og = nullptr;
-  const float* stat_g = nullptr;
-  const float inv_scale = 1.0f / a.scale;
-  auto fetch = [&](int it) {
-    const int q0 = tile_of(it) * QT;
-    if (stager) {
-      const uint32_t lim = (uint32_t)min(a.Lq - 1 - q0, QT - 1) * row_bytes + st_col * 16;
-      const uint32_t off = min(st_off, lim);
-      qreg = *(const u32x4*)(qg + (size_t)q0 * row_bytes + off);
-      oreg = *(const u32x4*)(og + (size_t)q0 * row_bytes + off);
+  for (;;) {
+    // arguments and lane constants are read / derived anew for every item, so that nothing derived from them is
+    // carried in registers across the item loop
+    auto ap = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+    const ItemQueues queues = {ap->ticket_slot, ap->n_items, (int)gridDim.x, ap->n_queues};
+    __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
+    int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
+    turn ^= 1;
+    if (w >= queues.n_items) {
+      if (threadIdx.x == 0) queues.leave();
+      break;
     }
-    if (tid < 2 * QT) streg = stat_g[min(q0 + (tid % QT), a.Lq - 1)];   // raw: converted when stashed, not here
-  };
-  auto stash = [&](int buf) {
-    char* base = lds + buf * STAGE;
-    if (stager) {
-      *(u32x4*)(base + st_row * USTR + st_col * 16) = qreg;
-      *(u32x4*)(base + QT * USTR + st_row * USTR + st_col * 16) = oreg;
-    }
-    if (tid < 2 * QT) {
-      // The row statistics ride through the matrix core: with one more k-step whose A row is x split into three
-      // bf16 pieces (exact to fp32 accuracy) and whose B column is 1, 1, 1, the first product comes out as
-      // q.k - LSE/scale (threads 0..QT-1, into the Q rows) and dO.v - D (the next QT threads, into the dO rows)
-      // without any per-row read by the 16 rows a lane holds.  A row that saw nothing gets -1e30: P = 0.
-      float x = tid < QT ? ((streg == -INFINITY) ? -1e30f : fmaxf(fminf(-streg * inv_scale, 1e30f), -1e30f)) : -streg;
-      const __bf16 hi = (__bf16)x;
-      x -= (float)hi;
-      const __bf16 mid = (__bf16)x;
-      x -= (float)mid;
-      const __bf16 lo = (__bf16)x;
-      const bf16x8 piece = {hi, mid, lo, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
-      *(bf16x8*)(base + (tid < QT ? 0 : QT * USTR) + (tid % QT) * USTR + XOFF) = piece;
-    }
-  };
-  const int tr_off = tr_lane_offset<USTR>(lane);
-  const int row_off = l32 * USTR + hl * 16;
-  // B operand of the extra k-step: k indices 0..2 are one (lanes of the lower half hold k 0..7), the rest zero;
-  // the upper 16 bytes of the A rows' extra step are zeroed once (nothing else writes them)
-  bf16x8 ones;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)((hl == 0 && e < 3) ? 1.f : 0.f);
-  if (tid < 4 * QT) *(u32x4*)(lds + (tid / QT) * (QT * USTR) + (tid % QT) * USTR + XOFF + 16) = u32x4{0, 0, 0, 0};
+    DkdvItemArgs a;
+    a.q = ap->q; a.d_o = ap->d_o; a.lse = ap->lse; a.delta = ap->delta;
+    a.bs = ap->bs; a.hq = ap->hq; a.hkv = ap->hkv; a.g = ap->g;
+    a.Lq = ap->Lq; a.Lk = ap->Lk;
+    a.n_tiles = ap->n_tiles; a.causal = ap->causal; a.heads_per_wg = ap->heads_per_wg;
+    a.scale = ap->scale; a.scale_log2 = ap->scale_log2;
+    a.qpos = PosDesc32{ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
+    const int l32 = lane & 31, hl = lane >> 5;
+    const int n_groups = a.bs * a.hkv;
+    const int group = w % n_groups; w /= n_groups;
+    const int n_hsplit = a.g / a.heads_per_wg;   // workgroups that share a key tile's outputs (1: nobody else)
+    const int hg0 = (w % n_hsplit) * a.heads_per_wg; w /= n_hsplit;
+    const int ktile = w % a.n_tiles;         // ascending local index: keys seen by the most queries first
+    const int blk = w / a.n_tiles;           // K/V block of the ring loop
+    const PosDesc32 kpos = {ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
+    const int b = group / a.hkv, kvh = group % a.hkv;
+    const int tile_key0 = ktile * BN, tile_key1 = min(a.Lk, tile_key0 + BN);
+    const int wave_key0 = tile_key0 + wave * 32;
+    const int key = wave_key0 + l32;
+    const int kk = min(key, a.Lk - 1);
+    const int kp = a.causal ? pos_of(kpos, kk) : 0;
+    const bool key_ok = key < a.Lk;
 
-  // The query heads of the KV group that this workgroup walks (all g of them when the grid is large enough
-  // without splitting them: then nobody else adds to these keys' dK/dV and the epilogue is a plain store).
-  for (int hh = 0; hh < a.heads_per_wg; ++hh) {
-  const int h = kvh * a.g + hg0 + hh;
-  qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
-  og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
-  stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
-  if (nt > 0) {
-    fetch(0);
-    stash(0);                              // the previous head's last step ended on a barrier
-  }
-  __syncthreads();
-  for (int it = 0; it < nt; ++it) {
-    const bool more = it + 1 < nt;
-    if (more) fetch(it + 1);
-    __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
-    const char* base = lds + (it & 1) * STAGE;
-    const char* q_s = base;
-    const char* o_s = base + QT * USTR;
-    const int q0 = tile_of(it) * QT;
-
-    // S = Q K^T and dP = dO V^T: rows = queries, cols = keys
-    f32x16 s, dp;
-    zero16(s);
-    zero16(dp);
+    // B operands of S = Q K^T and dP = dO V^T: lane = key l32, dims 16 ks + 8 hl ..  The K fragments stay in
+    // registers; the V fragments are read from LDS every step (both in registers next to the two accumulators
+    // do not fit 256 VGPRs: the spills' reloads share the counter of the prefetch loads and stall on them).
+    bf16x8 kf[KSTEPS];
+    {
+      const size_t off = (((size_t)b * a.Lk + kk) * a.hkv + kvh) * HS + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      const bf16x8 qa = *(const bf16x8*)(q_s + row_off + ks * 32);
-      const bf16x8 oa = *(const bf16x8*)(o_s + row_off + ks * 32);
-      const bf16x8 vb = *(const bf16x8*)(v_row + ks * 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vb, dp, 0, 0, 0);
-    }
-    {   // the extra k-step: s -= LSE / scale, dp -= D
-      const bf16x8 qa = *(const bf16x8*)(q_s + row_off + XOFF);
-      const bf16x8 oa = *(const bf16x8*)(o_s + row_off + XOFF);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, ones, s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, ones, dp, 0, 0, 0);
-    }
-
-    // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile.
-    // P and dS overwrite s and dp in place; the mask (rare: tiles on the causal boundary or ragged) sits
-    // behind a wave-uniform branch.
-    const int q1 = min(a.Lq, q0 + QT);
-    bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
-    if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
+      for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8*)((const __bf16*)ap->k[blk] + off + 16 * ks);
+      const char* vg = (const char*)((const __bf16*)ap->v[blk] + ((size_t)b * a.Lk * a.hkv + kvh) * HS);
+      const uint32_t v_row_bytes = (uint32_t)a.hkv * HS * 2;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(s[i] * a.scale_log2);
-    if (need_mask) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int qr = q0 + 8 * (i >> 2) + 4 * hl + (i & 3);
-        const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
-        s[i] = vis ? s[i] : 0.f;
+      for (int c = 0; c < BN * CPR / NT; ++c) {
+        const int r = (tid + c * NT) / CPR, col = (tid + c * NT) % CPR;
+        const int krow = min(tile_key0 + r, a.Lk - 1);
+        *(u32x4*)(v_s + r * USTR + col * 16) = *(const u32x4*)(vg + (size_t)krow * v_row_bytes + col * 16);
       }
     }
+    const char* v_row = v_s + (wave * 32 + l32) * USTR + hl * 16;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) dp[i] *= s[i];
-
-    // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
+    for (int ks = 0; ks < KSTEPS; ++ks) settle(kf[ks]);
+    f32x16 dk[DB], dv[DB];
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      u32x4 pw, dw;
-#pragma unroll
-      for (int pr = 0; pr < 4; ++pr) {
-        pw[pr] = pack_bf16(s[8 * st + 2 * pr], s[8 * st + 2 * pr + 1]);
-        dw[pr] = pack_bf16(dp[8 * st + 2 * pr], dp[8 * st + 2 * pr + 1]);
-      }
-      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw), dsf = __builtin_bit_cast(bf16x8, dw);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 ot = tr_read<USTR>(o_s + tr_off + (16 * st) * USTR + db * 64);
-        const bf16x8 qt = tr_read<USTR>(q_s + tr_off + (16 * st) * USTR + db * 64);
-        dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf, dv[db], 0, 0, 0);
-        dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[db], 0, 0, 0);
-      }
+    for (int db = 0; db < DB; ++db) {
+      zero16(dk[db]);
+      zero16(dv[db]);
     }
-    if (more) stash((it + 1) & 1);
+
+    const TileRanges tr = visible_query_tiles<QT>(a.causal, a.qpos, kpos, a.Lq, tile_key0, tile_key1);
+    const int na = tr.a1 - tr.a0, nt = na + (tr.b1 - tr.b0);
+    // Query tiles are walked from the LAST one down: every workgroup of a head then starts on the same tile and
+    // the ones running side by side on an XCD read the same Q / dO rows at about the same time (one L2 fill
+    // serves them all); walking up from each workgroup's own diagonal would spread them over the sequence.
+    auto tile_of = [&](int it) { const int j = nt - 1 - it; return j < na ? tr.a0 + j : tr.b0 + (j - na); };
+    const bool wave_live = wave_key0 < a.Lk;
+    const int wave_kmax = (a.causal && wave_live) ? pos_max(kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
+
+    const int st_row = tid / CPR, st_col = tid % CPR;
+    const bool stager = st_row < QT;
+    u32x4 qreg, oreg;
+    float streg = 0.f;
+    // tile base addresses are wave-uniform; the per-thread byte offset is the same for every tile, clamped by a
+    // min on the offset for rows past the last query (offsets grow with the row)
+    const uint32_t row_bytes = (uint32_t)a.hq * HS * 2;
+    const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
+    const char* qg = nullptr;      // per query head, set at the top of the head loop
+    const char* og = nullptr;
+    const float* stat_g = nullptr;
+    const float inv_scale = 1.0f / a.scale;
+    auto fetch = [&](int it) {
+      const int q0 = tile_of(it) * QT;
+      if (stager) {
+        const uint32_t lim = (uint32_t)min(a.Lq - 1 - q0, QT - 1) * row_bytes + st_col * 16;
+        const uint32_t off = min(st_off, lim);
+        qreg = *(const u32x4*)(qg + (size_t)q0 * row_bytes + off);
+        oreg = *(const u32x4*)(og + (size_t)q0 * row_bytes + off);
+      }
+      if (tid < 2 * QT) streg = stat_g[min(q0 + (tid % QT), a.Lq - 1)];   // raw: converted when stashed, not here
+    };
+    auto stash = [&](int buf) {
+      char* base = lds + buf * STAGE;
+      if (stager) {
+        *(u32x4*)(base + st_row * USTR + st_col * 16) = qreg;
+        *(u32x4*)(base + QT * USTR + st_row * USTR + st_col * 16) = oreg;
+      }
+      if (tid < 2 * QT) {
+        // The row statistics ride through the matrix core: with one more k-step whose A row is x split into three
+        // bf16 pieces (exact to fp32 accuracy) and whose B column is 1, 1, 1, the first product comes out as
+        // q.k - LSE/scale (threads 0..QT-1, into the Q rows) and dO.v - D (the next QT threads, into the dO rows)
+        // without any per-row read by the 16 rows a lane holds.  A row that saw nothing gets -1e30: P = 0.
+        float x = tid < QT ? ((streg == -INFINITY) ? -1e30f : fmaxf(fminf(-streg * inv_scale, 1e30f), -1e30f)) : -streg;
+        const __bf16 hi = (__bf16)x;
+        x -= (float)hi;
+        const __bf16 mid = (__bf16)x;
+        x -= (float)mid;
+        const __bf16 lo = (__bf16)x;
+        const bf16x8 piece = {hi, mid, lo, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+        *(bf16x8*)(base + (tid < QT ? 0 : QT * USTR) + (tid % QT) * USTR + XOFF) = piece;
+      }
+    };
+    const int tr_off = tr_lane_offset<USTR>(lane);
+    const int row_off = l32 * USTR + hl * 16;
+    // B operand of the extra k-step: k indices 0..2 are one (lanes of the lower half hold k 0..7), the rest zero;
+    // the upper 16 bytes of the A rows' extra step are zeroed once (nothing else writes them)
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)((hl == 0 && e < 3) ? 1.f : 0.f);
+
+    // The query heads of the KV group that this workgroup walks (all g of them when the grid is large enough
+    // without splitting them: then nobody else adds to these keys' dK/dV and the epilogue is a plain store).
+    for (int hh = 0; hh < a.heads_per_wg; ++hh) {
+    const int h = kvh * a.g + hg0 + hh;
+    qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
+    og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
+    stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
+    if (nt > 0) {
+      fetch(0);
+      stash(0);                              // the previous head's last step ended on a barrier
+    }
     __syncthreads();
-  }
-  }   // query heads
+    for (int it = 0; it < nt; ++it) {
+      const bool more = it + 1 < nt;
+      if (more) fetch(it + 1);
+      __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
+      const char* base = lds + (it & 1) * STAGE;
+      const char* q_s = base;
+      const char* o_s = base + QT * USTR;
+      const int q0 = tile_of(it) * QT;
 
-  if (key_ok) {
-    const size_t off = (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
-    float* dkp = a.dk[blk] + off;
-    float* dvp = a.dv[blk] + off;
-    if (n_hsplit > 1) {
+      // S = Q K^T and dP = dO V^T: rows = queries, cols = keys
+      f32x16 s, dp;
+      zero16(s);
+      zero16(dp);
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const bf16x8 qa = *(const bf16x8*)(q_s + row_off + ks * 32);
+        const bf16x8 oa = *(const bf16x8*)(o_s + row_off + ks * 32);
+        const bf16x8 vb = *(const bf16x8*)(v_row + ks * 32);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vb, dp, 0, 0, 0);
+      }
+      {   // the extra k-step: s -= LSE / scale, dp -= D
+        const bf16x8 qa = *(const bf16x8*)(q_s + row_off + XOFF);
+        const bf16x8 oa = *(const bf16x8*)(o_s + row_off + XOFF);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, ones, s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, ones, dp, 0, 0, 0);
+      }
+
+      // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile.
+      // P and dS overwrite s and dp in place; the mask (rare: tiles on the causal boundary or ragged) sits
+      // behind a wave-uniform branch.
+      const int q1 = min(a.Lq, q0 + QT);
+      bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
+      if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+      for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(s[i] * a.scale_log2);
+      if (need_mask) {
 #pragma unroll
-          for (int tt = 0; tt < 4; ++tt) {
-            atomicAdd(dkp + db * 32 + j * 8 + tt, dk[db][4 * j + tt] * a.scale);
-            atomicAdd(dvp + db * 32 + j * 8 + tt, dv[db][4 * j + tt]);
-          }
-    } else {
-      const bool add = a.acc_dkdv[blk] != 0;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          f32x4 k4 = {dk[db][4 * j] * a.scale, dk[db][4 * j + 1] * a.scale, dk[db][4 * j + 2] * a.scale,
-                      dk[db][4 * j + 3] * a.scale};
-          f32x4 v4 = {dv[db][4 * j], dv[db][4 * j + 1], dv[db][4 * j + 2], dv[db][4 * j + 3]};
-          f32x4* kd = (f32x4*)(dkp + db * 32 + j * 8);
-          f32x4* vd = (f32x4*)(dvp + db * 32 + j * 8);
-          if (add) {
-            k4 += *kd;
-            v4 += *vd;
-          }
-          *kd = k4;
-          *vd = v4;
+        for (int i = 0; i < 16; ++i) {
+          const int qr = q0 + 8 * (i >> 2) + 4 * hl + (i & 3);
+          const bool vis = qr < a.Lq && key_ok && (!a.causal || kp <= pos_of(a.qpos, qr));
+          s[i] = vis ? s[i] : 0.f;
         }
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dp[i] *= s[i];
+
+      // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        u32x4 pw, dw;
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+          pw[pr] = pack_bf16(s[8 * st + 2 * pr], s[8 * st + 2 * pr + 1]);
+          dw[pr] = pack_bf16(dp[8 * st + 2 * pr], dp[8 * st + 2 * pr + 1]);
+        }
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw), dsf = __builtin_bit_cast(bf16x8, dw);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 ot = tr_read<USTR>(o_s + tr_off + (16 * st) * USTR + db * 64);
+          const bf16x8 qt = tr_read<USTR>(q_s + tr_off + (16 * st) * USTR + db * 64);
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf, dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[db], 0, 0, 0);
+        }
+      }
+      if (more) stash((it + 1) & 1);
+      __syncthreads();
     }
-  }
+    }   // query heads
+
+    unsigned own_ticket = kNoDraw;
+    if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
+    if (key_ok) {
+      const size_t off = (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
+      float* dkp = ap->dk[blk] + off;
+      float* dvp = ap->dv[blk] + off;
+      if (n_hsplit > 1) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+              atomicAdd(dkp + db * 32 + j * 8 + tt, dk[db][4 * j + tt] * a.scale);
+              atomicAdd(dvp + db * 32 + j * 8 + tt, dv[db][4 * j + tt]);
+            }
+      } else {
+        const bool add = ap->acc_dkdv[blk] != 0;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            f32x4 k4 = {dk[db][4 * j] * a.scale, dk[db][4 * j + 1] * a.scale, dk[db][4 * j + 2] * a.scale,
+                        dk[db][4 * j + 3] * a.scale};
+            f32x4 v4 = {dv[db][4 * j], dv[db][4 * j + 1], dv[db][4 * j + 2], dv[db][4 * j + 3]};
+            f32x4* kd = (f32x4*)(dkp + db * 32 + j * 8);
+            f32x4* vd = (f32x4*)(dvp + db * 32 + j * 8);
+            if (add) {
+              k4 += *kd;
+              v4 += *vd;
+            }
+            *kd = k4;
+            *vd = v4;
+          }
+      }
+    }
+
+    if (threadIdx.x == 0) {
+      unsigned empty = empty_queues;
+      next_item[turn] = queues.finish(own_ticket, empty);
+      empty_queues = empty;
+    }
+  }   // next work item
 }
 
 __global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* dst, size_t n4) {
@@ -708,7 +764,14 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     }
     const int64_t grid = unsplit * (a.g / a.heads_per_wg);
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
-    const int dk_st = hs == 128 ? launch_dkdv<128>(a, grid, stream) : launch_dkdv<64>(a, grid, stream);
+    // one workgroup per CU (256 VGPRs x 8 waves fill it), fewer when there are fewer items
+    a.ticket_slot = next_ticket_slot();
+    a.n_items = (int)grid;
+    // workgroups that walk the same query head share its Q / dO rows through the XCD's L2: one queue per
+    // (KV group, head split) value, the two fastest indices of the item number
+    a.n_queues = std::gcd(dev::kMaxItemQueues, bs * hkv * (a.g / a.heads_per_wg));
+    const int64_t n_wgs = std::min<int64_t>(grid, compute_units());
+    const int dk_st = hs == 128 ? launch_dkdv<128>(a, n_wgs, stream) : launch_dkdv<64>(a, n_wgs, stream);
     if (dk_st != USP_OK) return dk_st;
   }
   return launch_status();
