@@ -155,6 +155,7 @@ constexpr int kTicketSlots = 256;
 constexpr int kMaxItemQueues = 8;
 constexpr int kSlotStride = 16;          // counters per set: eight queues, "left", padding to 64 bytes
 constexpr unsigned kNoDraw = ~0u;
+constexpr int kFirstRun = 8;            // see ItemQueues::first_item
 static __device__ unsigned g_work_ticket[kTicketSlots * kSlotStride];
 
 // the XCD (accelerator complex die) this wave runs on, 0..7
@@ -166,10 +167,25 @@ struct ItemQueues {
   int slot, n_items, n_wgs, n_queues;
   __device__ unsigned* counter(int q) const { return &g_work_ticket[slot * kSlotStride + q]; }
   __device__ unsigned* left() const { return &g_work_ticket[slot * kSlotStride + kMaxItemQueues]; }
-  // Queue q holds items q, q + n_queues, ...  The first n_wgs items of the launch are not drawn: workgroup b starts
-  // with item b (the hardware puts workgroup b on XCD b mod 8, so that is an item of its own queue), which saves
-  // every launch the latency of a first draw.  Draw number t from queue q is therefore item q + n_queues (given(q) + t).
+  // Queue q holds items q, q + n_queues, ...  The first n_wgs items of the launch are not drawn but given: that
+  // saves every launch the latency of a first draw.  Draw number t from queue q is therefore item
+  // q + n_queues (given(q) + t).  Which workgroup is given which item: see first_item().
   __device__ unsigned given(int q) const { return (unsigned)(max(0, n_wgs - q + n_queues - 1) / n_queues); }
+  // The item workgroup b starts with: one of the first n_wgs items, each exactly once.  The hardware puts workgroup
+  // b on XCD b mod 8, so item b would be one of its own queue, but would give the 32 CUs of an XCD 32 different
+  // weights: they would finish their first items one by one, 15 us apart, start their second items one by one, and
+  // such a train of CUs that walk the same K/V a few tiles behind one another is longer than the L2 holds: every
+  // one of them fetches every tile again (five times the fabric traffic, measured).  Instead the XCDs that share a
+  // queue take its given items in runs of kFirstRun: eight CUs of an XCD hold neighbouring weights, finish together
+  // and start their next items together, in step like the first ones.  (Whole XCDs of neighbouring weights would
+  // share even more, but then each XCD's CUs pair their items among themselves and a slow XCD is not helped.)
+  __device__ int first_item(int b) const {
+    if (n_wgs % kMaxItemQueues) return b;   // fewer workgroups than CUs: one item each, nothing to arrange
+    const int x = b % kMaxItemQueues, j = b / kMaxItemQueues, per_xcd = n_wgs / kMaxItemQueues;
+    const int q = x % n_queues, sharers = kMaxItemQueues / n_queues, rank = x / n_queues;
+    const int run = per_xcd % kFirstRun ? per_xcd : kFirstRun;
+    return q + n_queues * (((j / run) * sharers + rank) * run + j % run);
+  }
   __device__ unsigned items_of(int q) const {
     return (unsigned)(max(0, n_items - q + n_queues - 1) / n_queues) - given(q);   // n_wgs <= n_items: never negative
   }

@@ -166,7 +166,9 @@ void bwd_dq_kernel(const BwdArgs) {
   __shared__ unsigned empty_queues;
   int turn = 0;
   if (threadIdx.x == 0) {
-    next_item[0] = blockIdx.x;   // the first item is given, not drawn
+    auto ap0 = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    // the first item is given, not drawn
+    next_item[0] = ItemQueues{ap0->ticket_slot, ap0->n_items, (int)gridDim.x, ap0->n_queues}.first_item(blockIdx.x);
     empty_queues = 0;
   }
   for (;;) {
@@ -387,7 +389,9 @@ void bwd_dkdv_kernel(const BwdArgs) {
   __shared__ unsigned empty_queues;
   int turn = 0;
   if (threadIdx.x == 0) {
-    next_item[0] = blockIdx.x;   // the first item is given, not drawn
+    auto ap0 = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    // the first item is given, not drawn
+    next_item[0] = ItemQueues{ap0->ticket_slot, ap0->n_items, (int)gridDim.x, ap0->n_queues}.first_item(blockIdx.x);
     empty_queues = 0;
   }
   for (;;) {

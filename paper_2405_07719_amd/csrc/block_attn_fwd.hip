@@ -122,7 +122,9 @@ void block_attn_fwd_mfma(const AttnArgs) {
   __shared__ unsigned empty_queues;   // thread 0's record of the item queues it has found empty
   int turn = 0;
   if (threadIdx.x == 0) {
-    next_item[0] = blockIdx.x;   // the first item is given, not drawn (ItemQueues::given)
+    auto ap0 = (const __attribute__((address_space(4))) AttnArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    // the first item is given, not drawn
+    next_item[0] = ItemQueues{ap0->ticket_slot, ap0->n_items, (int)gridDim.x, ap0->n_queues}.first_item(blockIdx.x);
     empty_queues = 0;
   }
   for (;;) {
