@@ -146,11 +146,29 @@ int usp_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* co
                       int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
                       int in_dtype, int o_dtype, void* stream);
 
+/* The same query rows against n_blocks K/V blocks with the key dimension SPLIT over the chip (Sec. 2: the
+ * blockwise loop gives partial results that combine by their log-sum-exp, in any grouping): every (query tile,
+ * head, batch, block) is its own work item of ONE launch, and block j's result goes to its own partial,
+ * o_parts[j] [bs,Lq,hq,hs] fp32 and lse_parts[j] [bs,hq,Lq] float, for usp_lse_merge to combine.  For short
+ * sequences, where the rows of the last query tile alone (one workgroup per tile and head) would take longer
+ * than the whole chip needs for everything: the blocks may be pieces of one K/V tensor.
+ *   k_blocks, v_blocks: HOST arrays of n_blocks DEVICE pointers to the first row of each block; rows are hkv*hs
+ *   elements apart, batches Lk rows apart (so pieces of a [bs,Lk,hkv,hs] tensor are blocks of it);
+ *   lk_blocks: HOST array, keys in each block, 1 <= lk_blocks[j] <= Lk (NULL: Lk each); kpos_blocks as in
+ *   usp_ring_attn_fwd, describing lk_blocks[j] keys each; o_parts, lse_parts: HOST arrays of DEVICE pointers;
+ *   bf16 inputs.  A query row that sees no key of block j gets o = 0, lse = -inf there. */
+int usp_ring_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                               const usp_posdesc* kpos_blocks, const int32_t* lk_blocks, int n_blocks,
+                               float* const* o_parts, float* const* lse_parts, int bs, int64_t Lq, int64_t Lk, int hq,
+                               int hkv, int hs, float scale, int causal, const usp_posdesc* qpos, void* stream);
+
 /* Algorithm 1 forward for virtual ranks [rank_begin, rank_end):
  * all-to-all of Q,K,V -> ring loop of block attention -> LSE merge -> all-to-all of O.
  * With bf16 data and R <= USP_MAX_RING_BLOCKS the ring loop and the merge are the single launch of
  * usp_ring_attn_fwd (all blocks are resident on the one GPU); otherwise one usp_block_attn_fwd per ring step
- * with fp32 partials, then usp_lse_merge.
+ * with fp32 partials, then usp_lse_merge.  Short sequences (fewer query tiles x heads than keep 256 CUs busy for
+ * as long as the last tile takes) run the single launch of usp_ring_attn_fwd_partials over two to eight parts of
+ * the keys, then usp_lse_merge; the workspace query knows.
  *   q, o: seq layout with hc heads; k, v: seq layout with hk heads (ALL N shards must be
  *   present: the ring reads the other ring ranks' K/V where hardware would receive them);
  *   lse: [N][bs][hc/U][L/R] float, written for the ranks in range. */

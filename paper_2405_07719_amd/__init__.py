@@ -65,6 +65,8 @@ def load():
     lib.usp_lse_merge.argtypes = [P(V), P(V), I, V, V, I, L, I, I, I, I, V]
     lib.usp_ring_attn_fwd.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc),
                                       I, I, V]
+    lib.usp_ring_attn_fwd_partials.argtypes = [V, P(V), P(V), P(usp_posdesc), P(C.c_int32), I, P(V), P(V), I, L, L, I, I,
+                                               I, F, I, P(usp_posdesc), V]
     lib.usp_attn_fwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_fwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_fwd.argtypes = [P(usp_problem), V, V, V, V, V, I, I, V, C.c_size_t, V]
@@ -154,6 +156,21 @@ def usp_ring_attn_fwd(q, k_blocks, v_blocks, kpos_blocks, o, lse, bs, Lq, Lk, hq
     _check(load().usp_ring_attn_fwd(_ptr(q), ka, va, kd, n, _ptr(o), _ptr(lse), bs, Lq, Lk, hq, hkv, hs, scale,
                                     int(bool(causal)), C.byref(qpos) if qpos is not None else None, in_dtype,
                                     o_dtype, _stream(stream)), "usp_ring_attn_fwd")
+
+
+def usp_ring_attn_fwd_partials(q, k_blocks, v_blocks, kpos_blocks, lk_blocks, o_parts, lse_parts, bs, Lq, Lk, hq, hkv,
+                               hs, scale, causal, qpos, stream=None):
+    """k_blocks / v_blocks: tensors, or integer device addresses (pieces of one tensor)."""
+    n = len(k_blocks)
+    ka = (C.c_void_p * n)(*[_ptr(x) for x in k_blocks])
+    va = (C.c_void_p * n)(*[_ptr(x) for x in v_blocks])
+    kd = (usp_posdesc * n)(*kpos_blocks) if kpos_blocks is not None else None
+    lk = (C.c_int32 * n)(*lk_blocks) if lk_blocks is not None else None
+    oa = (C.c_void_p * n)(*[_ptr(x) for x in o_parts])
+    la = (C.c_void_p * n)(*[_ptr(x) for x in lse_parts])
+    _check(load().usp_ring_attn_fwd_partials(_ptr(q), ka, va, kd, lk, n, oa, la, bs, Lq, Lk, hq, hkv, hs, scale,
+                                             int(bool(causal)), C.byref(qpos) if qpos is not None else None,
+                                             _stream(stream)), "usp_ring_attn_fwd_partials")
 
 
 def usp_attn_fwd_workspace_bytes(p, n_ranks):

@@ -61,6 +61,13 @@ struct AttnArgs {
   int ticket_slot;   // counter the workgroups draw their work items from (MFMA kernel)
   int n_items;       // work items of the launch: query tiles x heads x batch
   int n_queues;      // gcd(8, batch x KV heads): item w waits in queue w mod n_queues
+  // Key split (launch_attn_fwd_partials): an item is (query tile, head, batch, ONE block), the blocks may differ in
+  // their number of keys, and the item's O (fp32, dense) and LSE go to the block's own partial result.  Otherwise
+  // (per_block = 0) an item walks all blocks, every block holds Lk keys and the result goes to o / lse.
+  int per_block;
+  int lk_blk[kMaxBlocks];
+  void* o_part[kMaxBlocks];
+  float* lse_part[kMaxBlocks];
 };
 
 // The scalar arguments as one work item of the MFMA kernel sees them (read anew for every item, see the kernel).
@@ -160,7 +167,14 @@ void block_attn_fwd_mfma(const AttnArgs) {
     const int l32 = lane & 31, hl = lane >> 5;
     const int group = w % n_groups; w /= n_groups;
     const int hg = w % a.g;
-    const int t = w / a.g;
+    int t = w / a.g;
+    int blk0 = 0, blk1 = a.n_blocks;         // the blocks this item walks
+    const bool per_block = ap->per_block != 0;
+    if (per_block) {
+      blk0 = t % a.n_blocks;
+      blk1 = blk0 + 1;
+      t /= a.n_blocks;
+    }
     const int qtile = a.causal ? a.n_qtiles - 1 - t : t;
     const int b = group / a.hkv, kvh = group % a.hkv;
     const int h = kvh * a.g + hg;
@@ -171,6 +185,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
 
     const __bf16* qg = (const __bf16*)a.q;
     const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes; + key * hkv * HS * 2
+    int Lk_b = a.Lk;   // keys of the current block (a.Lk stays the batch stride of every block's tensors)
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
     bf16x8 qf[NQB][KSTEPS];
@@ -224,7 +239,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
     auto fetch = [&](const char* base, int it, u32x4* reg) {
       const int key0 = tile_of(it) * KT;
       const char* tb = base + (size_t)key0 * row_bytes;
-      const int rows = min(a.Lk - key0, KT);
+      const int rows = min(Lk_b - key0, KT);
       const __amdgpu_buffer_rsrc_t tile = __builtin_amdgcn_make_buffer_rsrc(
           (void*)tb, 0, (rows - 1) * (int)row_bytes + HS * 2, kRawBufferFlags);
 #pragma unroll
@@ -272,8 +287,8 @@ void block_attn_fwd_mfma(const AttnArgs) {
       const int key0 = tile_of(it) * KT;
 
       // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave
-      const int key1 = min(a.Lk, key0 + KT);
-      bool need_mask = key0 + KT > a.Lk;
+      const int key1 = min(Lk_b, key0 + KT);
+      bool need_mask = key0 + KT > Lk_b;
       if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
       if (need_mask) {
         int qp[NQB];   // the lane's query position: derived here, where it is rarely needed, rather than kept in a register
@@ -284,7 +299,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int key = key0 + kbk * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
-            const bool inb = key < a.Lk;
+            const bool inb = key < Lk_b;
             const int kp = a.causal ? pos_of(kpos, key) : 0;
 #pragma unroll
             for (int qb = 0; qb < NQB; ++qb) {
@@ -389,9 +404,10 @@ void block_attn_fwd_mfma(const AttnArgs) {
 
     const std::integral_constant<bool, true> steady;
     const std::integral_constant<bool, false> draining;
-    for (int blk = 0; blk < a.n_blocks; ++blk) {
+    for (int blk = blk0; blk < blk1; ++blk) {
+      if (per_block) Lk_b = ap->lk_blk[blk];
       kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
-      tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
+      tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, Lk_b, tile_row0, tile_row1);
       na = tr.a1 - tr.a0;
       nt = na + (tr.b1 - tr.b0);
       if (nt == 0) continue;         // nothing of this block is visible to the query tile (workgroup-uniform)
@@ -447,7 +463,8 @@ void block_attn_fwd_mfma(const AttnArgs) {
       const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
       const int qrow = wave_row0 + qb * 32 + l32;
       if (qrow < a.Lq) {
-        OutT* dst = (OutT*)a.o + qo_offset(a, b, qrow, h, HS) + 4 * hl;
+        OutT* dst = per_block ? (OutT*)ap->o_part[blk0] + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl
+                              : (OutT*)a.o + qo_offset(a, b, qrow, h, HS) + 4 * hl;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -464,7 +481,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
           }
         if (hl == 0) {
           const float lse = l_tot > 0.f ? m_run[qb] * a.scale + __logf(l_tot) : -INFINITY;
-          a.lse[((size_t)b * a.hq + h) * a.Lq + qrow] = lse;
+          (per_block ? ap->lse_part[blk0] : a.lse)[((size_t)b * a.hq + h) * a.Lq + qrow] = lse;
         }
       }
     }
@@ -551,7 +568,7 @@ int launch_mfma(AttnArgs a, hipStream_t stream) {
   constexpr int KSTR = HS * 2 + 48, VSTR = HS * 2 + 64;
   constexpr size_t lds = 2 * (size_t)KT * (KSTR + VSTR);
   a.n_qtiles = (a.Lq + BM - 1) / BM;
-  const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs;
+  const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs * (a.per_block ? a.n_blocks : 1);
   if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
   auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT>;
   static bool attr_set = false;   // raise the dynamic LDS limit once per instance
@@ -599,6 +616,12 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
     a.kpos[j] = PosDesc32{(int)kp.start0, (int)kp.len0, (int)kp.start1, (int)kp.len1};
   }
   a.n_blocks = n_blocks;
+  a.per_block = 0;
+  for (int j = 0; j < kMaxBlocks; ++j) {
+    a.lk_blk[j] = (int)Lk;
+    a.o_part[j] = nullptr;
+    a.lse_part[j] = nullptr;
+  }
   a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
   a.Lq = (int)Lq; a.Lk = (int)Lk;
   a.n_qtiles = 0;
@@ -626,6 +649,43 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
                           const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream) {
   return launch_ring_attn_fwd(q, &k, &v, &kpos, 1, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal, qpos, in_dtype,
                               o_dtype, stream);
+}
+
+int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                             const usp_posdesc* kpos_blocks, const int* lk_blocks, int n_blocks, float* const* o_parts,
+                             float* const* lse_parts, int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
+                             float scale, int causal, const usp_posdesc& qpos, hipStream_t stream,
+                             const SeqLayoutIO* seq) {
+  if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
+  AttnArgs a;
+  a.seq_n = seq ? seq->rows_per_shard : 0;
+  a.seq_heads = seq ? seq->heads : 0;
+  a.seq_head0 = seq ? seq->head0 : 0;
+  a.q = q; a.o = nullptr; a.lse = nullptr;
+  for (int j = 0; j < kMaxBlocks; ++j) {
+    const int jj = j < n_blocks ? j : 0;
+    a.k[j] = k_blocks[jj];
+    a.v[j] = v_blocks[jj];
+    const usp_posdesc& kp = kpos_blocks[jj];
+    a.kpos[j] = PosDesc32{(int)kp.start0, (int)kp.len0, (int)kp.start1, (int)kp.len1};
+    a.lk_blk[j] = lk_blocks ? lk_blocks[jj] : (int)Lk;
+    if (a.lk_blk[j] < 1 || a.lk_blk[j] > Lk) return USP_ERR_SHAPE;
+    a.o_part[j] = o_parts[jj];
+    a.lse_part[j] = lse_parts[jj];
+  }
+  a.n_blocks = n_blocks;
+  a.per_block = 1;
+  a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
+  a.Lq = (int)Lq; a.Lk = (int)Lk;
+  a.n_qtiles = 0;
+  a.ticket_slot = 0;
+  a.n_items = 0;
+  a.n_queues = 1;
+  a.causal = causal;
+  a.scale = scale;
+  a.scale_log2 = scale * 1.4426950408889634f;
+  a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
+  return hs == 128 ? launch_mfma<128, 1, 8, 64, 2, float>(a, stream) : launch_mfma<64, 1, 8, 64, 2, float>(a, stream);
 }
 
 }  // namespace usp

@@ -2,6 +2,8 @@
 // orchestration of Algorithm 1 (all-to-all -> ring loop -> merge -> all-to-all) over kernels.
 // No arithmetic of the method runs on the host; every step is a kernel launch.
 #include <math.h>
+
+#include <algorithm>
 #include <string.h>
 
 #include "usp_internal.h"
@@ -157,6 +159,39 @@ extern "C" int usp_ring_attn_fwd(const void* q, const void* const* k_blocks, con
                               causal ? 1 : 0, qd, in_dtype, o_dtype, (hipStream_t)stream);
 }
 
+extern "C" int usp_ring_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                                          const usp_posdesc* kpos_blocks, const int32_t* lk_blocks, int n_blocks,
+                                          float* const* o_parts, float* const* lse_parts, int bs, int64_t Lq,
+                                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                                          const usp_posdesc* qpos, void* stream) {
+  if (!q || !k_blocks || !v_blocks || !o_parts || !lse_parts) return USP_ERR_NULL;
+  if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return USP_ERR_UNSUPPORTED;
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
+  if (hq % hkv) return USP_ERR_DEGREE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
+  if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  usp_posdesc qd = {0, Lq, 0, 0};
+  usp_posdesc kd[USP_MAX_RING_BLOCKS];
+  int lk[USP_MAX_RING_BLOCKS];
+  if (causal && (!qpos || !kpos_blocks)) return USP_ERR_NULL;
+  if (causal && !desc_ok(qpos, Lq)) return USP_ERR_SHAPE;
+  if (causal) qd = *qpos;
+  for (int j = 0; j < n_blocks; ++j) {
+    if (!k_blocks[j] || !v_blocks[j] || !o_parts[j] || !lse_parts[j]) return USP_ERR_NULL;
+    lk[j] = lk_blocks ? lk_blocks[j] : (int)Lk;
+    if (lk[j] < 1 || lk[j] > Lk) return USP_ERR_SHAPE;
+    kd[j] = usp_posdesc{0, lk[j], 0, 0};
+    if (causal) {
+      if (!desc_ok(&kpos_blocks[j], lk[j])) return USP_ERR_SHAPE;
+      kd[j] = kpos_blocks[j];
+    }
+  }
+  if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  return launch_attn_fwd_partials(q, k_blocks, v_blocks, kd, lk, n_blocks, o_parts, lse_parts, bs, Lq, Lk, hq, hkv, hs,
+                                  scale, causal ? 1 : 0, qd, (hipStream_t)stream);
+}
+
 extern "C" int usp_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                              float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
                              void* stream) {
@@ -205,6 +240,37 @@ void column_range(const usp_problem& p, int rb, int re, int* c0, int* c1) {
 // supports it: bf16 data and few enough blocks for the launch arguments.
 bool ring_in_one_launch(const usp_problem& p) { return p.dtype == USP_BF16 && p.ring <= USP_MAX_RING_BLOCKS; }
 
+// Key split of a rank's ring loop (launch_attn_fwd_partials): 0 = none (one work item per query tile, head and
+// batch walks all blocks), else the number of pieces each K/V block is cut into, every piece of every block then
+// being a work item of its own with a partial result of its own (1: the blocks themselves, for R > 1).  In the
+// unsplit launch the item of the last query tile walks every key, which takes ratio = 256 / (items x 1/2 under
+// a causal mask) times a CU's fair share of the whole launch.  Split from a ratio of 1.5: into two parts in all, three
+// from a ratio of 3.5 (the R blocks as they are when that is already as many or more); more parts cost more in
+// partial results (fp32, written and merged) than they gain (measured at L = 8192 and 16384: 2 and 3 pieces 1.4-1.8 x
+// faster than none, 4 and more slower again).  Pieces hold at least 1024 keys, and a launch takes no more parts in
+// all than it takes blocks.  Host arithmetic only, with the chip's 256 CUs as a constant: the workspace query must
+// not need a GPU.
+int key_splits(const usp_problem& p) {
+  if (!ring_in_one_launch(p)) return 0;
+  const int64_t Lq = p.L / p.ring;
+  const int64_t items = ((Lq + 255) / 256) * (p.hc / p.ulysses) * p.bs;
+  const double ratio = 256.0 / ((double)items * (p.causal ? 0.5 : 1.0));
+  if (ratio < 1.5) return 0;
+  const int64_t parts_wanted = ratio >= 3.5 ? 3 : 2;
+  int64_t s = (parts_wanted + p.ring - 1) / p.ring;
+  s = std::min<int64_t>(s, Lq / 1024);
+  s = std::min<int64_t>(s, USP_MAX_RING_BLOCKS / p.ring);
+  s = std::max<int64_t>(s, 1);
+  return s * p.ring > 1 ? (int)s : 0;
+}
+
+// Positions of the keys [a, b) of a block whose positions are d.
+usp_posdesc piece_of(const usp_posdesc& d, int64_t a, int64_t b) {
+  if (a >= d.len0) return usp_posdesc{d.start1 + (a - d.len0), b - a, 0, 0};
+  const int64_t n0 = std::min(b, d.len0) - a;
+  return usp_posdesc{d.start0 + a, n0, d.start1, (b - a) - n0};
+}
+
 FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   FwdPlan f;
   const size_t es = dtype_size(p.dtype);
@@ -219,9 +285,10 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   f.o_head = off; off += qb;
   f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.v_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
-  const bool parts = p.ring > 1 && !ring_in_one_launch(p);
-  f.o_parts = off; off += parts ? f.part_o_bytes * p.ring : 0;
-  f.lse_parts = off; off += parts ? f.part_lse_bytes * p.ring : 0;
+  const int splits = key_splits(p);
+  const size_t parts = splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
+  f.o_parts = off; off += f.part_o_bytes * parts;
+  f.lse_parts = off; off += f.part_lse_bytes * parts;
   f.total = off;
   return f;
 }
@@ -313,6 +380,39 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
       // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
       const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
       const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * es;
+      const int splits = key_splits(*p);
+      if (splits > 0) {
+        // Short sequence: every block in `splits` pieces, each (query tile, head, piece) its own work item of one
+        // launch; the pieces' partial results are merged, and O takes the separate pass back to the sequence layout.
+        const int64_t piece = ((Lq + splits - 1) / splits + 63) / 64 * 64;
+        const void* kp[USP_MAX_RING_BLOCKS];
+        const void* vp[USP_MAX_RING_BLOCKS];
+        usp_posdesc pd[USP_MAX_RING_BLOCKS];
+        int lk[USP_MAX_RING_BLOCKS];
+        float* o_ptrs[USP_MAX_RING_BLOCKS];
+        float* l_ptrs[USP_MAX_RING_BLOCKS];
+        int n = 0;
+        for (int i = 0; i < R; ++i)
+          for (int64_t a0 = 0; a0 < Lq; a0 += piece, ++n) {
+            const int64_t a1 = std::min(Lq, a0 + piece);
+            const size_t row_off = (size_t)a0 * hkv * p->hs * es;
+            kp[n] = (const char*)kb[i] + row_off;
+            vp[n] = (const char*)vb[i] + row_off;
+            pd[n] = piece_of(kds[i], a0, a1);
+            lk[n] = (int)(a1 - a0);
+            o_ptrs[n] = (float*)(ws + f.o_parts + (size_t)n * f.part_o_bytes);
+            l_ptrs[n] = (float*)(ws + f.lse_parts + (size_t)n * f.part_lse_bytes);
+          }
+        st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, n, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq,
+                                      hkv, p->hs, scale, p->causal ? 1 : 0, qd, stream, &seq);
+        if (st != USP_OK) return st;
+        st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, n, ws + f.o_head, lse_rank,
+                              p->bs, Lq, hq, p->hs, USP_FP32, p->dtype, stream);
+        if (st != USP_OK) return st;
+        st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.o_head, o, rank, rank + 1, rank, stream);
+        if (st != USP_OK) return st;
+        continue;
+      }
       st = launch_ring_attn_fwd((const char*)q + group_off, kb, vb, kds, R, (char*)o + group_off, lse_rank, p->bs, Lq,
                                 Lq, hq, hkv, p->hs, scale, p->causal ? 1 : 0, qd, p->dtype, p->dtype, stream, &seq);
       if (st != USP_OK) return st;

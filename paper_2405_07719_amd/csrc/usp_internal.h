@@ -57,6 +57,14 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
                          int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq = nullptr);
+// Key split: the same query rows against n_blocks blocks, every (query tile, head, batch, block) its own work item of
+// ONE launch, each block's result (fp32 O, LSE) in its own partial, to be merged by launch_lse_merge.  Block j holds
+// lk_blocks[j] <= Lk keys (all Lk when lk_blocks is null); Lk is the batch stride, in rows, of every block's tensors.
+int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                             const usp_posdesc* kpos_blocks, const int* lk_blocks, int n_blocks, float* const* o_parts,
+                             float* const* lse_parts, int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
+                             float scale, int causal, const usp_posdesc& qpos, hipStream_t stream,
+                             const SeqLayoutIO* seq = nullptr);
 int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int bs, int64_t Lq,
                           int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
                           const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream);

@@ -8,7 +8,7 @@ merge) is timed alone; a synchronous 8-GPU step would take the maximum over the 
 split.  No communication is modelled.  Inputs are seeded N(0,1) tensors made on the device (values do not change
 the timing); this is a measurement script, not a parity test.
 
-    python -m paper_2405_07719_amd.ring_balance_table [--seqlens 8192 32768 131072] [--iters 5]
+    python -m paper_2405_07719_amd.ring_balance_table [--seqlens 8192 16384 32768 131072] [--iters 5]
 """
 from __future__ import annotations
 
@@ -33,7 +33,7 @@ def time_rank(p, q, k, v, o, lse, ws, rank, iters):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--seqlens", type=int, nargs="+", default=[8192, 32768, 131072])
+    ap.add_argument("--seqlens", type=int, nargs="+", default=[8192, 16384, 32768, 131072])
     ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     usp.load()

@@ -86,4 +86,8 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     # more ring ranks than one launch takes blocks: partials again
     long_ring = usp.problem(1, 32768, 32, 8, 128, 1, 32, True)
     assert usp.usp_attn_fwd_workspace_bytes(long_ring, 1) == 2 * 8 * 2**20 + 2 * 2 * 32 * 2**20 + 32 * 16 * 2**20 + 32 * 2**17
+    # a short sequence (128 work items for 256 CUs): each block is cut into 3 pieces that run side by side,
+    # + 3 fp32 partial O (16 MiB each) and 3 partial LSE (128 KiB each)
+    short = usp.problem(1, 8192, 32, 8, 128, 8, 1, True)
+    assert usp.usp_attn_fwd_workspace_bytes(short, 1) == 2 * 8 * 2**20 + 2 * 2 * 2**20 + 3 * 16 * 2**20 + 3 * 2**17
     assert usp.usp_attn_fwd_workspace_bytes(p, 0) == 0

@@ -240,3 +240,50 @@ def test_ring_attn_fwd_in_a_hip_graph(usp):
         launch(o_e, l_e)            # eager work between the replays
         torch.cuda.synchronize()
         assert torch.equal(o_e.view(torch.int16), o_ref.view(torch.int16)), rep
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_ring_attn_fwd_partials_of_pieces_merge_to_the_whole(usp, causal):
+    """Key split: pieces of ONE K/V tensor (unequal, not tile-aligned, batch of two) as the blocks of
+    usp_ring_attn_fwd_partials; the merged partials against the oracle's plain attention and against the unsplit
+    launch.  A piece that a query row cannot see must come back as O = 0, LSE = -inf for that row."""
+    bs, Lq, Lk, hq, hkv, hs = 2, 700, 1000, 4, 2, 128
+    cuts = [0, 300, 364, 1000]
+    qpos = np.arange(250, 250 + Lq)          # rows 250..949: the first rows see nothing of the last piece
+    kpos = np.arange(Lk)
+    sq, gq = tl.gen(91, inputs.TENSOR_Q, bs, qpos, np.arange(hq), hs, tl.BF16)
+    sk, gk = tl.gen(91, inputs.TENSOR_K, bs, kpos, np.arange(hkv), hs, tl.BF16)
+    sv, gv = tl.gen(91, inputs.TENSOR_V, bs, kpos, np.arange(hkv), hs, tl.BF16)
+    ref_o, ref_l = orc.block_attention(gq, gk, gv, qpos, kpos, causal)
+    q, k, v = (tl.to_device(x, tl.BF16) for x in (sq, sk, sv))
+    qd = usp.usp_posdesc(250, Lq, 0, 0)
+    row = hkv * hs * 2
+    n = len(cuts) - 1
+    kb = [k.data_ptr() + a * row for a in cuts[:-1]]
+    vb = [v.data_ptr() + a * row for a in cuts[:-1]]
+    lk = [b - a for a, b in zip(cuts, cuts[1:])]
+    kd = [usp.usp_posdesc(a, b - a, 0, 0) for a, b in zip(cuts, cuts[1:])]
+    o_parts = [torch.full((bs, Lq, hq, hs), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n)]
+    l_parts = [torch.full((bs, hq, Lq), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n)]
+    usp.usp_ring_attn_fwd_partials(q, kb, vb, kd if causal else None, lk, o_parts, l_parts, bs, Lq, Lk, hq, hkv, hs,
+                                   0.0, causal, qd if causal else None)
+    o = torch.empty((bs, Lq, hq, hs), dtype=torch.float32, device="cuda")
+    lse = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
+    usp.usp_lse_merge(o_parts, l_parts, o, lse, bs, Lq, hq, hs, tl.FP32, tl.FP32)
+    o1 = torch.empty_like(o)
+    l1 = torch.empty_like(lse)
+    usp.usp_ring_attn_fwd(q, [k], [v], [usp.usp_posdesc(0, Lk, 0, 0)], o1, l1, bs, Lq, Lk, hq, hkv, hs, 0.0, causal,
+                          qd, tl.BF16, tl.FP32)
+    torch.cuda.synchronize()
+    for part_o, part_l in zip(o_parts, l_parts):
+        assert not torch.isnan(part_o).any() and not torch.isnan(part_l).any()
+    tl.assert_lse_close(tl.to_f64(lse), ref_l, 1e-3)
+    assert tl.max_abs(tl.to_f64(o), ref_o) <= 2e-2
+    assert tl.max_abs(tl.to_f64(o), tl.to_f64(o1)) <= 1e-2
+    if causal:   # rows at positions below 364 see nothing of the last piece
+        dead = int(364 - 250)
+        assert torch.isneginf(l_parts[2][:, :, :dead]).all() and (o_parts[2][:, :dead] == 0).all()
+        assert torch.isfinite(l_parts[2][:, :, dead:]).all()
+    with pytest.raises(usp.UspError):
+        usp.usp_ring_attn_fwd_partials(q, kb, vb, kd, [300, 64, 2000], o_parts, l_parts, bs, Lq, Lk, hq, hkv, hs, 0.0,
+                                       causal, qd)
