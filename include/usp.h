@@ -218,7 +218,10 @@ int usp_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* co
  * dq is complete for the ranks in range (each fills its head slice of its Ulysses group's shards).
  * dk/dv: for every ring row and every Ulysses column touched by the range, the column's head slice is
  * OVERWRITTEN with the sum of the contributions of the ranks in range; complete dk/dv therefore needs
- * rank_begin = 0, rank_end = N (or all R ring rows of one column for that column's head slice). */
+ * rank_begin = 0, rank_end = N (or all R ring rows of one column for that column's head slice).
+ * The fp32 accumulators may be held in several copies (one per slice of the work that a short or narrow problem is
+ * cut into, each written with plain stores and added up by the conversion pass; the workspace query knows): the
+ * results do not depend on the order in which workgroups finish. */
 size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks);
 int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,
                  const float* lse, const void* d_o, void* dq, void* dk, void* dv, int rank_begin,

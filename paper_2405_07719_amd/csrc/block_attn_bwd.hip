@@ -58,6 +58,13 @@ struct BwdArgs {
   PosDesc32 kpos[kMaxBlocks];
   // the workgroups of both kernels are persistent and draw their work items (attn_device.h); set per launch
   int ticket_slot, n_items, n_queues;
+  // Short sequences (few, long work items): the dQ kernel's items are cut into k_splits slices of their visible key
+  // tiles, the dK/dV kernel's into q_splits slices of their visible query tiles.  Slice s of the dQ kernel writes the
+  // s-th copy of dq, dq_part_stride elements further on; part (head split x q_splits + query slice) of the dK/dV
+  // kernel writes that copy of the block's dk and dv, dkdv_part_stride elements further on (no atomics then); the
+  // caller adds the copies up (launch_bwd_convert).  1 and 0 = not cut, one copy.
+  int k_splits, q_splits;
+  size_t dq_part_stride, dkdv_part_stride;
 };
 
 // The scalar arguments as one work item of the dQ kernel sees them (read anew for every item, see the kernel).
@@ -198,8 +205,10 @@ void bwd_dq_kernel(const BwdArgs) {
     const int l32 = lane & 31, hl = lane >> 5;
     const int n_groups = a.bs * a.hkv;
     const int group = w % n_groups; w /= n_groups;
-    const int hg = w % a.g;
-    const int t = w / a.g;
+    const int hg = w % a.g; w /= a.g;
+    const int k_splits = ap->k_splits;
+    const int ks = w % k_splits;             // this item's slice of the visible key tiles of every block
+    const int t = w / k_splits;
     const int qtile = a.causal ? a.n_tiles - 1 - t : t;
     const int b = group / a.hkv, kvh = group % a.hkv;
     const int h = kvh * a.g + hg;
@@ -276,14 +285,15 @@ void bwd_dq_kernel(const BwdArgs) {
     tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
     na = tr.a1 - tr.a0;
     nt = na + (tr.b1 - tr.b0);
-    if (nt == 0) continue;                   // workgroup-uniform
+    const int it0 = (int)((int64_t)nt * ks / k_splits), it1 = (int)((int64_t)nt * (ks + 1) / k_splits);
+    if (it1 == it0) continue;                // workgroup-uniform
     kg = (const char*)ap->k[blk] + kv_head_off;
     vg = (const char*)ap->v[blk] + kv_head_off;
-    fetch(0);
-    stash(0);                                // the previous block's last step ended on a barrier
+    fetch(it0);
+    stash(it0 & 1);                          // the previous block's last step ended on a barrier
     __syncthreads();
-    for (int it = 0; it < nt; ++it) {
-      const bool more = it + 1 < nt;
+    for (int it = it0; it < it1; ++it) {
+      const bool more = it + 1 < it1;
       if (more) fetch(it + 1);
       __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
       const char* k_s = lds + (it & 1) * STAGE;
@@ -337,7 +347,7 @@ void bwd_dq_kernel(const BwdArgs) {
     unsigned own_ticket = kNoDraw;
     if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
     if (qrow < a.Lq) {
-      float* dst = a.dq + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
+      float* dst = a.dq + (size_t)ks * ap->dq_part_stride + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -422,7 +432,10 @@ void bwd_dkdv_kernel(const BwdArgs) {
     const int n_groups = a.bs * a.hkv;
     const int group = w % n_groups; w /= n_groups;
     const int n_hsplit = a.g / a.heads_per_wg;   // workgroups that share a key tile's outputs (1: nobody else)
-    const int hg0 = (w % n_hsplit) * a.heads_per_wg; w /= n_hsplit;
+    const int hsplit = w % n_hsplit; w /= n_hsplit;
+    const int hg0 = hsplit * a.heads_per_wg;
+    const int q_splits = ap->q_splits;
+    const int qs = w % q_splits; w /= q_splits;   // this item's slice of the visible query tiles
     const int ktile = w % a.n_tiles;         // ascending local index: keys seen by the most queries first
     const int blk = w / a.n_tiles;           // K/V block of the ring loop
     const PosDesc32 kpos = {ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
@@ -528,13 +541,14 @@ void bwd_dkdv_kernel(const BwdArgs) {
     qg = (const char*)((const __bf16*)a.q + ((size_t)b * a.Lq * a.hq + h) * HS);
     og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
     stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
-    if (nt > 0) {
-      fetch(0);
-      stash(0);                              // the previous head's last step ended on a barrier
+    const int it0 = (int)((int64_t)nt * qs / q_splits), it1 = (int)((int64_t)nt * (qs + 1) / q_splits);
+    if (it1 > it0) {
+      fetch(it0);
+      stash(it0 & 1);   // the previous head's last step ended on a barrier
     }
     __syncthreads();
-    for (int it = 0; it < nt; ++it) {
-      const bool more = it + 1 < nt;
+    for (int it = it0; it < it1; ++it) {
+      const bool more = it + 1 < it1;
       if (more) fetch(it + 1);
       __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
       const char* base = lds + (it & 1) * STAGE;
@@ -606,10 +620,11 @@ void bwd_dkdv_kernel(const BwdArgs) {
     unsigned own_ticket = kNoDraw;
     if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
     if (key_ok) {
-      const size_t off = (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
+      const size_t part_stride = ap->dkdv_part_stride;   // > 0: every (head split, query slice) has its own copy
+      const size_t off = (size_t)(hsplit * q_splits + qs) * part_stride + (((size_t)b * a.Lk + key) * a.hkv + kvh) * HS + 4 * hl;
       float* dkp = ap->dk[blk] + off;
       float* dvp = ap->dv[blk] + off;
-      if (n_hsplit > 1) {
+      if (n_hsplit > 1 && part_stride == 0) {
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -655,10 +670,12 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* dst, size_t n4) {
 
 // fp32 accumulator -> bf16 / fp32 output, 4 elements per lane
 template <typename OutT>
-__global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT* dst, size_t n4) {
+__global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT* dst, size_t n4, int n_copies,
+                                                          size_t copy_stride4) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
-  const f32x4 v = __builtin_nontemporal_load((const f32x4*)src + i);
+  f32x4 v = __builtin_nontemporal_load((const f32x4*)src + i);
+  for (int c = 1; c < n_copies; ++c) v += __builtin_nontemporal_load((const f32x4*)src + c * copy_stride4 + i);
   if constexpr (sizeof(OutT) == 4) {
     __builtin_nontemporal_store(v, (f32x4*)dst + i);
   } else {
@@ -698,14 +715,52 @@ int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64
   return launch_status();
 }
 
+// How a launch pair divides its work.  dK/dV: one workgroup per (key tile, KV head, batch, block) that walks all g
+// query heads of the group writes its outputs once; when that grid would leave CUs idle, the heads are split over
+// workgroups, in the coarsest split that still gives every CU about four workgroups (a wide group, as in multi-query
+// attention, would otherwise pay g-fold for meeting again), else one head per workgroup.  With room for copies of
+// the outputs (`cut_items`) short sequences are divided further: fewer than two dQ items per CU, each as long as its
+// query tile has visible keys, are cut into up to four slices of their key tiles (at least 32 tiles of 32 keys
+// each) until there are four per CU; fewer than four dK/dV items per CU likewise into slices of their query tiles
+// (at least 16 tiles of 32 rows each).
+BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_blocks, bool cut_items) {
+  BwdCut c;
+  const int g = hq / hkv;
+  const int64_t unsplit = ((Lk + 255) / 256) * hkv * bs * n_blocks;
+  c.heads_per_wg = g;
+  if (unsplit < 2 * 256) {
+    c.heads_per_wg = 1;
+    for (int h = g - 1; h > 1; --h)
+      if (g % h == 0 && unsplit * (g / h) >= 4 * 256) { c.heads_per_wg = h; break; }
+  }
+  c.k_splits = c.q_splits = 1;
+  if (cut_items) {
+    const int64_t dq_items = ((Lq + 255) / 256) * hq * bs;
+    if (dq_items < 2 * 256) {
+      const int64_t key_tiles = (int64_t)n_blocks * ((Lk + 31) / 32);
+      c.k_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (4 * 256 + dq_items - 1) / dq_items, key_tiles / 32}));
+    }
+    const int64_t dkdv_items = unsplit * (g / c.heads_per_wg);
+    if (dkdv_items < 4 * 256)
+      c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (4 * 256 + dkdv_items - 1) / dkdv_items, ((Lq + 31) / 32) / 16}));
+  }
+  return c;
+}
+
 int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
                          const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,
                          int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
                          const usp_posdesc& qpos, int accumulate_dq, const int* accumulate_dkdv,
-                         hipStream_t stream) {
+                         hipStream_t stream, const BwdCopies* copies) {
   if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
+  // without room for copies: items are not cut, and heads that are split over workgroups meet through atomic adds
+  const BwdCut cut = copies ? copies->cut : plan_bwd_cut(bs, Lq, Lk, hq, hkv, n_blocks, false);
   BwdArgs a;
+  a.k_splits = cut.k_splits;
+  a.q_splits = cut.q_splits;
+  a.dq_part_stride = copies ? copies->dq_stride : 0;
+  a.dkdv_part_stride = copies ? copies->dkdv_stride : 0;
   a.q = q; a.d_o = d_o; a.lse = lse; a.delta = delta;
   a.dq = dq;
   for (int j = 0; j < kMaxBlocks; ++j) {
@@ -727,7 +782,7 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
   a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
   {
     a.n_tiles = (a.Lq + 255) / 256;
-    const int64_t grid = (int64_t)a.n_tiles * hq * bs;
+    const int64_t grid = (int64_t)a.n_tiles * hq * bs * a.k_splits;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
     // one workgroup per CU (256 VGPRs x 8 waves fill it), fewer when there are fewer items
     a.ticket_slot = next_ticket_slot();
@@ -743,20 +798,10 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
   }
   {
     a.n_tiles = (a.Lk + 255) / 256;
-    // One workgroup per (key tile, KV head) that walks all g query heads of the group writes its outputs with
-    // plain stores; when that grid would leave CUs idle, the heads are split over workgroups that meet through
-    // atomic adds, on accumulators that start from zero unless the caller accumulates.  The split is the coarsest
-    // one that still gives every CU about four workgroups (a wide group, as in multi-query attention, would
-    // otherwise pay for g-fold atomic traffic), else one head per workgroup.
     const int64_t unsplit = (int64_t)a.n_tiles * hkv * bs * n_blocks;
-    a.heads_per_wg = a.g;
-    if (unsplit < 2 * 256) {
-      a.heads_per_wg = 1;
-      for (int h = a.g - 1; h > 1; --h)
-        if (a.g % h == 0 && unsplit * (a.g / h) >= 4 * 256) { a.heads_per_wg = h; break; }
-    }
+    a.heads_per_wg = cut.heads_per_wg;
     for (int j = 0; j < kMaxBlocks; ++j) a.acc_dkdv[j] = accumulate_dkdv[j < n_blocks ? j : 0];
-    if (a.heads_per_wg != a.g) {
+    if (a.heads_per_wg != a.g && !copies) {   // atomic adds need accumulators that start from zero
       const size_t n4 = (size_t)bs * Lk * hkv * hs / 4;
       const size_t zg = (n4 + 255) / 256;
       if (zg > 0x7fffffffull) return USP_ERR_UNSUPPORTED;
@@ -766,7 +811,7 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
         hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)zg), dim3(256), 0, stream, (f32x4*)dv_blocks[j], n4);
       }
     }
-    const int64_t grid = unsplit * (a.g / a.heads_per_wg);
+    const int64_t grid = unsplit * (a.g / a.heads_per_wg) * a.q_splits;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
     // one workgroup per CU (256 VGPRs x 8 waves fill it), fewer when there are fewer items
     a.ticket_slot = next_ticket_slot();
@@ -789,14 +834,17 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
                               causal, qpos, accumulate_dq, &accumulate_dkdv, stream);
 }
 
-int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream) {
+int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream, int n_copies,
+                       size_t copy_stride) {
   const size_t n4 = n / 4;
   const size_t grid = (n4 + 255) / 256;
-  if (grid > 0x7fffffffull) return USP_ERR_UNSUPPORTED;
+  if (grid > 0x7fffffffull || n_copies < 1 || (copy_stride & 3)) return USP_ERR_UNSUPPORTED;
   if (out_dtype == USP_FP32)
-    hipLaunchKernelGGL((bwd_convert_kernel<float>), dim3((unsigned)grid), dim3(256), 0, stream, src, (float*)dst, n4);
+    hipLaunchKernelGGL((bwd_convert_kernel<float>), dim3((unsigned)grid), dim3(256), 0, stream, src, (float*)dst, n4,
+                       n_copies, copy_stride / 4);
   else
-    hipLaunchKernelGGL((bwd_convert_kernel<__bf16>), dim3((unsigned)grid), dim3(256), 0, stream, src, (__bf16*)dst, n4);
+    hipLaunchKernelGGL((bwd_convert_kernel<__bf16>), dim3((unsigned)grid), dim3(256), 0, stream, src, (__bf16*)dst, n4,
+                       n_copies, copy_stride / 4);
   return launch_status();
 }
 

@@ -490,7 +490,9 @@ namespace {
 
 struct BwdPlan {
   size_t q_head, o_head, do_head, delta, k_head, v_head, dq_acc, dk_acc, dv_acc, total;
-  size_t kv_block_bytes, kv_acc_bytes;
+  size_t kv_block_bytes, kv_acc_bytes;   // kv_acc_bytes: ALL copies of one block's dk (or dv) accumulator
+  BwdCopies copies;                      // how the launch pairs are cut, and the copies of dq / dk / dv they fill
+  int dkdv_copies;
 };
 
 BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
@@ -500,7 +502,12 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   const size_t q_elems = (size_t)p.bs * Lq * hq * p.hs, kv_elems = (size_t)p.bs * Lq * hkv * p.hs;
   const size_t qb = up256(q_elems * es);
   f.kv_block_bytes = kv_elems * es;   // exact: blocks are packed back to back
-  f.kv_acc_bytes = up256(kv_elems * sizeof(float));
+  // every launch pair of this problem is cut the same way (that of its largest launch: up to 16 blocks)
+  f.copies.cut = plan_bwd_cut(p.bs, (int64_t)Lq, (int64_t)Lq, (int)hq, (int)hkv, std::min(p.ring, USP_MAX_RING_BLOCKS), true);
+  f.copies.dq_stride = q_elems;
+  f.copies.dkdv_stride = kv_elems;
+  f.dkdv_copies = (int)(hq / hkv) / f.copies.cut.heads_per_wg * f.copies.cut.q_splits;
+  f.kv_acc_bytes = up256(kv_elems * sizeof(float) * f.dkdv_copies);
   const size_t blocks = (size_t)p.ring * n_cols;
   size_t off = 0;
   f.q_head = off; off += qb;
@@ -509,7 +516,7 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   f.delta = off; off += up256((size_t)p.bs * hq * Lq * sizeof(float));
   f.k_head = off; off += up256(f.kv_block_bytes * blocks);
   f.v_head = off; off += up256(f.kv_block_bytes * blocks);
-  f.dq_acc = off; off += up256(q_elems * sizeof(float));
+  f.dq_acc = off; off += up256(q_elems * sizeof(float) * f.copies.cut.k_splits);
   f.dk_acc = off; off += f.kv_acc_bytes * blocks;
   f.dv_acc = off; off += f.kv_acc_bytes * blocks;
   f.total = off;
@@ -593,11 +600,12 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
       }
       st = launch_ring_attn_bwd(ws + f.q_head, kb, vb, kds, nb, ws + f.do_head, lse_rank, delta,
                                 (float*)(ws + f.dq_acc), dkb, dvb, p->bs, Lq, Lq, hq, hkv, p->hs, scale,
-                                p->causal ? 1 : 0, qd, i0 > 0 ? 1 : 0, acc, stream);
+                                p->causal ? 1 : 0, qd, i0 > 0 ? 1 : 0, acc, stream, &f.copies);
       if (st != USP_OK) return st;
     }
     // dQ of this rank: convert into the (now free) q_head region and send it back to the sequence layout
-    st = launch_bwd_convert((const float*)(ws + f.dq_acc), ws + f.q_head, q_elems, p->dtype, stream);
+    st = launch_bwd_convert((const float*)(ws + f.dq_acc), ws + f.q_head, q_elems, p->dtype, stream,
+                            f.copies.cut.k_splits, f.copies.dq_stride);
     if (st != USP_OK) return st;
     st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.q_head, dq, rank, rank + 1, rank, stream);
     if (st != USP_OK) return st;
@@ -610,9 +618,11 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
       const size_t sl = slot(r, u);
       char* kdst = ws + f.k_head + sl * f.kv_block_bytes;
       char* vdst = ws + f.v_head + sl * f.kv_block_bytes;
-      st = launch_bwd_convert((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), kdst, kv_elems, p->dtype, stream);
+      st = launch_bwd_convert((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), kdst, kv_elems, p->dtype, stream,
+                              f.dkdv_copies, f.copies.dkdv_stride);
       if (st != USP_OK) return st;
-      st = launch_bwd_convert((const float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), vdst, kv_elems, p->dtype, stream);
+      st = launch_bwd_convert((const float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), vdst, kv_elems, p->dtype, stream,
+                              f.dkdv_copies, f.copies.dkdv_stride);
       if (st != USP_OK) return st;
       st = launch_layout_a2a(*p, p->hk, USP_HEAD_TO_SEQ, kdst, dk, rank, rank + 1, rank, stream);
       if (st != USP_OK) return st;

@@ -71,16 +71,27 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
 
 int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
                      hipStream_t stream);
+// How a backward launch pair divides its work (plan_bwd_cut): query heads of a KV group walked by one dK/dV
+// workgroup, slices of a dQ item's key tiles, slices of a dK/dV item's query tiles.
+struct BwdCut { int heads_per_wg, k_splits, q_splits; };
+BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_blocks, bool cut_items);
+// Room for copies of the outputs, one per slice: dq holds cut.k_splits copies dq_stride elements apart, every block's
+// dk and dv hold (hq / hkv / cut.heads_per_wg) * cut.q_splits copies dkdv_stride elements apart; every copy is
+// written (or added to, as the accumulate flags say) in full, nothing is atomic; launch_bwd_convert adds them up.
+struct BwdCopies { BwdCut cut; size_t dq_stride, dkdv_stride; };
 int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
                          const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,
                          int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
-                         const usp_posdesc& qpos, int accumulate_dq, const int* accumulate_dkdv, hipStream_t stream);
+                         const usp_posdesc& qpos, int accumulate_dq, const int* accumulate_dkdv, hipStream_t stream,
+                         const struct BwdCopies* copies = nullptr);
 int launch_block_attn_bwd(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                           const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
                           int hkv, int hs, float scale, int causal, const usp_posdesc& qpos, const usp_posdesc& kpos,
                           int accumulate_dq, int accumulate_dkdv, hipStream_t stream);
-int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream);
+// dst[i] = sum over n_copies of src[c * copy_stride + i], converted
+int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream, int n_copies = 1,
+                       size_t copy_stride = 0);
 
 // Calibration loops (mode 0 pure MFMA, 1 attention mix); sink holds kCalibSinkBytes.  *flop = MFMA flop of the launch.
 constexpr size_t kCalibSinkBytes = 256 * 512 * sizeof(float);
