@@ -719,10 +719,12 @@ int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64
 // query heads of the group writes its outputs once; when that grid would leave CUs idle, the heads are split over
 // workgroups, in the coarsest split that still gives every CU about four workgroups (a wide group, as in multi-query
 // attention, would otherwise pay g-fold for meeting again), else one head per workgroup.  With room for copies of
-// the outputs (`cut_items`) short sequences are divided further: fewer than two dQ items per CU, each as long as its
-// query tile has visible keys, are cut into up to four slices of their key tiles (at least 32 tiles of 32 keys
-// each) until there are four per CU; fewer than four dK/dV items per CU likewise into slices of their query tiles
-// (at least 16 tiles of 32 rows each).
+// the outputs (`cut_items`) the items are divided further where that pays (measured on one rank of L = 8192 ... 65536):
+// fewer than two dQ items per CU, each as long as its query tile has visible keys, are cut into slices of their key
+// tiles until there are two per CU (at most 4 slices, of at least 32 tiles of 32 keys); fewer than two dK/dV items
+// per CU likewise into slices of their query tiles (at least 16 tiles of 32 rows), and up to eight per CU into two
+// slices when an item walks several heads (long items, few copies); one head per item and two or more items per CU
+// are left alone (config 2: 8 copies of dK/dV instead of 4 cost 1 %).
 BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_blocks, bool cut_items) {
   BwdCut c;
   const int g = hq / hkv;
@@ -736,13 +738,14 @@ BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_block
   c.k_splits = c.q_splits = 1;
   if (cut_items) {
     const int64_t dq_items = ((Lq + 255) / 256) * hq * bs;
-    if (dq_items < 2 * 256) {
-      const int64_t key_tiles = (int64_t)n_blocks * ((Lk + 31) / 32);
-      c.k_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (4 * 256 + dq_items - 1) / dq_items, key_tiles / 32}));
-    }
+    const int64_t key_tiles = (int64_t)n_blocks * ((Lk + 31) / 32), query_tiles = (Lq + 31) / 32;
+    if (dq_items < 2 * 256)
+      c.k_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (2 * 256 + dq_items - 1) / dq_items, key_tiles / 32}));
     const int64_t dkdv_items = unsplit * (g / c.heads_per_wg);
-    if (dkdv_items < 4 * 256)
-      c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (4 * 256 + dkdv_items - 1) / dkdv_items, ((Lq + 31) / 32) / 16}));
+    if (dkdv_items < 2 * 256)
+      c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (2 * 256 + dkdv_items - 1) / dkdv_items, query_tiles / 16}));
+    else if (dkdv_items < 8 * 256 && c.heads_per_wg > 1)
+      c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>(2, query_tiles / 16));
   }
   return c;
 }
