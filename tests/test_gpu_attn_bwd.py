@@ -148,6 +148,13 @@ def test_usp_bwd_all_ranks(usp, U, R, zigzag):
     ("mqa_ring_only", 1, 512, 4, 1, 128, 1, 4, True),
     ("head_size_64_batch2", 2, 512, 8, 4, 64, 2, 2, True),
     ("noncausal", 1, 768, 8, 4, 128, 2, 2, False),
+    # more ring blocks than one launch pair takes: two pairs, the second adds to dQ
+    ("ring_of_20_two_launch_pairs", 1, 2560, 4, 2, 128, 1, 20, True),
+    # short sequences: dQ items in slices of their key tiles, dK/dV items in slices of their query tiles, every
+    # slice with its own copy of the output (4 + 4 slices, 4 head splits; then 2 ring blocks, batch of two)
+    ("sliced_items_one_block", 1, 4096, 8, 2, 128, 2, 1, True),
+    ("sliced_items_two_blocks_batch_of_two", 2, 4096, 4, 2, 128, 1, 2, True),
+    ("sliced_items_noncausal_hs64", 1, 3072, 4, 4, 64, 2, 1, False),
 ])
 def test_usp_bwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
     prob = tl.Problem(400 + len(name), bs, L, hc, hk, hs, U, R, causal, True, tl.BF16, with_do=True)
