@@ -91,3 +91,9 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     short = usp.problem(1, 8192, 32, 8, 128, 8, 1, True)
     assert usp.usp_attn_fwd_workspace_bytes(short, 1) == 2 * 8 * 2**20 + 2 * 2 * 2**20 + 3 * 16 * 2**20 + 3 * 2**17
     assert usp.usp_attn_fwd_workspace_bytes(p, 0) == 0
+    # backward: Q, O, dO in head layout (32 MiB each), delta (0.5), K and V (8 each), fp32 dQ (64) and one fp32 copy of
+    # dK and of dV (16 MiB each) per query head of the group: the four heads run as separate work items
+    assert usp.usp_attn_bwd_workspace_bytes(p, 1) == (3 * 32 + 2 * 8 + 64 + 2 * 4 * 16) * 2**20 + 2**19
+    # the short sequence: 4 slices of the dQ items (4 copies of 16 MiB), 4 head splits x 4 query slices of dK/dV
+    # (16 copies of 4 MiB each)
+    assert usp.usp_attn_bwd_workspace_bytes(short, 1) == (3 * 8 + 2 * 2 + 4 * 16 + 2 * 16 * 4) * 2**20 + 2**17
