@@ -1,6 +1,7 @@
 """GPU parity on randomly drawn shapes and position descriptors (seeded): ragged lengths, arbitrary two-run
 descriptors whose runs are not aligned to any tile size and may be out of order, GQA groups, both head sizes,
-one to five K/V blocks per launch.  Forward against the oracle's plain attention, backward against its gradient.
+one to five K/V blocks per launch; and whole problems of medium length (random U, R, heads, batch, chunk length)
+through usp_attn_fwd and usp_attn_bwd.  Forward against the oracle's plain attention, backward against its gradient.
 Tolerances as everywhere: O 2e-2, LSE 1e-3, gradients 5e-2 (max-abs)."""
 import numpy as np
 import pytest
@@ -146,3 +147,53 @@ def test_ring_fwd_bwd_extreme_logit_scales(usp, gain):
     for name, got, ref in (("dq", tl.to_f64(dq), ref_dq), ("dk", got_dk, ref_dk), ("dv", got_dv, ref_dv)):
         assert not np.isnan(got).any(), name
         assert tl.max_abs(got, ref) <= 5e-2 * max(1.0, float(np.max(np.abs(ref)))), name
+
+
+def _draw_problem(rng):
+    """A whole USP problem of medium length: long enough that usp_attn_fwd cuts the keys into parts and usp_attn_bwd
+    cuts its work items into slices (how, depends on every one of these numbers), small enough for the oracle."""
+    while True:
+        N = int(rng.choice([1, 2, 4, 8]))
+        U = int(rng.choice([u for u in (1, 2, 4, 8) if N % u == 0]))
+        R = N // U
+        hkv_local = int(rng.choice([1, 2]))
+        g = int(rng.choice([1, 2, 4]))
+        hk, hc = hkv_local * U, hkv_local * U * g
+        bs = int(rng.choice([1, 2]))
+        hs = int(rng.choice([64, 128]))
+        c = int(rng.integers(1, 40)) * 64 + int(rng.choice([0, 0, 8, 32]))     # chunk length, not always a tile multiple
+        L = 2 * N * c
+        if 2048 <= L <= 8192 and bs * hc * L * L <= 1.4e8:
+            return bs, L, hc, hk, hs, U, R, bool(rng.random() < 0.8), bool(rng.random() < 0.75)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_usp_fwd_bwd_random_problems(usp, seed):
+    rng = np.random.default_rng(7000 + seed)
+    bs, L, hc, hk, hs, U, R, causal, zigzag = _draw_problem(rng)
+    prob = tl.Problem(7000 + seed, bs, L, hc, hk, hs, U, R, causal, zigzag, tl.BF16, with_do=True)
+    p = usp.problem(bs, L, hc, hk, hs, U, R, causal, usp.USP_SPLIT_ZIGZAG if zigzag else usp.USP_SPLIT_CONTIG, usp.USP_BF16)
+    q, k, v, d_o = (prob.seq_layout_dev(n) for n in ("q", "k", "v", "do"))
+    o = torch.full(q.shape, float("nan"), dtype=q.dtype, device="cuda")
+    lse = torch.full((prob.N, bs, hc // U, L // R), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    usp.usp_attn_fwd(p, q, k, v, o, lse, 0, prob.N, ws)
+    ws2 = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    dq = torch.full(q.shape, float("nan"), dtype=q.dtype, device="cuda")
+    dk = torch.full(k.shape, float("nan"), dtype=k.dtype, device="cuda")
+    dv = torch.full(v.shape, float("nan"), dtype=v.dtype, device="cuda")
+    usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, 0, prob.N, ws2)
+    torch.cuda.synchronize()
+    what = (bs, L, hc, hk, hs, U, R, causal, zigzag)
+    ref_o, ref_l = orc.usp_attention_reference_by_rank(prob.val["q"], prob.val["k"], prob.val["v"], causal, R, U, zigzag)
+    og, lg = tl.to_f64(o), tl.to_f64(lse)
+    for rank in range(prob.N):
+        tl.assert_lse_close(lg[rank], ref_l[rank], 1e-3)
+        assert tl.max_abs(og[rank], ref_o[rank]) <= 2e-2, (what, rank)
+    refs = orc.attention_backward(prob.val["q"], prob.val["k"], prob.val["v"], prob.val["do"], causal)
+    for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+        gg = tl.to_f64(got)
+        assert not np.isnan(gg).any(), (what, name)
+        for rank in range(prob.N):
+            pos = orc.zigzag_positions(L, R, U, rank // U, rank % U, zigzag)
+            assert tl.max_abs(gg[rank], ref[:, pos]) <= 5e-2, (what, name, rank)
