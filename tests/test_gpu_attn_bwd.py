@@ -183,3 +183,42 @@ def test_usp_bwd_rejects_bad_arguments(usp):
     with pytest.raises(usp.UspError) as e:
         usp.usp_attn_bwd(p, x, x, x, x, x, x, x, x, x, 0, 1, x, 64)
     assert e.value.status == 5
+
+
+def test_usp_fwd_and_bwd_in_a_hip_graph(usp):
+    """Algorithm 1 forward and backward of all ranks captured into ONE HIP graph (some thirty kernels: permutations,
+    the persistent attention kernels with their item counters, merge, conversion) and replayed with eager calls and
+    synchronisations between the replays: every replay must reproduce the eager result bit for bit (the forward and
+    dQ are deterministic; dK/dV too, since slices and split heads write copies that are added in a fixed order)."""
+    prob = tl.Problem(93, 1, 4096, 8, 4, 128, 2, 2, True, True, tl.BF16, with_do=True)
+    p = usp.problem(prob.bs, prob.L, prob.hc, prob.hk, prob.hs, 2, 2, True, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
+    q, k, v, d_o = (prob.seq_layout_dev(n) for n in ("q", "k", "v", "do"))
+    ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+
+    def outputs():
+        return (torch.empty_like(q), torch.empty((prob.N, 1, 4, 2048), dtype=torch.float32, device="cuda"),
+                torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+
+    def run(o, lse, dq, dk, dv):
+        usp.usp_attn_fwd(p, q, k, v, o, lse, 0, prob.N, ws)
+        usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, 0, prob.N, ws2)
+    ref = outputs()
+    run(*ref)                      # eager first: one-time kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    got = outputs()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(*got)
+    eager = outputs()
+    for rep in range(3):
+        for t in got:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(got, ref):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a.view(torch.int16),
+                               b.view(torch.int32) if b.dtype == torch.float32 else b.view(torch.int16)), rep
+        run(*eager)                # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(eager[2].view(torch.int16), ref[2].view(torch.int16)), rep
