@@ -207,6 +207,20 @@ int usp_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* co
                       int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
                       const usp_posdesc* qpos, int accumulate_dq, const int* accumulate_dkdv, void* stream);
 
+/* usp_ring_attn_bwd with a workspace (same arguments, same results up to rounding): problems whose work items
+ * are few and long (short sequences) or whose query heads are split over workgroups are cut into slices that
+ * each write their own fp32 copy of dq / dk / dv into the workspace, and one more pass adds the copies up into
+ * the outputs (adding to what is there where the accumulate flags say so).  No atomic adds: the results do not
+ * depend on the order in which workgroups finish, and on such problems it is the faster of the two.  The
+ * workspace size is a function of the shape alone (0: no copies needed, the call is usp_ring_attn_bwd). */
+size_t usp_ring_attn_bwd_workspace_bytes(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, int n_blocks);
+int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                         const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
+                         const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,
+                         int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                         const usp_posdesc* qpos, int accumulate_dq, const int* accumulate_dkdv, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
 /* Algorithm 1 backward (Sec. 3: the all-to-alls swap their scatter/gather roles) for virtual ranks
  * [rank_begin, rank_end); bf16 problems only.
  *   q, k, v, o, d_o: seq layout (o as usp_attn_fwd wrote it); lse: [N][bs][hc/U][L/R] from usp_attn_fwd;

@@ -75,6 +75,10 @@ def load():
                                        I, V]
     lib.usp_ring_attn_bwd.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, V, V, P(V), P(V), I, L, L, I, I, I, F, I,
                                       P(usp_posdesc), I, P(I), V]
+    lib.usp_ring_attn_bwd_workspace_bytes.restype = C.c_size_t
+    lib.usp_ring_attn_bwd_workspace_bytes.argtypes = [I, L, L, I, I, I, I]
+    lib.usp_ring_attn_bwd_ws.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, V, V, P(V), P(V), I, L, L, I, I, I, F, I,
+                                         P(usp_posdesc), I, P(I), V, C.c_size_t, V]
     lib.usp_attn_bwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_bwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_bwd.argtypes = [P(usp_problem), V, V, V, V, V, V, V, V, V, I, I, V, C.c_size_t, V]
@@ -218,6 +222,26 @@ def usp_ring_attn_bwd(q, k_blocks, v_blocks, kpos_blocks, d_o, lse, delta, dq, d
                                     _ptr(dq), arr(dk_blocks), arr(dv_blocks), bs, Lq, Lk, hq, hkv, hs, scale,
                                     int(bool(causal)), C.byref(qpos) if qpos is not None else None,
                                     int(bool(accumulate_dq)), acc, _stream(stream)), "usp_ring_attn_bwd")
+
+
+def usp_ring_attn_bwd_workspace_bytes(bs, Lq, Lk, hq, hkv, hs, n_blocks):
+    return int(load().usp_ring_attn_bwd_workspace_bytes(bs, Lq, Lk, hq, hkv, hs, n_blocks))
+
+
+def usp_ring_attn_bwd_ws(q, k_blocks, v_blocks, kpos_blocks, d_o, lse, delta, dq, dk_blocks, dv_blocks, bs, Lq, Lk, hq,
+                         hkv, hs, scale, causal, qpos, accumulate_dq, accumulate_dkdv, workspace, workspace_bytes=None,
+                         stream=None):
+    n = len(k_blocks)
+    arr = lambda xs: (C.c_void_p * n)(*[_ptr(x) for x in xs])
+    kd = (usp_posdesc * n)(*kpos_blocks) if kpos_blocks is not None else None
+    acc = (C.c_int * n)(*[int(bool(x)) for x in accumulate_dkdv])
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().usp_ring_attn_bwd_ws(_ptr(q), arr(k_blocks), arr(v_blocks), kd, n, _ptr(d_o), _ptr(lse), _ptr(delta),
+                                       _ptr(dq), arr(dk_blocks), arr(dv_blocks), bs, Lq, Lk, hq, hkv, hs, scale,
+                                       int(bool(causal)), C.byref(qpos) if qpos is not None else None,
+                                       int(bool(accumulate_dq)), acc, _ptr(workspace), workspace_bytes,
+                                       _stream(stream)), "usp_ring_attn_bwd_ws")
 
 
 def usp_attn_bwd_workspace_bytes(p, n_ranks):

@@ -671,12 +671,13 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* dst, size_t n4) {
 // fp32 accumulator -> bf16 / fp32 output, 4 elements per lane
 template <typename OutT>
 __global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT* dst, size_t n4, int n_copies,
-                                                          size_t copy_stride4) {
+                                                          size_t copy_stride4, int add_to_dst) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
   f32x4 v = __builtin_nontemporal_load((const f32x4*)src + i);
   for (int c = 1; c < n_copies; ++c) v += __builtin_nontemporal_load((const f32x4*)src + c * copy_stride4 + i);
   if constexpr (sizeof(OutT) == 4) {
+    if (add_to_dst) v += *((const f32x4*)dst + i);
     __builtin_nontemporal_store(v, (f32x4*)dst + i);
   } else {
     u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
@@ -838,16 +839,17 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
 }
 
 int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream, int n_copies,
-                       size_t copy_stride) {
+                       size_t copy_stride, int add_to_dst) {
+  if (add_to_dst && out_dtype != USP_FP32) return USP_ERR_UNSUPPORTED;
   const size_t n4 = n / 4;
   const size_t grid = (n4 + 255) / 256;
   if (grid > 0x7fffffffull || n_copies < 1 || (copy_stride & 3)) return USP_ERR_UNSUPPORTED;
   if (out_dtype == USP_FP32)
     hipLaunchKernelGGL((bwd_convert_kernel<float>), dim3((unsigned)grid), dim3(256), 0, stream, src, (float*)dst, n4,
-                       n_copies, copy_stride / 4);
+                       n_copies, copy_stride / 4, add_to_dst);
   else
     hipLaunchKernelGGL((bwd_convert_kernel<__bf16>), dim3((unsigned)grid), dim3(256), 0, stream, src, (__bf16*)dst, n4,
-                       n_copies, copy_stride / 4);
+                       n_copies, copy_stride / 4, 0);
   return launch_status();
 }
 

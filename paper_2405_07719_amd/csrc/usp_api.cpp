@@ -667,6 +667,104 @@ extern "C" int usp_ring_attn_bwd(const void* q, const void* const* k_blocks, con
                               (hipStream_t)stream);
 }
 
+namespace {
+
+// Copies of the outputs that usp_ring_attn_bwd_ws keeps in its workspace: dq when its items are cut, every block's
+// dk and dv when they have more than one writer per element.
+struct RingBwdWs {
+  BwdCopies copies;
+  int dkdv_copies;
+  size_t dq_bytes, kv_bytes_per_block, total;   // dq_bytes / kv_bytes_per_block are 0 where the output is written directly
+};
+
+RingBwdWs plan_ring_bwd_ws(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, int n_blocks) {
+  RingBwdWs w;
+  w.copies.cut = plan_bwd_cut(bs, Lq, Lk, hq, hkv, n_blocks, true);
+  w.copies.dq_stride = (size_t)bs * Lq * hq * hs;
+  w.copies.dkdv_stride = (size_t)bs * Lk * hkv * hs;
+  w.dkdv_copies = (hq / hkv) / w.copies.cut.heads_per_wg * w.copies.cut.q_splits;
+  w.dq_bytes = w.copies.cut.k_splits > 1 ? up256(w.copies.dq_stride * sizeof(float) * w.copies.cut.k_splits) : 0;
+  w.kv_bytes_per_block = w.dkdv_copies > 1 ? up256(w.copies.dkdv_stride * sizeof(float) * w.dkdv_copies) : 0;
+  w.total = w.dq_bytes + 2 * w.kv_bytes_per_block * n_blocks;
+  return w;
+}
+
+}  // namespace
+
+extern "C" size_t usp_ring_attn_bwd_workspace_bytes(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
+                                                    int n_blocks) {
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1 || hq % hkv || (hs != 64 && hs != 128)) return 0;
+  if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return 0;
+  return plan_ring_bwd_ws(bs, Lq, Lk, hq, hkv, hs, n_blocks).total;
+}
+
+extern "C" int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                                    const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
+                                    const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks,
+                                    int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                                    const usp_posdesc* qpos, int accumulate_dq, const int* accumulate_dkdv,
+                                    void* workspace, size_t workspace_bytes, void* stream_) {
+  if (!q || !k_blocks || !v_blocks || !d_o || !lse || !delta || !dq || !dk_blocks || !dv_blocks || !accumulate_dkdv)
+    return USP_ERR_NULL;
+  if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return USP_ERR_UNSUPPORTED;
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
+  if (hq % hkv) return USP_ERR_DEGREE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
+  if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  const RingBwdWs w = plan_ring_bwd_ws(bs, Lq, Lk, hq, hkv, hs, n_blocks);
+  if (w.total > 0 && (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255))) return USP_ERR_WORKSPACE;
+  usp_posdesc qd = {0, Lq, 0, 0};
+  usp_posdesc kd[USP_MAX_RING_BLOCKS];
+  if (causal && (!qpos || !kpos_blocks)) return USP_ERR_NULL;
+  if (causal && !desc_ok(qpos, Lq)) return USP_ERR_SHAPE;
+  if (causal) qd = *qpos;
+  hipStream_t stream = (hipStream_t)stream_;
+  char* ws = (char*)workspace;
+  // where the kernels write: the copies in the workspace (always overwritten there), or the outputs themselves
+  float* dq_dst = w.dq_bytes ? (float*)ws : dq;
+  float* dk_dst[USP_MAX_RING_BLOCKS];
+  float* dv_dst[USP_MAX_RING_BLOCKS];
+  int acc[USP_MAX_RING_BLOCKS];
+  for (int j = 0; j < n_blocks; ++j) {
+    if (!k_blocks[j] || !v_blocks[j] || !dk_blocks[j] || !dv_blocks[j]) return USP_ERR_NULL;
+    kd[j] = usp_posdesc{0, Lk, 0, 0};
+    if (causal) {
+      if (!desc_ok(&kpos_blocks[j], Lk)) return USP_ERR_SHAPE;
+      kd[j] = kpos_blocks[j];
+    }
+    if (w.kv_bytes_per_block) {
+      dk_dst[j] = (float*)(ws + w.dq_bytes + (size_t)(2 * j) * w.kv_bytes_per_block);
+      dv_dst[j] = (float*)(ws + w.dq_bytes + (size_t)(2 * j + 1) * w.kv_bytes_per_block);
+      acc[j] = 0;
+    } else {
+      dk_dst[j] = dk_blocks[j];
+      dv_dst[j] = dv_blocks[j];
+      acc[j] = accumulate_dkdv[j] ? 1 : 0;
+    }
+  }
+  if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  int st = launch_ring_attn_bwd(q, k_blocks, v_blocks, kd, n_blocks, d_o, lse, delta, dq_dst, dk_dst, dv_dst, bs, Lq, Lk,
+                                hq, hkv, hs, scale, causal ? 1 : 0, qd, w.dq_bytes ? 0 : (accumulate_dq ? 1 : 0), acc,
+                                stream, &w.copies);
+  if (st != USP_OK) return st;
+  if (w.dq_bytes) {
+    st = launch_bwd_convert(dq_dst, dq, w.copies.dq_stride, USP_FP32, stream, w.copies.cut.k_splits, w.copies.dq_stride,
+                            accumulate_dq ? 1 : 0);
+    if (st != USP_OK) return st;
+  }
+  if (w.kv_bytes_per_block)
+    for (int j = 0; j < n_blocks; ++j) {
+      st = launch_bwd_convert(dk_dst[j], dk_blocks[j], w.copies.dkdv_stride, USP_FP32, stream, w.dkdv_copies,
+                              w.copies.dkdv_stride, accumulate_dkdv[j] ? 1 : 0);
+      if (st != USP_OK) return st;
+      st = launch_bwd_convert(dv_dst[j], dv_blocks[j], w.copies.dkdv_stride, USP_FP32, stream, w.dkdv_copies,
+                              w.copies.dkdv_stride, accumulate_dkdv[j] ? 1 : 0);
+      if (st != USP_OK) return st;
+    }
+  return USP_OK;
+}
+
 extern "C" int usp_calib_mfma(int mode, int iters, void* sink, size_t sink_bytes, double* flop, void* stream) {
   if (!sink || !flop) return USP_ERR_NULL;
   if (mode != 0 && mode != 1) return USP_ERR_UNSUPPORTED;

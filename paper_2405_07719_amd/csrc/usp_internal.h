@@ -89,9 +89,9 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
                           const float* delta, float* dq, float* dk, float* dv, int bs, int64_t Lq, int64_t Lk, int hq,
                           int hkv, int hs, float scale, int causal, const usp_posdesc& qpos, const usp_posdesc& kpos,
                           int accumulate_dq, int accumulate_dkdv, hipStream_t stream);
-// dst[i] = sum over n_copies of src[c * copy_stride + i], converted
+// dst[i] = sum over n_copies of src[c * copy_stride + i], converted (fp32 output: optionally added to dst[i])
 int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream, int n_copies = 1,
-                       size_t copy_stride = 0);
+                       size_t copy_stride = 0, int add_to_dst = 0);
 
 // Calibration loops (mode 0 pure MFMA, 1 attention mix); sink holds kCalibSinkBytes.  *flop = MFMA flop of the launch.
 constexpr size_t kCalibSinkBytes = 256 * 512 * sizeof(float);

@@ -287,3 +287,63 @@ def test_ring_attn_fwd_partials_of_pieces_merge_to_the_whole(usp, causal):
     with pytest.raises(usp.UspError):
         usp.usp_ring_attn_fwd_partials(q, kb, vb, kd, [300, 64, 2000], o_parts, l_parts, bs, Lq, Lk, hq, hkv, hs, 0.0,
                                        causal, qd)
+
+
+@pytest.mark.parametrize("bs,L,hq,hkv,hs,R", [
+    (1, 4096, 4, 1, 128, 2),      # 2 slices of the dQ items; 4 head splits x 4 query slices = 16 copies of dK/dV
+    (2, 2048, 4, 2, 64, 4),       # batch of two, head size 64, four blocks
+    (1, 16384, 16, 8, 128, 4),    # two heads per K/V head over a long block: copies of dK/dV only
+    (2, 16384, 8, 8, 128, 2),     # full grids, one head per K/V head: no copies at all, the workspace size is 0
+])
+def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R):
+    """usp_ring_attn_bwd_ws (slices of the work items write copies into a workspace, one pass adds them up) against
+    usp_ring_attn_bwd (one copy, split heads meet through atomic adds): same gradients up to fp32 rounding order;
+    the accumulate flags add to what is there; two runs of the workspace variant agree bit for bit."""
+    r = 1
+    order = [(r - i) % R for i in range(R)]
+    q, kb, vb, kd, qd, _, _ = _ring_case(usp, 95, bs, L, hq, hkv, hs, R, r, True, True, order)
+    Lq = L // R
+    d_o = torch.randn((bs, Lq, hq, hs), device="cuda").bfloat16()
+    o = torch.empty_like(q)
+    lse = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
+    usp.usp_ring_attn_fwd(q, kb, vb, kd, o, lse, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, tl.BF16, tl.BF16)
+    delta = torch.empty_like(lse)
+    usp.usp_attn_delta(o, d_o, delta, bs, Lq, hq, hs)
+    f32 = dict(dtype=torch.float32, device="cuda")
+
+    def fresh(fill):
+        return (torch.full((bs, Lq, hq, hs), fill, **f32), [torch.full((bs, Lq, hkv, hs), fill, **f32) for _ in order],
+                [torch.full((bs, Lq, hkv, hs), fill, **f32) for _ in order])
+    dq0, dk0, dv0 = fresh(float("nan"))
+    usp.usp_ring_attn_bwd(q, kb, vb, kd, d_o, lse, delta, dq0, dk0, dv0, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, False,
+                          [False] * R)
+    nbytes = usp.usp_ring_attn_bwd_workspace_bytes(bs, Lq, Lq, hq, hkv, hs, R)
+    assert (nbytes == 0) == (hq == hkv)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    runs = []
+    for _ in range(2):
+        dq1, dk1, dv1 = fresh(float("nan"))
+        usp.usp_ring_attn_bwd_ws(q, kb, vb, kd, d_o, lse, delta, dq1, dk1, dv1, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd,
+                                 False, [False] * R, ws, nbytes)
+        runs.append((dq1, dk1, dv1))
+    torch.cuda.synchronize()
+    dq1, dk1, dv1 = runs[0]
+    for a, b in zip([dq1] + dk1 + dv1, [dq0] + dk0 + dv0):
+        assert not torch.isnan(a).any()
+        assert torch.allclose(a, b, atol=3e-5, rtol=1e-5)
+    for a, b in zip([runs[0][0]] + runs[0][1] + runs[0][2], [runs[1][0]] + runs[1][1] + runs[1][2]):
+        assert torch.equal(a, b)
+    # accumulate: dq and the blocks flagged so are added to, the others overwritten
+    flags = [i % 2 == 1 for i in range(R)]
+    dq2, dk2, dv2 = fresh(1.0)
+    usp.usp_ring_attn_bwd_ws(q, kb, vb, kd, d_o, lse, delta, dq2, dk2, dv2, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd, True,
+                             flags, ws, nbytes)
+    torch.cuda.synchronize()
+    assert torch.allclose(dq2, dq1 + 1.0, atol=1e-6, rtol=1e-6)
+    for i in range(R):
+        want_k = dk1[i] + 1.0 if flags[i] else dk1[i]
+        assert torch.allclose(dk2[i], want_k, atol=1e-6, rtol=1e-6), i
+    if nbytes:
+        with pytest.raises(usp.UspError):
+            usp.usp_ring_attn_bwd_ws(q, kb, vb, kd, d_o, lse, delta, dq2, dk2, dv2, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd,
+                                     False, flags, ws, nbytes - 256)
