@@ -275,15 +275,28 @@ def main():
     if not args.no_backward:
         d_o = seq_buffer(inputs.TENSOR_DO, hc, q_heads)
         dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
-        ws_b = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, 1), dtype=torch.uint8, device="cuda")
+        n_plain, n_ds = usp.usp_attn_bwd_workspace_bytes(p, 1), usp.usp_attn_bwd_workspace_bytes_with_ds(p, 1)
+        # the larger workspace lets the dK/dV kernel keep dS for the dQ kernel (5 products per tile pair instead of
+        # 7): timed as well when it fits in a quarter of the free memory
+        with_ds = n_ds <= torch.cuda.mem_get_info()[0] // 4
+        ws_b = torch.empty(n_ds if with_ds else n_plain, dtype=torch.uint8, device="cuda")
 
-        def bwd():
-            usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, rank, rank + 1, ws_b)
+        def bwd(nbytes=n_plain):
+            usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, rank, rank + 1, ws_b, nbytes)
         bwd()
         bms = event_ms(bwd, max(3, args.steps // 4))
         out["backward"] = {"ms_per_step": round(bms, 4), "value": round(2.5 * flop / (bms * 1e-3) / 1e12, 2),
                            "unit": "TFLOP/s", "frac_of_mfma_peak": round(2.5 * flop / (bms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                           "workspace_bytes": n_plain,
                            "note": "whole usp_attn_bwd of the timed rank (all-to-alls, delta, dQ and dK/dV kernels, conversion)"}
+        if with_ds:
+            bwd(n_ds)
+            dms = event_ms(lambda: bwd(n_ds), max(3, args.steps // 4))
+            out["backward"]["with_stored_ds"] = {
+                "ms_per_step": round(dms, 4), "value": round(2.5 * flop / (dms * 1e-3) / 1e12, 2),
+                "frac_of_mfma_peak": round(2.5 * flop / (dms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                "workspace_bytes": n_ds,
+                "note": "same call with the larger workspace: dS written by the dK/dV kernel and read by the dQ kernel"}
         del d_o, dq, dk, dv, ws_b
 
     if args.copy_calibration:

@@ -235,8 +235,15 @@ int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void*
  * rank_begin = 0, rank_end = N (or all R ring rows of one column for that column's head slice).
  * The fp32 accumulators may be held in several copies (one per slice of the work that a short or narrow problem is
  * cut into, each written with plain stores and added up by the conversion pass; the workspace query knows): the
- * results do not depend on the order in which workgroups finish. */
+ * results do not depend on the order in which workgroups finish.
+ * Optional, for callers with memory to spare: a workspace of at least usp_attn_bwd_workspace_bytes_with_ds() bytes
+ * (the plain size plus 2 bytes per (query, key) pair, masked or not, of one rank's ring loop: bs * hc/U * R *
+ * (L/R)^2 * 2, keys and queries rounded up to 256) lets the dK/dV kernel keep the dS it forms, as bf16, and
+ * the dQ kernel read it back instead of forming S and dP a second time: 5 matrix products per tile pair instead
+ * of 7.  Same results up to the bf16 rounding of dS, which both kernels apply anyway.  Chosen by workspace_bytes
+ * alone; any size from usp_attn_bwd_workspace_bytes() up is accepted. */
 size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks);
+size_t usp_attn_bwd_workspace_bytes_with_ds(const usp_problem* p, int n_ranks);
 int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,
                  const float* lse, const void* d_o, void* dq, void* dk, void* dv, int rank_begin,
                  int rank_end, void* workspace, size_t workspace_bytes, void* stream);

@@ -81,6 +81,8 @@ def load():
                                          P(usp_posdesc), I, P(I), V, C.c_size_t, V]
     lib.usp_attn_bwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_bwd_workspace_bytes.argtypes = [P(usp_problem), I]
+    lib.usp_attn_bwd_workspace_bytes_with_ds.restype = C.c_size_t
+    lib.usp_attn_bwd_workspace_bytes_with_ds.argtypes = [P(usp_problem), I]
     lib.usp_attn_bwd.argtypes = [P(usp_problem), V, V, V, V, V, V, V, V, V, I, I, V, C.c_size_t, V]
     lib.usp_calib_mfma.argtypes = [I, I, V, C.c_size_t, P(C.c_double), V]
     for name in ("usp_ring_attn_bwd", "usp_ring_attn_fwd", "usp_calib_mfma", "usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
@@ -246,6 +248,10 @@ def usp_ring_attn_bwd_ws(q, k_blocks, v_blocks, kpos_blocks, d_o, lse, delta, dq
 
 def usp_attn_bwd_workspace_bytes(p, n_ranks):
     return int(load().usp_attn_bwd_workspace_bytes(C.byref(p), n_ranks))
+
+
+def usp_attn_bwd_workspace_bytes_with_ds(p, n_ranks):
+    return int(load().usp_attn_bwd_workspace_bytes_with_ds(C.byref(p), n_ranks))
 
 
 def usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, rank_begin, rank_end, workspace, workspace_bytes=None,

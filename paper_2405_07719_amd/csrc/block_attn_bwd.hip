@@ -65,6 +65,14 @@ struct BwdArgs {
   // caller adds the copies up (launch_bwd_convert).  1 and 0 = not cut, one copy.
   int k_splits, q_splits;
   size_t dq_part_stride, dkdv_part_stride;
+  // dS kept between the two kernels (null: each kernel forms its own).  The dK/dV kernel, which runs first then,
+  // writes every 32 x 32 block of dS it forms, unscaled, as bf16 [key][query] (2 KiB), block (head, K/V block, key
+  // tile kt, query tile qt) at index ((((b hq + h) n_blocks + blk) ds_qt8 + qt / 8) ds_kt + kt) 8 + qt % 8: what
+  // a workgroup of the dQ kernel (256 queries: qt / 8) reads, key tile after key tile, is one contiguous stream.
+  // The dQ kernel reads the blocks that hold a visible pair (all of those have been written) and is left with
+  // one product, dQ^T += K^T dS^T.
+  void* ds;
+  int ds_kt, ds_qt8;    // per K/V block: blocks along the keys (a multiple of 8: whole 256-key tiles), 256-query tiles
 };
 
 // The scalar arguments as one work item of the dQ kernel sees them (read anew for every item, see the kernel).
@@ -368,12 +376,195 @@ void bwd_dq_kernel(const BwdArgs) {
 }
 
 // -------------------------------------------------------------------------------------------------
+// dQ from a stored dS: what is left of the dQ kernel when the dK/dV kernel has written its dS blocks
+// (BwdArgs::ds).  One product, dQ^T += K^T dS^T, and the kernel is bound by reading dS: 2 bytes per visible
+// (query, key) pair.  Same work items, slices and epilogue as bwd_dq_kernel.  A step covers KT keys (64 or
+// 128): the K rows staged by the workgroup (double buffered), and per wave KT / 32 blocks of dS (2 KiB: its 32
+// queries x 32 keys each) that the wave copies as they are into its own part of LDS and reads back through
+// transpose reads, which yields the B operand (lane = query, k = keys in the order of the K^T fragments).  A
+// wave reads a step's blocks only when one of their (query, key) pairs is visible: the dK/dV kernel has written
+// them all then (they lie in one of its 256-key tiles, which has a visible pair with this query tile); the
+// others would be all zero, and may never have been written.
+// -------------------------------------------------------------------------------------------------
+template <int HS, int KT>
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
+void bwd_dq_ds_kernel(const BwdArgs) {
+  constexpr int NT = 512, BM = 256;
+  constexpr int NB = KT / 32;                       // dS blocks per wave and step
+  constexpr int DB = HS / 32;
+  constexpr int USTR = HS * 2 + 48;
+  constexpr int CPR = HS / 8;
+  constexpr int CPT = KT * CPR / NT;                // 16 B chunks of K per thread and step
+  constexpr int STAGE = KT * USTR;
+  static_assert(KT * CPR % NT == 0, "whole chunks per thread");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* const lds = smem;                           // [2][STAGE]  K
+  char* const ds_all = smem + 2 * STAGE;            // [8 waves][NB blocks][32 keys][32 queries] bf16
+
+  __shared__ int next_item[2];
+  __shared__ unsigned empty_queues;
+  int turn = 0;
+  if (threadIdx.x == 0) {
+    auto ap0 = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    next_item[0] = ItemQueues{ap0->ticket_slot, ap0->n_items, (int)gridDim.x, ap0->n_queues}.first_item(blockIdx.x);
+    empty_queues = 0;
+  }
+  for (;;) {
+    auto ap = (const __attribute__((address_space(4))) BwdArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+    const ItemQueues queues = {ap->ticket_slot, ap->n_items, (int)gridDim.x, ap->n_queues};
+    __syncthreads();   // the previous item is done with LDS, and next_item[turn] has been written
+    int w = __builtin_amdgcn_readfirstlane(next_item[turn]);
+    turn ^= 1;
+    if (w >= queues.n_items) {
+      if (threadIdx.x == 0) queues.leave();
+      break;
+    }
+    const int bs = ap->bs, hq = ap->hq, hkv = ap->hkv, g = ap->g, Lq = ap->Lq, Lk = ap->Lk;
+    const int causal = ap->causal, n_blocks = ap->n_blocks;
+    const PosDesc32 qpos = {ap->qpos.start0, ap->qpos.len0, ap->qpos.start1, ap->qpos.len1};
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, hl = lane >> 5;
+    const int n_groups = bs * hkv;
+    const int group = w % n_groups; w /= n_groups;
+    const int hg = w % g; w /= g;
+    const int k_splits = ap->k_splits;
+    const int ks = w % k_splits;
+    const int t = w / k_splits;
+    const int qtile = causal ? ap->n_tiles - 1 - t : t;
+    const int b = group / hkv, kvh = group % hkv;
+    const int h = kvh * g + hg;
+    const int tile_row0 = qtile * BM, tile_row1 = min(Lq, tile_row0 + BM);
+    const int wave_row0 = tile_row0 + wave * 32;
+    const int qrow = wave_row0 + l32;
+    const bool wave_live = wave_row0 < Lq;
+    const int wave_qmax = (causal && wave_live) ? pos_max(qpos, wave_row0, min(Lq, wave_row0 + 32)) : 0;
+
+    const size_t kv_head_off = ((size_t)b * Lk * hkv + kvh) * HS * 2;   // bytes
+    const uint32_t row_bytes = (uint32_t)hkv * HS * 2;
+    const char* kg = nullptr;      // per block
+    const char* dsg = nullptr;     // per block: this wave's column of dS blocks (query tile qtile * 8 + wave)
+    constexpr size_t ds_kt_stride = 8 * 2048;   // bytes from one key tile of 32 to the next: the workgroup's 8 blocks
+
+    f32x16 dq[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) zero16(dq[db]);
+
+    PosDesc32 kpos = {0, 0, 0, 0};
+    TileRanges tr = {0, 0, 0, 0};
+    int na = 0;
+    auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
+    // does this wave's query tile see a key of the step's KT?
+    auto sees = [&](int it) {
+      if (!wave_live) return false;
+      if (!causal) return true;
+      const int key0 = tile_of(it) * KT;
+      return pos_min(kpos, key0, min(Lk, key0 + KT)) <= wave_qmax;
+    };
+
+    const int st_row = tid / CPR, st_col = tid % CPR;      // first chunk; chunk c is (NT / CPR) rows further down
+    const uint32_t st_off = (uint32_t)st_row * row_bytes + st_col * 16;
+    u32x4 kreg[CPT], dreg[2 * NB];
+    auto fetch = [&](int it, bool seen) {
+      const int key0 = tile_of(it) * KT;
+      const uint32_t last = (uint32_t)min(Lk - 1 - key0, KT - 1) * row_bytes + st_col * 16;   // rows past the last key: clamped
+#pragma unroll
+      for (int c = 0; c < CPT; ++c)
+        kreg[c] = *(const u32x4*)(kg + (size_t)key0 * row_bytes + min(st_off + c * (NT / CPR) * row_bytes, last));
+      if (seen) {
+        const char* blk0 = dsg + (size_t)(NB * tile_of(it)) * ds_kt_stride + lane * 16;
+#pragma unroll
+        for (int j = 0; j < 2 * NB; ++j) dreg[j] = *(const u32x4*)(blk0 + (j >> 1) * ds_kt_stride + (j & 1) * 1024);
+      }
+    };
+    char* const ds_s = ds_all + wave * (NB * 2048);
+    auto stash = [&](int buf, bool seen) {
+      char* base = lds + buf * STAGE;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) *(u32x4*)(base + (st_row + c * (NT / CPR)) * USTR + st_col * 16) = kreg[c];
+      if (seen) {
+#pragma unroll
+        for (int j = 0; j < 2 * NB; ++j) *(u32x4*)(ds_s + j * 1024 + lane * 16) = dreg[j];
+      }
+    };
+    const int tr_off = tr_lane_offset<USTR>(lane);
+    const int tr_off_ds = tr_lane_offset<64>(lane);
+
+    for (int blk = 0; blk < n_blocks; ++blk) {
+    kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
+    tr = visible_key_tiles<KT>(causal, qpos, kpos, Lk, tile_row0, tile_row1);
+    na = tr.a1 - tr.a0;
+    const int nt = na + (tr.b1 - tr.b0);
+    const int it0 = (int)((int64_t)nt * ks / k_splits), it1 = (int)((int64_t)nt * (ks + 1) / k_splits);
+    if (it1 == it0) continue;                // workgroup-uniform
+    kg = (const char*)ap->k[blk] + kv_head_off;
+    dsg = (const char*)ap->ds + (((((size_t)b * hq + h) * n_blocks + blk) * ap->ds_qt8 + qtile) * ap->ds_kt * 8 + wave) * 2048;
+    bool seen = sees(it0);
+    fetch(it0, seen);
+    stash(it0 & 1, seen);                    // the previous block's last step ended on a barrier
+    __syncthreads();
+    for (int it = it0; it < it1; ++it) {
+      const bool more = it + 1 < it1;
+      const bool seen_next = more && sees(it + 1);
+      bf16x8 dsf[2 * NB];
+      if (seen) {
+#pragma unroll
+        for (int st = 0; st < 2 * NB; ++st) dsf[st] = tr_read<64>(ds_s + (st >> 1) * 2048 + (16 * (st & 1)) * 64 + tr_off_ds);
+      }
+      if (more) fetch(it + 1, seen_next);
+      __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute
+      const char* k_s = lds + (it & 1) * STAGE;
+      if (seen) {
+        // dQ^T += K^T dS^T   (rows = head dims, cols = queries, k = keys)
+#pragma unroll
+        for (int st = 0; st < 2 * NB; ++st)
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            const bf16x8 kt = tr_read<USTR>(k_s + tr_off + (16 * st) * USTR + db * 64);
+            dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf[st], dq[db], 0, 0, 0);
+          }
+      }
+      if (more) stash((it + 1) & 1, seen_next);
+      seen = seen_next;
+      __syncthreads();
+    }
+    }   // blocks
+
+    unsigned own_ticket = kNoDraw;
+    if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
+    if (qrow < Lq) {
+      const float scale = ap->scale;
+      const int accumulate = ap->accumulate;
+      float* dst = ap->dq + (size_t)ks * ap->dq_part_stride + (((size_t)b * Lq + qrow) * hq + h) * HS + 4 * hl;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          f32x4 v4 = {dq[db][4 * j] * scale, dq[db][4 * j + 1] * scale, dq[db][4 * j + 2] * scale,
+                      dq[db][4 * j + 3] * scale};
+          f32x4* d = (f32x4*)(dst + db * 32 + j * 8);
+          if (accumulate) v4 += *d;
+          *d = v4;
+        }
+    }
+    if (threadIdx.x == 0) {
+      unsigned empty = empty_queues;
+      next_item[turn] = queues.finish(own_ticket, empty);
+      empty_queues = empty;
+    }
+  }   // next work item
+}
+
+// -------------------------------------------------------------------------------------------------
 // dK, dV.  A workgroup owns 256 keys of one KV head (eight waves of 32 keys) and ONE query head of its
 // group, and walks the visible query tiles of 32 rows, double buffered in LDS.  The query heads of a
 // group (and nothing else) meet in the fp32 outputs through atomic adds: at most hq/hkv addends per
 // element, the only non-deterministic rounding of the backward.
 // -------------------------------------------------------------------------------------------------
-template <int HS>
+template <int HS, bool WRITE_DS>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void bwd_dkdv_kernel(const BwdArgs) {
   constexpr int NT = 512, BN = 256, QT = 32;
@@ -542,6 +733,11 @@ void bwd_dkdv_kernel(const BwdArgs) {
     og = (const char*)((const __bf16*)a.d_o + ((size_t)b * a.Lq * a.hq + h) * HS);
     stat_g = (tid < QT ? a.lse : a.delta) + ((size_t)b * a.hq + h) * a.Lq;
     const int it0 = (int)((int64_t)nt * qs / q_splits), it1 = (int)((int64_t)nt * (qs + 1) / q_splits);
+    // where the dS blocks of this head and K/V block begin
+    char* ds_head = nullptr;
+    const int ds_lane_off = l32 * 64 + hl * 16;
+    if constexpr (WRITE_DS)
+      ds_head = (char*)ap->ds + ((((size_t)b * a.hq + h) * ap->n_blocks + blk) * ap->ds_qt8 * ap->ds_kt * 8) * 2048;
     if (it1 > it0) {
       fetch(it0);
       stash(it0 & 1);   // the previous head's last step ended on a barrier
@@ -594,6 +790,12 @@ void bwd_dkdv_kernel(const BwdArgs) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) dp[i] *= s[i];
 
+      __amdgpu_buffer_rsrc_t ds_blk;   // this wave's block of dS for this query tile
+      if constexpr (WRITE_DS) {
+        const int qt = q0 / QT;
+        const size_t idx = ((size_t)(qt >> 3) * ap->ds_kt + (ktile * 8 + wave)) * 8 + (qt & 7);
+        ds_blk = __builtin_amdgcn_make_buffer_rsrc(ds_head + idx * 2048, 0, 2048, kRawBufferFlags);
+      }
       // dV^T += dO^T P and dK^T += Q^T dS   (rows = head dims, cols = keys, k = queries)
 #pragma unroll
       for (int st = 0; st < 2; ++st) {
@@ -604,6 +806,19 @@ void bwd_dkdv_kernel(const BwdArgs) {
           dw[pr] = pack_bf16(dp[8 * st + 2 * pr], dp[8 * st + 2 * pr + 1]);
         }
         const bf16x8 pf = __builtin_bit_cast(bf16x8, pw), dsf = __builtin_bit_cast(bf16x8, dw);
+        if constexpr (WRITE_DS) {
+          // dw holds query rows 16 st + 4 hl .. + 3 and 8 more on .. + 3 of key column l32.  The two lanes of a key
+          // trade halves (v_permlane32_swap(a, b): lower lanes get {a, a of lane + 32}, upper lanes {b of lane - 32,
+          // b}), so that the lower one holds rows 16 st .. + 7 and the upper one rows 16 st + 8 .. + 15: 16 bytes each
+          const u32x2 e = __builtin_amdgcn_permlane32_swap(dw[0], dw[2], false, false);
+          const u32x2 o = __builtin_amdgcn_permlane32_swap(dw[1], dw[3], false, false);
+          // The block's address is in the descriptor and the scalar offset stays an immediate zero: a buffer
+          // store of more than 8 bytes reads its data registers after it has issued, and the compiler keeps the
+          // next instructions from overwriting them only in this form.  (With the block's offset in a scalar
+          // register, the data registers were reused at once and some blocks came out holding the next step's
+          // values, now and then: measured, the results differed from run to run.)
+          __builtin_amdgcn_raw_buffer_store_b128(u32x4{e[0], o[0], e[1], o[1]}, ds_blk, ds_lane_off + 32 * st, 0, 0);
+        }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
           const bf16x8 ot = tr_read<USTR>(o_s + tr_off + (16 * st) * USTR + db * 64);
@@ -685,17 +900,32 @@ __global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT
   }
 }
 
-template <int HS>
+template <int HS, bool WRITE_DS>
 int launch_dkdv(const BwdArgs& a, int64_t grid, hipStream_t stream) {
   constexpr int USTR = HS * 2 + 48;
   constexpr size_t lds = 256 * USTR + 2 * (2 * 32 * USTR);
   static bool attr_set = false;   // raise the dynamic LDS limit once per instance
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)bwd_dkdv_kernel<HS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    if (hipFuncSetAttribute((const void*)bwd_dkdv_kernel<HS, WRITE_DS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return USP_ERR_LAUNCH;
     attr_set = true;
   }
-  hipLaunchKernelGGL((bwd_dkdv_kernel<HS>), dim3((unsigned)grid), dim3(512), lds, stream, a);
+  hipLaunchKernelGGL((bwd_dkdv_kernel<HS, WRITE_DS>), dim3((unsigned)grid), dim3(512), lds, stream, a);
+  return launch_status();
+}
+
+template <int HS>
+int launch_dq_ds(const BwdArgs& a, int64_t grid, hipStream_t stream) {
+  constexpr int KT = 128;
+  constexpr int USTR = HS * 2 + 48;
+  constexpr size_t lds = 2 * KT * USTR + 8 * (KT / 32) * 2048;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)bwd_dq_ds_kernel<HS, KT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return USP_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((bwd_dq_ds_kernel<HS, KT>), dim3((unsigned)grid), dim3(512), lds, stream, a);
   return launch_status();
 }
 
@@ -784,7 +1014,12 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
   a.scale = scale;
   a.scale_log2 = scale * kLog2e;
   a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
-  {
+  a.ds = copies ? copies->ds : nullptr;
+  a.ds_kt = (int)((Lk + 255) / 256) * 8;
+  a.ds_qt8 = (int)((Lq + 255) / 256);
+  // with dS kept, the dK/dV kernel (which writes it) runs first; otherwise the two are independent
+  for (int pass = 0; pass < 2; ++pass)
+  if ((pass == 0) == (a.ds == nullptr)) {
     a.n_tiles = (a.Lq + 255) / 256;
     const int64_t grid = (int64_t)a.n_tiles * hq * bs * a.k_splits;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
@@ -793,14 +1028,18 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     a.n_items = (int)grid;
     a.n_queues = std::gcd(dev::kMaxItemQueues, bs * hkv);
     const unsigned n_wgs = (unsigned)std::min<int64_t>(grid, compute_units());
-    if (hs == 128)
-      hipLaunchKernelGGL((bwd_dq_kernel<128>), dim3(n_wgs), dim3(512), 0, stream, a);
-    else
-      hipLaunchKernelGGL((bwd_dq_kernel<64>), dim3(n_wgs), dim3(512), 0, stream, a);
-    const int st = launch_status();
+    int st;
+    if (a.ds) {
+      st = hs == 128 ? launch_dq_ds<128>(a, n_wgs, stream) : launch_dq_ds<64>(a, n_wgs, stream);
+    } else {
+      if (hs == 128)
+        hipLaunchKernelGGL((bwd_dq_kernel<128>), dim3(n_wgs), dim3(512), 0, stream, a);
+      else
+        hipLaunchKernelGGL((bwd_dq_kernel<64>), dim3(n_wgs), dim3(512), 0, stream, a);
+      st = launch_status();
+    }
     if (st != USP_OK) return st;
-  }
-  {
+  } else {
     a.n_tiles = (a.Lk + 255) / 256;
     const int64_t unsplit = (int64_t)a.n_tiles * hkv * bs * n_blocks;
     a.heads_per_wg = cut.heads_per_wg;
@@ -824,7 +1063,8 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     // (KV group, head split) value, the two fastest indices of the item number
     a.n_queues = std::gcd(dev::kMaxItemQueues, bs * hkv * (a.g / a.heads_per_wg));
     const int64_t n_wgs = std::min<int64_t>(grid, compute_units());
-    const int dk_st = hs == 128 ? launch_dkdv<128>(a, n_wgs, stream) : launch_dkdv<64>(a, n_wgs, stream);
+    const int dk_st = a.ds ? (hs == 128 ? launch_dkdv<128, true>(a, n_wgs, stream) : launch_dkdv<64, true>(a, n_wgs, stream))
+                           : (hs == 128 ? launch_dkdv<128, false>(a, n_wgs, stream) : launch_dkdv<64, false>(a, n_wgs, stream));
     if (dk_st != USP_OK) return dk_st;
   }
   return launch_status();

@@ -493,6 +493,8 @@ struct BwdPlan {
   size_t kv_block_bytes, kv_acc_bytes;   // kv_acc_bytes: ALL copies of one block's dk (or dv) accumulator
   BwdCopies copies;                      // how the launch pairs are cut, and the copies of dq / dk / dv they fill
   int dkdv_copies;
+  size_t ds, ds_bytes;                   // room for the dS of one launch pair (used when the workspace reaches that far)
+  size_t total_with_ds;
 };
 
 BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
@@ -520,6 +522,9 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   f.dk_acc = off; off += f.kv_acc_bytes * blocks;
   f.dv_acc = off; off += f.kv_acc_bytes * blocks;
   f.total = off;
+  f.ds = off;
+  f.ds_bytes = up256(bwd_ds_bytes(p.bs, (int64_t)Lq, (int64_t)Lq, (int)hq, std::min(p.ring, USP_MAX_RING_BLOCKS)));
+  f.total_with_ds = off + f.ds_bytes;
   return f;
 }
 
@@ -529,6 +534,12 @@ extern "C" size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks
   if (usp_validate(p) != USP_OK || n_ranks < 1 || p->dtype != USP_BF16) return 0;
   const int cols = n_ranks == 1 ? 1 : p->ulysses;
   return plan_bwd(*p, cols).total;
+}
+
+extern "C" size_t usp_attn_bwd_workspace_bytes_with_ds(const usp_problem* p, int n_ranks) {
+  if (usp_validate(p) != USP_OK || n_ranks < 1 || p->dtype != USP_BF16) return 0;
+  const int cols = n_ranks == 1 ? 1 : p->ulysses;
+  return plan_bwd(*p, cols).total_with_ds;
 }
 
 extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,
@@ -543,11 +554,12 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
   int c0, c1;
   column_range(*p, rank_begin, rank_end, &c0, &c1);
   const int n_cols = c1 - c0;
-  const BwdPlan f = plan_bwd(*p, n_cols);
+  BwdPlan f = plan_bwd(*p, n_cols);
   if (!workspace || workspace_bytes < f.total) return USP_ERR_WORKSPACE;
   if ((uintptr_t)workspace & 255) return USP_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   char* ws = (char*)workspace;
+  if (workspace_bytes >= f.total_with_ds) f.copies.ds = ws + f.ds;   // room to keep dS between the two kernels
   const int64_t Lq = p->L / R;
   const int hq = p->hc / U, hkv = p->hk / U;
   const float scale = p->scale == 0.0f ? 1.0f / sqrtf((float)p->hs) : p->scale;

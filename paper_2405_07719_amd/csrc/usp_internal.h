@@ -78,7 +78,13 @@ BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_block
 // Room for copies of the outputs, one per slice: dq holds cut.k_splits copies dq_stride elements apart, every block's
 // dk and dv hold (hq / hkv / cut.heads_per_wg) * cut.q_splits copies dkdv_stride elements apart; every copy is
 // written (or added to, as the accumulate flags say) in full, nothing is atomic; launch_bwd_convert adds them up.
-struct BwdCopies { BwdCut cut; size_t dq_stride, dkdv_stride; };
+// ds (optional, null = off): room for the dS of one launch pair, bwd_ds_bytes() bytes: the dK/dV kernel then runs
+// first and writes the dS blocks it forms, and the dQ kernel reads them back instead of forming S and dP again
+// (5 matrix products per tile pair instead of 7, for 2 bytes written and read per visible pair).
+struct BwdCopies { BwdCut cut; size_t dq_stride, dkdv_stride; void* ds = nullptr; };
+inline size_t bwd_ds_bytes(int bs, int64_t Lq, int64_t Lk, int hq, int n_blocks) {
+  return (size_t)bs * hq * n_blocks * (size_t)((Lk + 255) / 256 * 8) * (size_t)((Lq + 255) / 256 * 8) * 2048;
+}
 int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
                          const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,

@@ -117,8 +117,18 @@ def test_block_attn_bwd_accumulate_adds(usp):
         usp.usp_block_attn_bwd(q, k, v, d_o, lse, delta, dq, dk, dv, bs, L, L, 3, 2, hs, 0.0, True, d, d, False)
 
 
+def _bwd_workspace(usp, p, n_ranks, keep_ds):
+    """The backward workspace, every byte 0xFF (bf16 and fp32 NaNs: a read of something never written shows); with
+    keep_ds of the size at which the dK/dV kernel stores dS for the dQ kernel."""
+    nb = usp.usp_attn_bwd_workspace_bytes(p, n_ranks)
+    nb_ds = usp.usp_attn_bwd_workspace_bytes_with_ds(p, n_ranks)
+    assert 0 < nb < nb_ds
+    return torch.full((nb_ds if keep_ds else nb,), 0xFF, dtype=torch.uint8, device="cuda")
+
+
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
 @pytest.mark.parametrize("U,R,zigzag", [(2, 2, True), (1, 4, True), (4, 1, True), (2, 2, False)])
-def test_usp_bwd_all_ranks(usp, U, R, zigzag):
+def test_usp_bwd_all_ranks(usp, U, R, zigzag, keep_ds):
     """dQ, dK, dV of every virtual rank against the textbook gradient of the unsplit Eq. 1."""
     prob = tl.Problem(91, 1, 1024, 8, 4, 128, U, R, True, zigzag, tl.BF16, with_do=True)
     p = usp.problem(prob.bs, prob.L, prob.hc, prob.hk, prob.hs, U, R, True,
@@ -128,9 +138,7 @@ def test_usp_bwd_all_ranks(usp, U, R, zigzag):
     lse = torch.empty((prob.N, prob.bs, prob.hc // U, prob.L // R), dtype=torch.float32, device="cuda")
     ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
     usp.usp_attn_fwd(p, q, k, v, o, lse, 0, prob.N, ws)
-    nb = usp.usp_attn_bwd_workspace_bytes(p, prob.N)
-    assert nb > 0
-    ws2 = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    ws2 = _bwd_workspace(usp, p, prob.N, keep_ds)
     dq = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
     dk = torch.full(k.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
     dv = torch.full(v.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
@@ -155,8 +163,14 @@ def test_usp_bwd_all_ranks(usp, U, R, zigzag):
     ("sliced_items_one_block", 1, 4096, 8, 2, 128, 2, 1, True),
     ("sliced_items_two_blocks_batch_of_two", 2, 4096, 4, 2, 128, 1, 2, True),
     ("sliced_items_noncausal_hs64", 1, 3072, 4, 4, 64, 2, 1, False),
+    # lengths that are no multiple of the 32-row blocks: a ragged last tile, and zigzag runs of 250 rows that
+    # begin and end inside blocks
+    ("ragged_length_one_rank", 1, 1000, 4, 2, 128, 1, 1, True),
+    ("ragged_zigzag_runs_hs64", 1, 1000, 4, 2, 64, 1, 2, True),
+    ("ragged_noncausal_two_blocks", 2, 600, 2, 1, 128, 1, 2, False),
 ])
-def test_usp_bwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
+def test_usp_bwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal, keep_ds):
     prob = tl.Problem(400 + len(name), bs, L, hc, hk, hs, U, R, causal, True, tl.BF16, with_do=True)
     p = usp.problem(bs, L, hc, hk, hs, U, R, causal, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
     q, k, v, d_o = (prob.seq_layout_dev(n) for n in ("q", "k", "v", "do"))
@@ -164,13 +178,14 @@ def test_usp_bwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
     lse = torch.empty((prob.N, bs, hc // U, L // R), dtype=torch.float32, device="cuda")
     ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
     usp.usp_attn_fwd(p, q, k, v, o, lse, 0, prob.N, ws)
-    ws2 = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    ws2 = _bwd_workspace(usp, p, prob.N, keep_ds)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, 0, prob.N, ws2)
     torch.cuda.synchronize()
     ref = orc.attention_backward(prob.val["q"], prob.val["k"], prob.val["v"], prob.val["do"], causal)
     for name_, got, r in zip(("dq", "dk", "dv"), (dq, dk, dv), ref):
         g = tl.to_f64(got)
+        assert not np.isnan(g).any(), name_
         for rank in range(prob.N):
             assert tl.max_abs(g[rank], r[:, prob.rank_positions(rank)]) <= GRAD_TOL, (name_, rank)
 
