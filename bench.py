@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # (copy calibration: a 524288 KiB copy reads FETCH_SIZE 262158, WRITE_SIZE 524288)
 PREWARM_MS = 80.0          # untimed load before the warm-up steps, see main()
 MEASURED_CLOCK_GHZ = 2.06   # block_attn_fwd_mfma on the default workload, see profiles/clock_cycles_ulysses8_L32768.md
-MEASURED_TRAFFIC_BYTES = {"ulysses8_L32768": round((150557 * (524288 / 262158) + 40988 * (524288 / 524288)) * 1024.0)}
+MEASURED_TRAFFIC_BYTES = {"ulysses8_L32768": round((150998 * (524288 / 262156) + 40985 * (524288 / 524288)) * 1024.0)}
 
 WORKLOADS = {
     # name: (bs, L, hc, hk, hs, U, R, timed rank, causal)
