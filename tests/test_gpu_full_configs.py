@@ -59,7 +59,15 @@ def test_full_size_forward_one_rank(usp, name, L, U, R, rank, samples):
             assert np.array_equal(o0[0, 0, h], v0[0, 0, h // g])
 
 
-def test_full_size_training_rank_config5(usp):
+def _bwd_workspace(usp, p, keep_ds):
+    """Backward workspace for one rank, every byte 0xFF (NaN as bf16 and fp32); with keep_ds of the size at which
+    usp_attn_bwd keeps dS between its two kernels."""
+    n = usp.usp_attn_bwd_workspace_bytes_with_ds(p, 1) if keep_ds else usp.usp_attn_bwd_workspace_bytes(p, 1)
+    return torch.full((n,), 0xFF, dtype=torch.uint8, device="cuda")
+
+
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
+def test_full_size_training_rank_config5(usp, keep_ds):
     L, U, R, rank = 65536, 2, 4, 0
     case = tl.OneRankCase(usp, 1005, 1, L, 32, 8, 128, U, R, rank, with_do=True)
     case.forward()
@@ -71,9 +79,10 @@ def test_full_size_training_rank_config5(usp):
     dq = torch.zeros_like(case.q)
     dk = torch.zeros_like(case.k)
     dv = torch.zeros_like(case.v)
-    ws = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, 1), dtype=torch.uint8, device="cuda")
+    ws = _bwd_workspace(usp, p, keep_ds)
     usp.usp_attn_bwd(p, case.q, case.k, case.v, case.o, case.lse, case.d_o, dq, dk, dv, rank, rank + 1, ws)
     torch.cuda.synchronize()
+    del ws
     qs = slice(case.u * case.hq, (case.u + 1) * case.hq)
     ks = slice(case.u * case.hkv, (case.u + 1) * case.hkv)
     allpos = np.arange(L)
@@ -113,9 +122,11 @@ def test_full_size_training_rank_config5(usp):
     assert float(dq[:, :, :, case.hq:].abs().max()) == 0.0 and float(dk[:, :, :, case.hkv:].abs().max()) == 0.0
 
 
-def test_full_size_backward_ulysses_rank_config2(usp):
-    """The backward that bench.py times on its default workload: the Ulysses-8 rank of L = 32768 (one KV head per
-    rank, so the dK/dV workgroups split the four query heads of the group and meet through atomic adds)."""
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
+def test_full_size_backward_ulysses_rank_config2(usp, keep_ds):
+    """The backward that bench.py times on its default workload, in both forms it times: the Ulysses-8 rank of
+    L = 32768 (one KV head per rank, so the dK/dV workgroups split the four query heads of the group and each writes
+    its own copy of dK/dV)."""
     L, U, R, rank = 32768, 8, 1, 0
     case = tl.OneRankCase(usp, 1002, 1, L, 32, 8, 128, U, R, rank, with_do=True)
     case.forward()
@@ -124,9 +135,10 @@ def test_full_size_backward_ulysses_rank_config2(usp):
     kv, vv = _check_forward_rows(case, rows)
     p = case.p
     dq, dk, dv = torch.zeros_like(case.q), torch.zeros_like(case.k), torch.zeros_like(case.v)
-    ws = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, 1), dtype=torch.uint8, device="cuda")
+    ws = _bwd_workspace(usp, p, keep_ds)
     usp.usp_attn_bwd(p, case.q, case.k, case.v, case.o, case.lse, case.d_o, dq, dk, dv, rank, rank + 1, ws)
     torch.cuda.synchronize()
+    del ws
     qs = slice(case.u * case.hq, (case.u + 1) * case.hq)
     ks = slice(case.u * case.hkv, (case.u + 1) * case.hkv)
     allpos = np.arange(L)
@@ -135,6 +147,7 @@ def test_full_size_backward_ulysses_rank_config2(usp):
     gv = case.values(inputs.TENSOR_DO, pos, case.q_heads)
     ref_dq, _, _ = orc.attention_backward(qv, kv, vv, gv, True, None, pos, allpos)
     assert tl.max_abs(case.seq_rows(dq, rows, qs), ref_dq) <= GRAD_TOL
+    assert not torch.isnan(dq.float()).any()
     # dK, dV of the last 128 keys: only the last 128 queries see them, and with R = 1 the rank holds every query
     last = np.arange(L - 128, L)
     ql = case.values(inputs.TENSOR_Q, last, case.q_heads)
