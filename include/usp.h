@@ -212,8 +212,12 @@ int usp_ring_attn_bwd(const void* q, const void* const* k_blocks, const void* co
  * each write their own fp32 copy of dq / dk / dv into the workspace, and one more pass adds the copies up into
  * the outputs (adding to what is there where the accumulate flags say so).  No atomic adds: the results do not
  * depend on the order in which workgroups finish, and on such problems it is the faster of the two.  The
- * workspace size is a function of the shape alone (0: no copies needed, the call is usp_ring_attn_bwd). */
+ * workspace size is a function of the shape alone (0: no copies needed, the call is usp_ring_attn_bwd).
+ * With at least usp_ring_attn_bwd_workspace_bytes_with_ds() bytes (2 bytes more per (query, key) pair of the call,
+ * lengths rounded up to 256) the dK/dV kernel keeps its dS for the dQ kernel, as described at usp_attn_bwd. */
 size_t usp_ring_attn_bwd_workspace_bytes(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, int n_blocks);
+size_t usp_ring_attn_bwd_workspace_bytes_with_ds(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
+                                                 int n_blocks);
 int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, const void* d_o, const float* lse,
                          const float* delta, float* dq, float* const* dk_blocks, float* const* dv_blocks, int bs,

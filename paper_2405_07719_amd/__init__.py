@@ -77,6 +77,8 @@ def load():
                                       P(usp_posdesc), I, P(I), V]
     lib.usp_ring_attn_bwd_workspace_bytes.restype = C.c_size_t
     lib.usp_ring_attn_bwd_workspace_bytes.argtypes = [I, L, L, I, I, I, I]
+    lib.usp_ring_attn_bwd_workspace_bytes_with_ds.restype = C.c_size_t
+    lib.usp_ring_attn_bwd_workspace_bytes_with_ds.argtypes = [I, L, L, I, I, I, I]
     lib.usp_ring_attn_bwd_ws.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, V, V, P(V), P(V), I, L, L, I, I, I, F, I,
                                          P(usp_posdesc), I, P(I), V, C.c_size_t, V]
     lib.usp_attn_bwd_workspace_bytes.restype = C.c_size_t
@@ -228,6 +230,10 @@ def usp_ring_attn_bwd(q, k_blocks, v_blocks, kpos_blocks, d_o, lse, delta, dq, d
 
 def usp_ring_attn_bwd_workspace_bytes(bs, Lq, Lk, hq, hkv, hs, n_blocks):
     return int(load().usp_ring_attn_bwd_workspace_bytes(bs, Lq, Lk, hq, hkv, hs, n_blocks))
+
+
+def usp_ring_attn_bwd_workspace_bytes_with_ds(bs, Lq, Lk, hq, hkv, hs, n_blocks):
+    return int(load().usp_ring_attn_bwd_workspace_bytes_with_ds(bs, Lq, Lk, hq, hkv, hs, n_blocks))
 
 
 def usp_ring_attn_bwd_ws(q, k_blocks, v_blocks, kpos_blocks, d_o, lse, delta, dq, dk_blocks, dv_blocks, bs, Lq, Lk, hq,

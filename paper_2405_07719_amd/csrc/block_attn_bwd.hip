@@ -1017,9 +1017,7 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
   a.ds = copies ? copies->ds : nullptr;
   a.ds_kt = (int)((Lk + 255) / 256) * 8;
   a.ds_qt8 = (int)((Lq + 255) / 256);
-  // with dS kept, the dK/dV kernel (which writes it) runs first; otherwise the two are independent
-  for (int pass = 0; pass < 2; ++pass)
-  if ((pass == 0) == (a.ds == nullptr)) {
+  auto launch_dq = [&]() -> int {
     a.n_tiles = (a.Lq + 255) / 256;
     const int64_t grid = (int64_t)a.n_tiles * hq * bs * a.k_splits;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
@@ -1038,8 +1036,9 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
         hipLaunchKernelGGL((bwd_dq_kernel<64>), dim3(n_wgs), dim3(512), 0, stream, a);
       st = launch_status();
     }
-    if (st != USP_OK) return st;
-  } else {
+    return st;
+  };
+  auto launch_dkdv_pair = [&]() -> int {
     a.n_tiles = (a.Lk + 255) / 256;
     const int64_t unsplit = (int64_t)a.n_tiles * hkv * bs * n_blocks;
     a.heads_per_wg = cut.heads_per_wg;
@@ -1063,10 +1062,14 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     // (KV group, head split) value, the two fastest indices of the item number
     a.n_queues = std::gcd(dev::kMaxItemQueues, bs * hkv * (a.g / a.heads_per_wg));
     const int64_t n_wgs = std::min<int64_t>(grid, compute_units());
-    const int dk_st = a.ds ? (hs == 128 ? launch_dkdv<128, true>(a, n_wgs, stream) : launch_dkdv<64, true>(a, n_wgs, stream))
-                           : (hs == 128 ? launch_dkdv<128, false>(a, n_wgs, stream) : launch_dkdv<64, false>(a, n_wgs, stream));
-    if (dk_st != USP_OK) return dk_st;
-  }
+    return a.ds ? (hs == 128 ? launch_dkdv<128, true>(a, n_wgs, stream) : launch_dkdv<64, true>(a, n_wgs, stream))
+                : (hs == 128 ? launch_dkdv<128, false>(a, n_wgs, stream) : launch_dkdv<64, false>(a, n_wgs, stream));
+  };
+  // with dS kept, the dK/dV kernel (which writes it) runs first; otherwise the two are independent
+  int st = a.ds ? launch_dkdv_pair() : launch_dq();
+  if (st != USP_OK) return st;
+  st = a.ds ? launch_dq() : launch_dkdv_pair();
+  if (st != USP_OK) return st;
   return launch_status();
 }
 

@@ -687,6 +687,7 @@ struct RingBwdWs {
   BwdCopies copies;
   int dkdv_copies;
   size_t dq_bytes, kv_bytes_per_block, total;   // dq_bytes / kv_bytes_per_block are 0 where the output is written directly
+  size_t ds_bytes, total_with_ds;               // room for dS behind the copies: used when the workspace reaches that far
 };
 
 RingBwdWs plan_ring_bwd_ws(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, int n_blocks) {
@@ -698,6 +699,8 @@ RingBwdWs plan_ring_bwd_ws(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int 
   w.dq_bytes = w.copies.cut.k_splits > 1 ? up256(w.copies.dq_stride * sizeof(float) * w.copies.cut.k_splits) : 0;
   w.kv_bytes_per_block = w.dkdv_copies > 1 ? up256(w.copies.dkdv_stride * sizeof(float) * w.dkdv_copies) : 0;
   w.total = w.dq_bytes + 2 * w.kv_bytes_per_block * n_blocks;
+  w.ds_bytes = up256(bwd_ds_bytes(bs, Lq, Lk, hq, n_blocks));
+  w.total_with_ds = w.total + w.ds_bytes;
   return w;
 }
 
@@ -708,6 +711,13 @@ extern "C" size_t usp_ring_attn_bwd_workspace_bytes(int bs, int64_t Lq, int64_t 
   if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1 || hq % hkv || (hs != 64 && hs != 128)) return 0;
   if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return 0;
   return plan_ring_bwd_ws(bs, Lq, Lk, hq, hkv, hs, n_blocks).total;
+}
+
+extern "C" size_t usp_ring_attn_bwd_workspace_bytes_with_ds(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
+                                                            int n_blocks) {
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1 || hq % hkv || (hs != 64 && hs != 128)) return 0;
+  if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return 0;
+  return plan_ring_bwd_ws(bs, Lq, Lk, hq, hkv, hs, n_blocks).total_with_ds;
 }
 
 extern "C" int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void* const* v_blocks,
@@ -724,8 +734,10 @@ extern "C" int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, 
   if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
   if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
   if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
-  const RingBwdWs w = plan_ring_bwd_ws(bs, Lq, Lk, hq, hkv, hs, n_blocks);
+  RingBwdWs w = plan_ring_bwd_ws(bs, Lq, Lk, hq, hkv, hs, n_blocks);
   if (w.total > 0 && (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255))) return USP_ERR_WORKSPACE;
+  if (workspace && workspace_bytes >= w.total_with_ds && !((uintptr_t)workspace & 255))
+    w.copies.ds = (char*)workspace + w.total;   // room to keep dS between the two kernels
   usp_posdesc qd = {0, Lq, 0, 0};
   usp_posdesc kd[USP_MAX_RING_BLOCKS];
   if (causal && (!qpos || !kpos_blocks)) return USP_ERR_NULL;

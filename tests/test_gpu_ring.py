@@ -289,16 +289,19 @@ def test_ring_attn_fwd_partials_of_pieces_merge_to_the_whole(usp, causal):
                                        causal, qd)
 
 
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
 @pytest.mark.parametrize("bs,L,hq,hkv,hs,R", [
+    (1, 1332, 2, 1, 128, 2),      # ragged: 666 rows per rank in zigzag runs of 333
     (1, 4096, 4, 1, 128, 2),      # 2 slices of the dQ items; 4 head splits x 4 query slices = 16 copies of dK/dV
     (2, 2048, 4, 2, 64, 4),       # batch of two, head size 64, four blocks
     (1, 16384, 16, 8, 128, 4),    # two heads per K/V head over a long block: copies of dK/dV only
     (2, 16384, 8, 8, 128, 2),     # full grids, one head per K/V head: no copies at all, the workspace size is 0
 ])
-def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R):
+def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R, keep_ds):
     """usp_ring_attn_bwd_ws (slices of the work items write copies into a workspace, one pass adds them up) against
     usp_ring_attn_bwd (one copy, split heads meet through atomic adds): same gradients up to fp32 rounding order;
-    the accumulate flags add to what is there; two runs of the workspace variant agree bit for bit."""
+    the accumulate flags add to what is there; two runs of the workspace variant agree bit for bit.  With keep_ds the
+    workspace has room for dS and the dK/dV kernel keeps it for the dQ kernel (workspace pre-filled with NaN bytes)."""
     r = 1
     order = [(r - i) % R for i in range(R)]
     q, kb, vb, kd, qd, _, _ = _ring_case(usp, 95, bs, L, hq, hkv, hs, R, r, True, True, order)
@@ -319,7 +322,11 @@ def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R):
                           [False] * R)
     nbytes = usp.usp_ring_attn_bwd_workspace_bytes(bs, Lq, Lq, hq, hkv, hs, R)
     assert (nbytes == 0) == (hq == hkv)
-    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    if keep_ds:
+        n_ds = usp.usp_ring_attn_bwd_workspace_bytes_with_ds(bs, Lq, Lq, hq, hkv, hs, R)
+        assert n_ds >= nbytes + bs * hq * R * Lq * Lq * 2
+        nbytes = n_ds
+    ws = torch.full((max(nbytes, 256),), 0xFF, dtype=torch.uint8, device="cuda")
     runs = []
     for _ in range(2):
         dq1, dk1, dv1 = fresh(float("nan"))
@@ -328,9 +335,12 @@ def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R):
         runs.append((dq1, dk1, dv1))
     torch.cuda.synchronize()
     dq1, dk1, dv1 = runs[0]
-    for a, b in zip([dq1] + dk1 + dv1, [dq0] + dk0 + dv0):
+    for i, (a, b) in enumerate(zip([dq1] + dk1 + dv1, [dq0] + dk0 + dv0)):
         assert not torch.isnan(a).any()
-        assert torch.allclose(a, b, atol=3e-5, rtol=1e-5)
+        # dq from the stored dS: P comes out of the dK/dV kernel's arithmetic there (LSE folded into the product),
+        # so a dS element now and then rounds to the neighbouring bf16 value: one such step moves dq by some 1e-3
+        loose = keep_ds and i == 0
+        assert torch.allclose(a, b, atol=5e-3 if loose else 3e-5, rtol=1e-5), i
     for a, b in zip([runs[0][0]] + runs[0][1] + runs[0][2], [runs[1][0]] + runs[1][1] + runs[1][2]):
         assert torch.equal(a, b)
     # accumulate: dq and the blocks flagged so are added to, the others overwritten
@@ -343,7 +353,7 @@ def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R):
     for i in range(R):
         want_k = dk1[i] + 1.0 if flags[i] else dk1[i]
         assert torch.allclose(dk2[i], want_k, atol=1e-6, rtol=1e-6), i
-    if nbytes:
+    if nbytes and not keep_ds:
         with pytest.raises(usp.UspError):
             usp.usp_ring_attn_bwd_ws(q, kb, vb, kd, d_o, lse, delta, dq2, dk2, dv2, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd,
                                      False, flags, ws, nbytes - 256)
