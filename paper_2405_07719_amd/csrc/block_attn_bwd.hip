@@ -904,12 +904,8 @@ template <int HS, bool WRITE_DS>
 int launch_dkdv(const BwdArgs& a, int64_t grid, hipStream_t stream) {
   constexpr int USTR = HS * 2 + 48;
   constexpr size_t lds = 256 * USTR + 2 * (2 * 32 * USTR);
-  static bool attr_set = false;   // raise the dynamic LDS limit once per instance
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)bwd_dkdv_kernel<HS, WRITE_DS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return USP_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static LdsLimitRaised lds_limit;   // per kernel instance
+  if (!raise_dynamic_lds_limit((const void*)bwd_dkdv_kernel<HS, WRITE_DS>, lds, lds_limit)) return USP_ERR_LAUNCH;
   hipLaunchKernelGGL((bwd_dkdv_kernel<HS, WRITE_DS>), dim3((unsigned)grid), dim3(512), lds, stream, a);
   return launch_status();
 }
@@ -919,12 +915,8 @@ int launch_dq_ds(const BwdArgs& a, int64_t grid, hipStream_t stream) {
   constexpr int KT = 128;
   constexpr int USTR = HS * 2 + 48;
   constexpr size_t lds = 2 * KT * USTR + 8 * (KT / 32) * 2048;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)bwd_dq_ds_kernel<HS, KT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return USP_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static LdsLimitRaised lds_limit;   // per kernel instance
+  if (!raise_dynamic_lds_limit((const void*)bwd_dq_ds_kernel<HS, KT>, lds, lds_limit)) return USP_ERR_LAUNCH;
   hipLaunchKernelGGL((bwd_dq_ds_kernel<HS, KT>), dim3((unsigned)grid), dim3(512), lds, stream, a);
   return launch_status();
 }

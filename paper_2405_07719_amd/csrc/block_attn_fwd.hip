@@ -571,12 +571,8 @@ int launch_mfma(AttnArgs a, hipStream_t stream) {
   const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs * (a.per_block ? a.n_blocks : 1);
   if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
   auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT>;
-  static bool attr_set = false;   // raise the dynamic LDS limit once per instance
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return USP_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static LdsLimitRaised lds_limit;   // per kernel instance
+  if (!raise_dynamic_lds_limit((const void*)kern, lds, lds_limit)) return USP_ERR_LAUNCH;
   // one workgroup per CU (its registers and LDS fill a CU), fewer when there are fewer items
   a.ticket_slot = next_ticket_slot();
   a.n_items = (int)grid;

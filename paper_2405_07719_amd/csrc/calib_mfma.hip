@@ -146,12 +146,8 @@ int launch_calib_mfma(int mode, int iters, float* sink, double* flop, hipStream_
     return launch_status();
   }
   constexpr size_t lds = 2 * KBYTES + 2 * VBYTES;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)calib_attention_mix, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return USP_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static LdsLimitRaised lds_limit;   // per kernel instance
+  if (!raise_dynamic_lds_limit((const void*)calib_attention_mix, lds, lds_limit)) return USP_ERR_LAUNCH;
   hipLaunchKernelGGL(calib_attention_mix, dim3(kCalibGroups), dim3(kCalibThreads), lds, stream, sink, iters);
   return launch_status();
 }

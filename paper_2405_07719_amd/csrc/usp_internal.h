@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "usp.h"
 
 namespace usp {
@@ -39,6 +41,19 @@ __host__ __device__ inline int64_t pos_max(const usp_posdesc& d, int64_t a, int6
 }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? USP_OK : USP_ERR_LAUNCH; }
+
+// Raises a kernel's limit of dynamic LDS, once per kernel instance and device (the attribute belongs to the device's
+// copy of the function).  `done` is the instance's own record, a function-local static of the caller; later calls,
+// which may come during stream capture, only read it.  Two threads that meet here both set the same value.
+struct LdsLimitRaised { std::atomic<bool> on_device[64]; };
+inline bool raise_dynamic_lds_limit(const void* kernel, size_t bytes, LdsLimitRaised& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  if (done.on_device[dev].load(std::memory_order_acquire)) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
+  done.on_device[dev].store(true, std::memory_order_release);
+  return true;
+}
 
 // Kernel launchers (defined next to their kernels).  All take validated arguments.
 // Ranks rank_begin, rank_begin + rank_step, ... below rank_end are transformed in one launch.
