@@ -200,7 +200,8 @@ def test_usp_bwd_rejects_bad_arguments(usp):
     assert e.value.status == 5
 
 
-def test_usp_fwd_and_bwd_in_a_hip_graph(usp):
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
+def test_usp_fwd_and_bwd_in_a_hip_graph(usp, keep_ds):
     """Algorithm 1 forward and backward of all ranks captured into ONE HIP graph (some thirty kernels: permutations,
     the persistent attention kernels with their item counters, merge, conversion) and replayed with eager calls and
     synchronisations between the replays: every replay must reproduce the eager result bit for bit (the forward and
@@ -209,7 +210,7 @@ def test_usp_fwd_and_bwd_in_a_hip_graph(usp):
     p = usp.problem(prob.bs, prob.L, prob.hc, prob.hk, prob.hs, 2, 2, True, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
     q, k, v, d_o = (prob.seq_layout_dev(n) for n in ("q", "k", "v", "do"))
     ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
-    ws2 = torch.empty(usp.usp_attn_bwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    ws2 = _bwd_workspace(usp, p, prob.N, keep_ds)
 
     def outputs():
         return (torch.empty_like(q), torch.empty((prob.N, 1, 4, 2048), dtype=torch.float32, device="cuda"),
