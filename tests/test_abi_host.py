@@ -97,3 +97,13 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     # the short sequence: 4 slices of the dQ items (4 copies of 16 MiB), 4 head splits x 4 query slices of dK/dV
     # (16 copies of 4 MiB each)
     assert usp.usp_attn_bwd_workspace_bytes(short, 1) == (3 * 8 + 2 * 2 + 4 * 16 + 2 * 16 * 4) * 2**20 + 2**17
+    # with room for dS (bf16, one 32 x 32 block per 2 KiB, both lengths rounded up to 256): 4 heads x 32768^2 x 2 bytes more
+    assert usp.usp_attn_bwd_workspace_bytes_with_ds(p, 1) - usp.usp_attn_bwd_workspace_bytes(p, 1) == 4 * 32768**2 * 2
+    assert usp.usp_attn_bwd_workspace_bytes_with_ds(short, 1) - usp.usp_attn_bwd_workspace_bytes(short, 1) == 4 * 8192**2 * 2
+    # one rank of the ring: 32 heads, 8 blocks of 4096 keys for its 4096 queries
+    assert (usp.usp_attn_bwd_workspace_bytes_with_ds(ring, 1) - usp.usp_attn_bwd_workspace_bytes(ring, 1)
+            == 32 * 8 * 4096**2 * 2)
+    # the per-call form: lengths that are no multiple of 256 are rounded up (333 -> 512 queries, 700 -> 768 keys)
+    plain = usp.usp_ring_attn_bwd_workspace_bytes(2, 333, 700, 4, 2, 128, 3)
+    assert usp.usp_ring_attn_bwd_workspace_bytes_with_ds(2, 333, 700, 4, 2, 128, 3) - plain == 2 * 4 * 3 * 512 * 768 * 2
+    assert usp.usp_ring_attn_bwd_workspace_bytes_with_ds(2, 333, 700, 4, 3, 128, 3) == 0     # heads do not divide
