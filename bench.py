@@ -202,6 +202,14 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                 "launches_per_step": 1, "avg_launch_ms": round(attn_ms, 4), "traffic": traffic,
                 "algorithmic_bytes": float(2 * qh.numel() * 2 + 2 * kh.numel() * 2 + bs * hq * Lq * 4)}
+    if traffic is not None:
+        # the counters sit between the eight XCDs' private L2s and the fabric (Infinity Cache hits included): K and V
+        # must enter every L2 that runs a workgroup of their KV head, so what a perfect schedule would read here is
+        # Q once and K, V once per XCD, not once
+        kv_bytes = 2 * kh.numel() * 2
+        roofline["traffic_floor_with_8_l2"] = float(roofline["algorithmic_bytes"] + 7 * kv_bytes)
+        roofline["traffic_note"] = ("fills of the eight private L2s (the 16 MiB of K and V stay in the 256 MiB Infinity "
+                                    "Cache: cache-to-cache traffic, 0.36 TB/s, not a bound)")
     if stepwise is not None:
         roofline["stepwise_ring"] = stepwise
     # the same fraction against CUs x the clock the box sustained under this kernel (GRBM_GUI_ACTIVE / duration in
