@@ -66,7 +66,7 @@ struct BwdArgs {
   int k_splits, q_splits;
   size_t dq_part_stride, dkdv_part_stride;
   // dS kept between the two kernels (null: each kernel forms its own).  The dK/dV kernel, which runs first then,
-  // writes every 32 x 32 block of dS it forms, unscaled, as bf16 [key][query] (2 KiB), block (head, K/V block, key
+  // writes every 32 x 32 block of dS it forms, unscaled, as bf16 [query half][key][16 queries] (2 KiB), block (head, K/V block, key
   // tile kt, query tile qt) at index ((((b hq + h) n_blocks + blk) ds_qt8 + qt / 8) ds_kt + kt) 8 + qt % 8: what
   // a workgroup of the dQ kernel (256 queries: qt / 8) reads, key tile after key tile, is one contiguous stream.
   // The dQ kernel reads the blocks that hold a visible pair (all of those have been written) and is left with
@@ -103,6 +103,10 @@ struct DkdvItemArgs {
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
+// A stored 32 x 32 block of dS is two halves of 1 KiB, [query half][key][16 queries]: every 16-byte store
+// instruction of the writer fills whole 128-byte lines.  In the reader's LDS the second half sits 1152 bytes after
+// the first (an odd multiple of 128: the two 16-lane groups of a transpose read then hit different banks).
+constexpr int kDsHalfLds = 1152, kDsBlockLds = kDsHalfLds + 1024;
 
 // transpose-read address of this lane inside a [rows][VSTR] tile: see the forward kernel
 template <int VSTR>
@@ -399,7 +403,7 @@ void bwd_dq_ds_kernel(const BwdArgs) {
   static_assert(KT * CPR % NT == 0, "whole chunks per thread");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* const lds = smem;                           // [2][STAGE]  K
-  char* const ds_all = smem + 2 * STAGE;            // [8 waves][NB blocks][32 keys][32 queries] bf16
+  char* const ds_all = smem + 2 * STAGE;            // [8 waves][NB blocks] of kDsBlockLds bytes
 
   __shared__ int next_item[2];
   __shared__ unsigned empty_queues;
@@ -480,18 +484,19 @@ void bwd_dq_ds_kernel(const BwdArgs) {
         for (int j = 0; j < 2 * NB; ++j) dreg[j] = *(const u32x4*)(blk0 + (j >> 1) * ds_kt_stride + (j & 1) * 1024);
       }
     };
-    char* const ds_s = ds_all + wave * (NB * 2048);
+    char* const ds_s = ds_all + wave * (NB * kDsBlockLds);
     auto stash = [&](int buf, bool seen) {
       char* base = lds + buf * STAGE;
 #pragma unroll
       for (int c = 0; c < CPT; ++c) *(u32x4*)(base + (st_row + c * (NT / CPR)) * USTR + st_col * 16) = kreg[c];
       if (seen) {
 #pragma unroll
-        for (int j = 0; j < 2 * NB; ++j) *(u32x4*)(ds_s + j * 1024 + lane * 16) = dreg[j];
+        for (int j = 0; j < 2 * NB; ++j) *(u32x4*)(ds_s + (j >> 1) * kDsBlockLds + (j & 1) * kDsHalfLds + lane * 16) = dreg[j];
       }
     };
     const int tr_off = tr_lane_offset<USTR>(lane);
-    const int tr_off_ds = tr_lane_offset<64>(lane);
+    // transpose-read address inside a block: 32-byte rows of one half, the halves kDsHalfLds apart
+    const int tr_off_ds = (4 * (lane >> 5) + ((lane & 15) >> 2)) * 32 + ((lane >> 4) & 1) * kDsHalfLds + (lane & 3) * 8;
 
     for (int blk = 0; blk < n_blocks; ++blk) {
     kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
@@ -512,7 +517,7 @@ void bwd_dq_ds_kernel(const BwdArgs) {
       bf16x8 dsf[2 * NB];
       if (seen) {
 #pragma unroll
-        for (int st = 0; st < 2 * NB; ++st) dsf[st] = tr_read<64>(ds_s + (st >> 1) * 2048 + (16 * (st & 1)) * 64 + tr_off_ds);
+        for (int st = 0; st < 2 * NB; ++st) dsf[st] = tr_read<32>(ds_s + (st >> 1) * kDsBlockLds + (16 * (st & 1)) * 32 + tr_off_ds);
       }
       if (more) fetch(it + 1, seen_next);
       __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute
@@ -735,7 +740,7 @@ void bwd_dkdv_kernel(const BwdArgs) {
     const int it0 = (int)((int64_t)nt * qs / q_splits), it1 = (int)((int64_t)nt * (qs + 1) / q_splits);
     // where the dS blocks of this head and K/V block begin
     char* ds_head = nullptr;
-    const int ds_lane_off = l32 * 64 + hl * 16;
+    const int ds_lane_off = l32 * 32 + hl * 16;
     if constexpr (WRITE_DS)
       ds_head = (char*)ap->ds + ((((size_t)b * a.hq + h) * ap->n_blocks + blk) * ap->ds_qt8 * ap->ds_kt * 8) * 2048;
     if (it1 > it0) {
@@ -817,7 +822,7 @@ void bwd_dkdv_kernel(const BwdArgs) {
           // next instructions from overwriting them only in this form.  (With the block's offset in a scalar
           // register, the data registers were reused at once and some blocks came out holding the next step's
           // values, now and then: measured, the results differed from run to run.)
-          __builtin_amdgcn_raw_buffer_store_b128(u32x4{e[0], o[0], e[1], o[1]}, ds_blk, ds_lane_off + 32 * st, 0, 0);
+          __builtin_amdgcn_raw_buffer_store_b128(u32x4{e[0], o[0], e[1], o[1]}, ds_blk, ds_lane_off + 1024 * st, 0, 0);
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
@@ -914,7 +919,7 @@ template <int HS>
 int launch_dq_ds(const BwdArgs& a, int64_t grid, hipStream_t stream) {
   constexpr int KT = 128;
   constexpr int USTR = HS * 2 + 48;
-  constexpr size_t lds = 2 * KT * USTR + 8 * (KT / 32) * 2048;
+  constexpr size_t lds = 2 * KT * USTR + 8 * (KT / 32) * kDsBlockLds;
   static LdsLimitRaised lds_limit;   // per kernel instance
   if (!raise_dynamic_lds_limit((const void*)bwd_dq_ds_kernel<HS, KT>, lds, lds_limit)) return USP_ERR_LAUNCH;
   hipLaunchKernelGGL((bwd_dq_ds_kernel<HS, KT>), dim3((unsigned)grid), dim3(512), lds, stream, a);
