@@ -888,12 +888,15 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* dst, size_t n4) {
   if (i < n4) dst[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
-// fp32 accumulator -> bf16 / fp32 output, 4 elements per lane
+// fp32 accumulator -> bf16 / fp32 output, 4 elements per lane; blockIdx.y picks one of two tensors of the same size
+// (dK and dV go through one launch)
 template <typename OutT>
-__global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src, OutT* dst, size_t n4, int n_copies,
-                                                          size_t copy_stride4, int add_to_dst) {
+__global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src0, OutT* dst0, const float* src1, OutT* dst1,
+                                                          size_t n4, int n_copies, size_t copy_stride4, int add_to_dst) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
+  const float* src = blockIdx.y ? src1 : src0;
+  OutT* dst = blockIdx.y ? dst1 : dst0;
   f32x4 v = __builtin_nontemporal_load((const f32x4*)src + i);
   for (int c = 1; c < n_copies; ++c) v += __builtin_nontemporal_load((const f32x4*)src + c * copy_stride4 + i);
   if constexpr (sizeof(OutT) == 4) {
@@ -1080,16 +1083,22 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
 
 int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream, int n_copies,
                        size_t copy_stride, int add_to_dst) {
+  return launch_bwd_convert2(src, dst, nullptr, nullptr, n, out_dtype, stream, n_copies, copy_stride, add_to_dst);
+}
+
+int launch_bwd_convert2(const float* src0, void* dst0, const float* src1, void* dst1, size_t n, int out_dtype,
+                        hipStream_t stream, int n_copies, size_t copy_stride, int add_to_dst) {
   if (add_to_dst && out_dtype != USP_FP32) return USP_ERR_UNSUPPORTED;
   const size_t n4 = n / 4;
   const size_t grid = (n4 + 255) / 256;
   if (grid > 0x7fffffffull || n_copies < 1 || (copy_stride & 3)) return USP_ERR_UNSUPPORTED;
+  const dim3 g((unsigned)grid, src1 ? 2u : 1u);
   if (out_dtype == USP_FP32)
-    hipLaunchKernelGGL((bwd_convert_kernel<float>), dim3((unsigned)grid), dim3(256), 0, stream, src, (float*)dst, n4,
+    hipLaunchKernelGGL((bwd_convert_kernel<float>), g, dim3(256), 0, stream, src0, (float*)dst0, src1, (float*)dst1, n4,
                        n_copies, copy_stride / 4, add_to_dst);
   else
-    hipLaunchKernelGGL((bwd_convert_kernel<__bf16>), dim3((unsigned)grid), dim3(256), 0, stream, src, (__bf16*)dst, n4,
-                       n_copies, copy_stride / 4, 0);
+    hipLaunchKernelGGL((bwd_convert_kernel<__bf16>), g, dim3(256), 0, stream, src0, (__bf16*)dst0, src1, (__bf16*)dst1,
+                       n4, n_copies, copy_stride / 4, 0);
   return launch_status();
 }
 

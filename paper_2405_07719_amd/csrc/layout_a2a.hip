@@ -14,9 +14,14 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 1;   // vectors per thread; measured on MI355X: 1 -> 6.1 TB/s, 4 -> 5.4 TB/s, 8 -> 3.9 TB/s
 
+constexpr int kMaxTensors = USP_LAYOUT_MAX_TENSORS;
+
+// Up to kMaxTensors tensors of one geometry (same heads, same ranks) go through one launch: on short sequences a
+// launch costs as much as the copy itself (K and V of a rank; Q, O and dO of its backward; dK and dV).
 struct LayoutArgs {
-  const char* seq;     // sequence-layout buffer base
-  const char* head;    // head-layout buffer base (slot of rank head_rank_base)
+  const char* seq[kMaxTensors];    // sequence-layout buffer bases
+  const char* head[kMaxTensors];   // head-layout buffer bases (slot of rank head_rank_base)
+  int z_per_tensor;                // blockIdx.z values per tensor = ranks of the launch x batch
   int64_t n;           // rows per slab = L/N
   int64_t Lq;          // L/R
   int bs, U, rank_begin, rank_step, head_rank_base;
@@ -26,19 +31,21 @@ struct LayoutArgs {
 
 template <typename Vec, bool kToHead>
 __global__ __launch_bounds__(kThreads) void layout_a2a_kernel(LayoutArgs a) {
-  // blockIdx.z -> (rank, batch), blockIdx.y -> source shard u', blockIdx.x -> position in the slab
-  const int slot = (int)(blockIdx.z / a.bs);                 // the slot-th rank of this launch
+  // blockIdx.z -> (tensor, rank, batch), blockIdx.y -> source shard u', blockIdx.x -> position in the slab
+  const int tensor = (int)(blockIdx.z / a.z_per_tensor);
+  const int z = (int)(blockIdx.z % a.z_per_tensor);
+  const int slot = z / a.bs;                                 // the slot-th rank of this launch
   const int rank = a.rank_begin + slot * a.rank_step;
-  const int b = (int)(blockIdx.z % a.bs);
+  const int b = z % a.bs;
   const int up = (int)blockIdx.y;
   const int r = rank / a.U, u = rank % a.U;
   const uint64_t slab_vecs = (uint64_t)a.n * a.run_vecs;
   // head-layout side: whole buffers are indexed by rank; a packed workspace holds the launch's ranks back to back
   const uint64_t head_slot = a.head_rank_base < 0 ? (uint64_t)slot : (uint64_t)(rank - a.head_rank_base);
   const uint64_t head_row0 = head_slot * a.bs * a.Lq + (uint64_t)b * a.Lq + (uint64_t)up * a.n;
-  Vec* head = (Vec*)a.head + head_row0 * a.run_vecs;
+  Vec* head = (Vec*)a.head[tensor] + head_row0 * a.run_vecs;
   const uint64_t seq_row0 = ((uint64_t)(r * a.U + up) * a.bs + b) * a.n;
-  Vec* seq = (Vec*)a.seq + seq_row0 * a.row_vecs + (uint64_t)u * a.run_vecs;
+  Vec* seq = (Vec*)a.seq[tensor] + seq_row0 * a.row_vecs + (uint64_t)u * a.run_vecs;
 
   // One 32-bit division per thread; the following vectors step by kThreads with carried row / column.
   const uint32_t slab32 = (uint32_t)slab_vecs;
@@ -73,15 +80,17 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 template <typename Vec>
-int launch_vec(LayoutArgs a, int dir, size_t run_bytes, size_t row_bytes, int n_ranks, hipStream_t stream) {
+int launch_vec(LayoutArgs a, int dir, size_t run_bytes, size_t row_bytes, int n_ranks, int n_tensors, hipStream_t stream) {
   a.run_vecs = (uint32_t)(run_bytes / sizeof(Vec));
   a.row_vecs = (uint32_t)(row_bytes / sizeof(Vec));
   const uint64_t slab_vecs = (uint64_t)a.n * a.run_vecs;
   const uint64_t gx = (slab_vecs + (uint64_t)kThreads * kUnroll - 1) / ((uint64_t)kThreads * kUnroll);
   // the kernel indexes a slab with 32 bits (a slab is one rank's share of one shard: far below 4 Gi vectors)
-  if (slab_vecs + (uint64_t)kThreads * kUnroll >= (1ull << 32) || (uint64_t)n_ranks * a.bs > 65535ull || a.U > 65535)
+  if (slab_vecs + (uint64_t)kThreads * kUnroll >= (1ull << 32) || (uint64_t)n_tensors * n_ranks * a.bs > 65535ull ||
+      a.U > 65535)
     return USP_ERR_UNSUPPORTED;
-  dim3 grid((unsigned)gx, (unsigned)a.U, (unsigned)(n_ranks * a.bs));
+  a.z_per_tensor = n_ranks * a.bs;
+  dim3 grid((unsigned)gx, (unsigned)a.U, (unsigned)(n_tensors * n_ranks * a.bs));
   if (dir == USP_SEQ_TO_HEAD)
     hipLaunchKernelGGL((layout_a2a_kernel<Vec, true>), grid, dim3(kThreads), 0, stream, a);
   else
@@ -93,11 +102,23 @@ int launch_vec(LayoutArgs a, int dir, size_t run_bytes, size_t row_bytes, int n_
 
 int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src, void* dst, int rank_begin,
                       int rank_end, int head_rank_base, hipStream_t stream, int rank_step) {
+  return launch_layout_a2a_multi(p, heads, dir, 1, &src, &dst, rank_begin, rank_end, head_rank_base, stream, rank_step);
+}
+
+int launch_layout_a2a_multi(const usp_problem& p, int heads, int dir, int n_tensors, const void* const* src,
+                            void* const* dst, int rank_begin, int rank_end, int head_rank_base, hipStream_t stream,
+                            int rank_step) {
+  if (n_tensors < 1 || n_tensors > kMaxTensors) return USP_ERR_UNSUPPORTED;
   const size_t es = dtype_size(p.dtype);
   const int N = p.ulysses * p.ring;
   LayoutArgs a;
-  a.seq = (const char*)(dir == USP_SEQ_TO_HEAD ? src : dst);
-  a.head = (const char*)(dir == USP_SEQ_TO_HEAD ? dst : src);
+  uintptr_t align = 0;
+  for (int t = 0; t < kMaxTensors; ++t) {
+    const int tt = t < n_tensors ? t : 0;
+    a.seq[t] = (const char*)(dir == USP_SEQ_TO_HEAD ? src[tt] : dst[tt]);
+    a.head[t] = (const char*)(dir == USP_SEQ_TO_HEAD ? dst[tt] : src[tt]);
+    align |= (uintptr_t)src[tt] | (uintptr_t)dst[tt];
+  }
   a.n = p.L / N;
   a.Lq = p.L / p.ring;
   a.bs = p.bs;
@@ -107,12 +128,12 @@ int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src,
   a.head_rank_base = head_rank_base;
   const size_t run_bytes = (size_t)(heads / p.ulysses) * p.hs * es;
   const size_t row_bytes = (size_t)heads * p.hs * es;
-  const uintptr_t align = (uintptr_t)src | (uintptr_t)dst | run_bytes;
+  align |= run_bytes;
   const int n_ranks = (rank_end - rank_begin + rank_step - 1) / rank_step;
-  if (align % 16 == 0) return launch_vec<u32x4>(a, dir, run_bytes, row_bytes, n_ranks, stream);
-  if (align % 8 == 0) return launch_vec<u32x2>(a, dir, run_bytes, row_bytes, n_ranks, stream);
-  if (align % 4 == 0) return launch_vec<uint32_t>(a, dir, run_bytes, row_bytes, n_ranks, stream);
-  return launch_vec<uint16_t>(a, dir, run_bytes, row_bytes, n_ranks, stream);
+  if (align % 16 == 0) return launch_vec<u32x4>(a, dir, run_bytes, row_bytes, n_ranks, n_tensors, stream);
+  if (align % 8 == 0) return launch_vec<u32x2>(a, dir, run_bytes, row_bytes, n_ranks, n_tensors, stream);
+  if (align % 4 == 0) return launch_vec<uint32_t>(a, dir, run_bytes, row_bytes, n_ranks, n_tensors, stream);
+  return launch_vec<uint16_t>(a, dir, run_bytes, row_bytes, n_ranks, n_tensors, stream);
 }
 
 }  // namespace usp

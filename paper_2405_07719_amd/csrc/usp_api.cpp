@@ -301,22 +301,22 @@ namespace {
 int stage_kv_blocks(const usp_problem& p, const void* k, const void* v, char* k_head, char* v_head, size_t block_bytes,
                     int c0, int c1, hipStream_t stream) {
   const int U = p.ulysses, R = p.ring, n_cols = c1 - c0;
+  // K and V have one geometry: both go through the same launches
   const void* src[2] = {k, v};
-  char* dst[2] = {k_head, v_head};
-  for (int t = 0; t < 2; ++t) {
-    int st = USP_OK;
-    if (n_cols == U) {
-      st = launch_layout_a2a(p, p.hk, USP_SEQ_TO_HEAD, src[t], dst[t], 0, U * R, -1, stream);
-    } else if (n_cols == 1) {
-      st = launch_layout_a2a(p, p.hk, USP_SEQ_TO_HEAD, src[t], dst[t], c0, U * R, -1, stream, U);
-    } else {
-      for (int r = 0; r < R && st == USP_OK; ++r)
-        st = launch_layout_a2a(p, p.hk, USP_SEQ_TO_HEAD, src[t], dst[t] + (size_t)r * n_cols * block_bytes, r * U + c0,
-                               r * U + c1, -1, stream);
+  int st = USP_OK;
+  if (n_cols == U) {
+    void* dst[2] = {k_head, v_head};
+    st = launch_layout_a2a_multi(p, p.hk, USP_SEQ_TO_HEAD, 2, src, dst, 0, U * R, -1, stream);
+  } else if (n_cols == 1) {
+    void* dst[2] = {k_head, v_head};
+    st = launch_layout_a2a_multi(p, p.hk, USP_SEQ_TO_HEAD, 2, src, dst, c0, U * R, -1, stream, U);
+  } else {
+    for (int r = 0; r < R && st == USP_OK; ++r) {
+      void* dst[2] = {k_head + (size_t)r * n_cols * block_bytes, v_head + (size_t)r * n_cols * block_bytes};
+      st = launch_layout_a2a_multi(p, p.hk, USP_SEQ_TO_HEAD, 2, src, dst, r * U + c0, r * U + c1, -1, stream);
     }
-    if (st != USP_OK) return st;
   }
-  return USP_OK;
+  return st;
 }
 
 }  // namespace
@@ -575,10 +575,10 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
 
   for (int rank = rank_begin; rank < rank_end; ++rank) {
     const int r = rank / U, u = rank % U;
-    const void* srcs[3] = {q, o, d_o};
-    const size_t dsts[3] = {f.q_head, f.o_head, f.do_head};
-    for (int t = 0; t < 3; ++t) {
-      st = launch_layout_a2a(*p, p->hc, USP_SEQ_TO_HEAD, srcs[t], ws + dsts[t], rank, rank + 1, rank, stream);
+    {   // Q, O and dO of this rank to head layout: one geometry, one launch
+      const void* srcs[3] = {q, o, d_o};
+      void* dsts[3] = {ws + f.q_head, ws + f.o_head, ws + f.do_head};
+      st = launch_layout_a2a_multi(*p, p->hc, USP_SEQ_TO_HEAD, 3, srcs, dsts, rank, rank + 1, rank, stream);
       if (st != USP_OK) return st;
     }
     float* delta = (float*)(ws + f.delta);
@@ -630,15 +630,13 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
       const size_t sl = slot(r, u);
       char* kdst = ws + f.k_head + sl * f.kv_block_bytes;
       char* vdst = ws + f.v_head + sl * f.kv_block_bytes;
-      st = launch_bwd_convert((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), kdst, kv_elems, p->dtype, stream,
-                              f.dkdv_copies, f.copies.dkdv_stride);
+      st = launch_bwd_convert2((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), kdst,
+                               (const float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), vdst, kv_elems, p->dtype, stream,
+                               f.dkdv_copies, f.copies.dkdv_stride);
       if (st != USP_OK) return st;
-      st = launch_bwd_convert((const float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), vdst, kv_elems, p->dtype, stream,
-                              f.dkdv_copies, f.copies.dkdv_stride);
-      if (st != USP_OK) return st;
-      st = launch_layout_a2a(*p, p->hk, USP_HEAD_TO_SEQ, kdst, dk, rank, rank + 1, rank, stream);
-      if (st != USP_OK) return st;
-      st = launch_layout_a2a(*p, p->hk, USP_HEAD_TO_SEQ, vdst, dv, rank, rank + 1, rank, stream);
+      const void* heads_kv[2] = {kdst, vdst};
+      void* seqs_kv[2] = {dk, dv};
+      st = launch_layout_a2a_multi(*p, p->hk, USP_HEAD_TO_SEQ, 2, heads_kv, seqs_kv, rank, rank + 1, rank, stream);
       if (st != USP_OK) return st;
     }
   return USP_OK;

@@ -61,6 +61,11 @@ inline bool raise_dynamic_lds_limit(const void* kernel, size_t bytes, LdsLimitRa
 // head_rank_base < 0: the head-layout side is a packed workspace holding the launch's ranks back to back.
 int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src, void* dst, int rank_begin,
                       int rank_end, int head_rank_base, hipStream_t stream, int rank_step = 1);
+// The same for up to USP_LAYOUT_MAX_TENSORS tensors of one geometry (same heads, ranks and head_rank_base) in ONE launch.
+#define USP_LAYOUT_MAX_TENSORS 3
+int launch_layout_a2a_multi(const usp_problem& p, int heads, int dir, int n_tensors, const void* const* src,
+                            void* const* dst, int rank_begin, int rank_end, int head_rank_base, hipStream_t stream,
+                            int rank_step = 1);
 int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                      float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
                      hipStream_t stream);
@@ -113,6 +118,9 @@ int launch_block_attn_bwd(const void* q, const void* k, const void* v, const voi
 // dst[i] = sum over n_copies of src[c * copy_stride + i], converted (fp32 output: optionally added to dst[i])
 int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hipStream_t stream, int n_copies = 1,
                        size_t copy_stride = 0, int add_to_dst = 0);
+// The same for two tensors of the same size and copy layout in one launch (src1 == nullptr: one tensor).
+int launch_bwd_convert2(const float* src0, void* dst0, const float* src1, void* dst1, size_t n, int out_dtype,
+                        hipStream_t stream, int n_copies = 1, size_t copy_stride = 0, int add_to_dst = 0);
 
 // Calibration loops (mode 0 pure MFMA, 1 attention mix); sink holds kCalibSinkBytes.  *flop = MFMA flop of the launch.
 constexpr size_t kCalibSinkBytes = 256 * 512 * sizeof(float);
