@@ -163,3 +163,26 @@ def test_full_size_backward_ulysses_rank_config2(usp, keep_ds):
     dk_sum = dk[:, :, :, ks, :].double().sum(dim=(0, 2)).cpu().numpy()
     dk_abs = float(dk[:, :, :, ks, :].double().abs().sum(dim=(0, 2)).max())
     assert np.max(np.abs(dk_sum)) <= 2e-3 * dk_abs
+
+
+def test_full_size_stored_ds_backward_is_deterministic(usp):
+    """The backward with dS kept between its kernels, config 2 at full size (4.3 GB of dS through 16-byte stores):
+    runs with the workspace pre-filled with 0xFF and with 0x00 bytes agree bit for bit, so no store lost or mixed up
+    its data and the dQ kernel read nothing that had not been written."""
+    L, U, R, rank = 32768, 8, 1, 0
+    case = tl.OneRankCase(usp, 1012, 1, L, 32, 8, 128, U, R, rank, with_do=True)
+    case.forward()
+    p = case.p
+    n = usp.usp_attn_bwd_workspace_bytes_with_ds(p, 1)
+    outs = []
+    for fill in (0xFF, 0x00, 0xFF):
+        ws = torch.full((n,), fill, dtype=torch.uint8, device="cuda")
+        dq, dk, dv = torch.zeros_like(case.q), torch.zeros_like(case.k), torch.zeros_like(case.v)
+        usp.usp_attn_bwd(p, case.q, case.k, case.v, case.o, case.lse, case.d_o, dq, dk, dv, rank, rank + 1, ws)
+        torch.cuda.synchronize()
+        del ws
+        outs.append((dq, dk, dv))
+    for other in outs[1:]:
+        for a, b in zip(other, outs[0]):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert not any(torch.isnan(t.float()).any().item() for t in outs[0])
