@@ -22,6 +22,9 @@ struct MergeArgs {
   int64_t Lq;
   int n_parts, hq, hs, bs;
   int64_t rows_per_batch;   // Lq * hq
+  // SEQ instances: o_out is the first sequence-layout shard of the rank's Ulysses group, [U][bs][rows_per_shard]
+  // [seq_heads][hs]; the rank's heads begin at seq_head0 (Algorithm 1's last all-to-all rides on the merge's stores)
+  int rows_per_shard, seq_heads, seq_head0;
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -40,7 +43,7 @@ __device__ inline void store4(__bf16* p, f32x4 v) {
 }
 
 // NP = number of parts when it is at most 8 (everything unrolled, all loads in flight at once); NP = 0: any n.
-template <typename PartT, typename OutT, int NP>
+template <typename PartT, typename OutT, int NP, bool SEQ>
 __global__ __launch_bounds__(kThreads) void lse_merge_kernel(MergeArgs a) {
   const int vec_per_row = a.hs / 4;
   const int64_t vec = (int64_t)blockIdx.x * kThreads + threadIdx.x;      // over bs * rows_per_batch * vec_per_row
@@ -96,19 +99,25 @@ __global__ __launch_bounds__(kThreads) void lse_merge_kernel(MergeArgs a) {
       if (w != 0.f) acc += load4((const PartT*)a.o[p] + off) * w;
     }
   }
-  store4((OutT*)a.o_out + off, acc);
+  int64_t out_off = off;
+  if constexpr (SEQ) {
+    const int64_t shard = i / a.rows_per_shard, s = i - shard * a.rows_per_shard;
+    out_off = (((shard * a.bs + b) * a.rows_per_shard + s) * a.seq_heads + a.seq_head0 + h) * a.hs +
+              (vec - row_all * vec_per_row) * 4;
+  }
+  store4((OutT*)a.o_out + out_off, acc);
   if (vec - row_all * vec_per_row == 0) a.lse_out[li] = lse_out;
 }
 
-template <typename PartT, typename OutT>
+template <typename PartT, typename OutT, bool SEQ = false>
 void launch_typed(const MergeArgs& a, dim3 grid, hipStream_t stream) {
   switch (a.n_parts) {
 #define USP_MERGE_CASE(N) \
-  case N: hipLaunchKernelGGL((lse_merge_kernel<PartT, OutT, N>), grid, dim3(kThreads), 0, stream, a); break;
+  case N: hipLaunchKernelGGL((lse_merge_kernel<PartT, OutT, N, SEQ>), grid, dim3(kThreads), 0, stream, a); break;
     USP_MERGE_CASE(1) USP_MERGE_CASE(2) USP_MERGE_CASE(3) USP_MERGE_CASE(4)
     USP_MERGE_CASE(5) USP_MERGE_CASE(6) USP_MERGE_CASE(7) USP_MERGE_CASE(8)
 #undef USP_MERGE_CASE
-    default: hipLaunchKernelGGL((lse_merge_kernel<PartT, OutT, 0>), grid, dim3(kThreads), 0, stream, a); break;
+    default: hipLaunchKernelGGL((lse_merge_kernel<PartT, OutT, 0, SEQ>), grid, dim3(kThreads), 0, stream, a); break;
   }
 }
 
@@ -116,8 +125,12 @@ void launch_typed(const MergeArgs& a, dim3 grid, hipStream_t stream) {
 
 int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                      float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
-                     hipStream_t stream) {
+                     hipStream_t stream, const SeqLayoutIO* seq) {
   MergeArgs a;
+  a.rows_per_shard = seq ? seq->rows_per_shard : 0;
+  a.seq_heads = seq ? seq->heads : 0;
+  a.seq_head0 = seq ? seq->head0 : 0;
+  if (seq && part_dtype != USP_FP32) return USP_ERR_UNSUPPORTED;
   for (int i = 0; i < n_parts; ++i) {
     a.o[i] = o_parts[i];
     a.lse[i] = lse_parts[i];
@@ -134,7 +147,9 @@ int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, 
   const int64_t gx = (vecs + kThreads - 1) / kThreads;
   if (gx > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
   dim3 grid((unsigned)gx);
-  if (part_dtype == USP_FP32 && out_dtype == USP_BF16) launch_typed<float, __bf16>(a, grid, stream);
+  if (seq && out_dtype == USP_BF16) launch_typed<float, __bf16, true>(a, grid, stream);
+  else if (seq) launch_typed<float, float, true>(a, grid, stream);
+  else if (part_dtype == USP_FP32 && out_dtype == USP_BF16) launch_typed<float, __bf16>(a, grid, stream);
   else if (part_dtype == USP_FP32 && out_dtype == USP_FP32) launch_typed<float, float>(a, grid, stream);
   else if (part_dtype == USP_BF16 && out_dtype == USP_BF16) launch_typed<__bf16, __bf16>(a, grid, stream);
   else launch_typed<__bf16, float>(a, grid, stream);

@@ -406,10 +406,9 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
         st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, n, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq,
                                       hkv, p->hs, scale, p->causal ? 1 : 0, qd, stream, &seq);
         if (st != USP_OK) return st;
-        st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, n, ws + f.o_head, lse_rank,
-                              p->bs, Lq, hq, p->hs, USP_FP32, p->dtype, stream);
-        if (st != USP_OK) return st;
-        st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.o_head, o, rank, rank + 1, rank, stream);
+        // the merge writes O straight to the sequence-layout shards (step 6 rides on its stores)
+        st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, n, (char*)o + group_off, lse_rank,
+                              p->bs, Lq, hq, p->hs, USP_FP32, p->dtype, stream, &seq);
         if (st != USP_OK) return st;
         continue;
       }
@@ -436,9 +435,13 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
       l_ptrs[i] = l_dst;
     }
     if (R > 1) {
-      st = launch_lse_merge(o_ptrs, l_ptrs, R, ws + f.o_head, lse_rank, p->bs, Lq, hq, p->hs, USP_FP32, p->dtype,
-                            stream);
+      // Step 6 rides on the merge's stores: O goes straight to the sequence-layout shards of the Ulysses group
+      const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
+      const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * es;
+      st = launch_lse_merge(o_ptrs, l_ptrs, R, (char*)o + group_off, lse_rank, p->bs, Lq, hq, p->hs, USP_FP32, p->dtype,
+                            stream, &seq);
       if (st != USP_OK) return st;
+      continue;
     }
     // Step 6: O back to the sequence layout.
     st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.o_head, o, rank, rank + 1, rank, stream);

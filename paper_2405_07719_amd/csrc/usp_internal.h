@@ -66,13 +66,14 @@ int launch_layout_a2a(const usp_problem& p, int heads, int dir, const void* src,
 int launch_layout_a2a_multi(const usp_problem& p, int heads, int dir, int n_tensors, const void* const* src,
                             void* const* dst, int rank_begin, int rank_end, int head_rank_base, hipStream_t stream,
                             int rank_step = 1);
-int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
-                     float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
-                     hipStream_t stream);
 // Optional: Q is read from and O written to the sequence-layout shards of the rank's Ulysses group
 // ([U][bs][rows_per_shard][heads][hs], q and o pointing at the group's first shard) instead of dense head-layout
-// tensors; head0 is the rank's first head.  bf16 instance only.
+// tensors; head0 is the rank's first head.  Attention kernels: bf16 instance only.  Merge: fp32 partials only (the
+// merged O goes to the shards, the merged LSE stays [bs,hq,Lq]).
 struct SeqLayoutIO { int rows_per_shard, heads, head0; };
+int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
+                     float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
+                     hipStream_t stream, const SeqLayoutIO* seq = nullptr);
 int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
