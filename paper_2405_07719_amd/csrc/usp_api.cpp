@@ -245,9 +245,10 @@ bool ring_in_one_launch(const usp_problem& p) { return p.dtype == USP_BF16 && p.
 // being a work item of its own with a partial result of its own (1: the blocks themselves, for R > 1).  In the
 // unsplit launch the item of the last query tile walks every key, which takes ratio = 256 / (items x 1/2 under
 // a causal mask) times a CU's fair share of the whole launch.  Split from a ratio of 1.5: into two parts in all, three
-// from a ratio of 3.5 (the R blocks as they are when that is already as many or more); more parts cost more in
-// partial results (fp32, written and merged) than they gain (measured at L = 8192 and 16384: 2 and 3 pieces 1.4-1.8 x
-// faster than none, 4 and more slower again).  Pieces hold at least 1024 keys, and a launch takes no more parts in
+// from a ratio of 3.5, four from 7 (the R blocks as they are when that is already as many or more); more parts cost
+// more in partial results (fp32, written and merged) than they gain, and with one or two items per CU the finish time
+// is a bin-packing matter (measured at L = 8192 and 16384: 2 and 3 pieces 1.4-1.8 x faster than none, 4 and more slower
+// again; at L = 4096: 76 / 64 / 58 us with 2 / 3 / 4).  Pieces hold at least 1024 keys, and a launch takes no more parts in
 // all than it takes blocks.  Host arithmetic only, with the chip's 256 CUs as a constant: the workspace query must
 // not need a GPU.
 int key_splits(const usp_problem& p) {
@@ -256,7 +257,7 @@ int key_splits(const usp_problem& p) {
   const int64_t items = ((Lq + 255) / 256) * (p.hc / p.ulysses) * p.bs;
   const double ratio = 256.0 / ((double)items * (p.causal ? 0.5 : 1.0));
   if (ratio < 1.5) return 0;
-  const int64_t parts_wanted = ratio >= 3.5 ? 3 : 2;
+  const int64_t parts_wanted = ratio >= 7.0 ? 4 : ratio >= 3.5 ? 3 : 2;
   int64_t s = (parts_wanted + p.ring - 1) / p.ring;
   s = std::min<int64_t>(s, Lq / 1024);
   s = std::min<int64_t>(s, USP_MAX_RING_BLOCKS / p.ring);

@@ -184,7 +184,7 @@ def test_usp_fwd_causal_gqa_all_factorisations(usp, U, R, zigzag):
     # short sequences, few work items: the K/V blocks are cut into pieces that run as work items of their own
     ("key_split_3_pieces_across_zigzag_runs", 1, 6144, 4, 2, 128, 1, 2, True),   # Lq 3072: pieces of 1024, runs of 1536
     ("key_split_3_pieces_noncausal", 1, 4096, 8, 4, 128, 2, 1, False),
-    ("key_split_3_pieces_batch_of_two", 2, 4096, 4, 2, 128, 2, 1, True),
+    ("key_split_4_pieces_batch_of_two", 2, 4096, 4, 2, 128, 2, 1, True),   # ratio 8: four pieces of 1024 keys
     ("key_split_head_size_64", 1, 2048, 4, 2, 64, 2, 1, True),
 ])
 def test_usp_fwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
