@@ -286,7 +286,7 @@ def main():
         n_plain, n_ds = usp.usp_attn_bwd_workspace_bytes(p, 1), usp.usp_attn_bwd_workspace_bytes_with_ds(p, 1)
         # the larger workspace lets the dK/dV kernel keep dS for the dQ kernel (5 products per tile pair instead of
         # 7): timed as well when it fits in a quarter of the free memory
-        with_ds = n_ds <= torch.cuda.mem_get_info()[0] // 4
+        with_ds = n_plain < n_ds <= torch.cuda.mem_get_info()[0] // 4   # equal sizes: dS is not kept at this head size
         ws_b = torch.empty(n_ds if with_ds else n_plain, dtype=torch.uint8, device="cuda")
 
         def bwd(nbytes=n_plain):

@@ -245,7 +245,8 @@ int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void*
  * (L/R)^2 * 2, keys and queries rounded up to 256) lets the dK/dV kernel keep the dS it forms, as bf16, and
  * the dQ kernel read it back instead of forming S and dP a second time: 5 matrix products per tile pair instead
  * of 7.  Same results up to the bf16 rounding of dS, which both kernels apply anyway.  Chosen by workspace_bytes
- * alone; any size from usp_attn_bwd_workspace_bytes() up is accepted. */
+ * alone; any size from usp_attn_bwd_workspace_bytes() up is accepted.  Head size 128 only: at head size 64 the second
+ * pair of products costs less than moving dS, the _with_ds query returns the plain size and more room is ignored. */
 size_t usp_attn_bwd_workspace_bytes(const usp_problem* p, int n_ranks);
 size_t usp_attn_bwd_workspace_bytes_with_ds(const usp_problem* p, int n_ranks);
 int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, const void* v, const void* o,

@@ -527,7 +527,9 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   f.dv_acc = off; off += f.kv_acc_bytes * blocks;
   f.total = off;
   f.ds = off;
-  f.ds_bytes = up256(bwd_ds_bytes(p.bs, (int64_t)Lq, (int64_t)Lq, (int)hq, std::min(p.ring, USP_MAX_RING_BLOCKS)));
+  // dS is kept only at head size 128: at 64 forming S and dP a second time costs less than moving 4 bytes per pair
+  // (measured: 2.32 ms recomputed against 2.46 ms with dS kept on the Ulysses-8 rank of L = 32768)
+  f.ds_bytes = bwd_keeps_ds(p.hs) ? up256(bwd_ds_bytes(p.bs, (int64_t)Lq, (int64_t)Lq, (int)hq, std::min(p.ring, USP_MAX_RING_BLOCKS))) : 0;
   f.total_with_ds = off + f.ds_bytes;
   return f;
 }
@@ -563,7 +565,7 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
   if ((uintptr_t)workspace & 255) return USP_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   char* ws = (char*)workspace;
-  if (workspace_bytes >= f.total_with_ds) f.copies.ds = ws + f.ds;   // room to keep dS between the two kernels
+  if (f.ds_bytes && workspace_bytes >= f.total_with_ds) f.copies.ds = ws + f.ds;   // room to keep dS between the two kernels
   const int64_t Lq = p->L / R;
   const int hq = p->hc / U, hkv = p->hk / U;
   const float scale = p->scale == 0.0f ? 1.0f / sqrtf((float)p->hs) : p->scale;
@@ -701,7 +703,7 @@ RingBwdWs plan_ring_bwd_ws(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int 
   w.dq_bytes = w.copies.cut.k_splits > 1 ? up256(w.copies.dq_stride * sizeof(float) * w.copies.cut.k_splits) : 0;
   w.kv_bytes_per_block = w.dkdv_copies > 1 ? up256(w.copies.dkdv_stride * sizeof(float) * w.dkdv_copies) : 0;
   w.total = w.dq_bytes + 2 * w.kv_bytes_per_block * n_blocks;
-  w.ds_bytes = up256(bwd_ds_bytes(bs, Lq, Lk, hq, n_blocks));
+  w.ds_bytes = bwd_keeps_ds(hs) ? up256(bwd_ds_bytes(bs, Lq, Lk, hq, n_blocks)) : 0;
   w.total_with_ds = w.total + w.ds_bytes;
   return w;
 }
@@ -738,7 +740,7 @@ extern "C" int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, 
   if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
   RingBwdWs w = plan_ring_bwd_ws(bs, Lq, Lk, hq, hkv, hs, n_blocks);
   if (w.total > 0 && (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255))) return USP_ERR_WORKSPACE;
-  if (workspace && workspace_bytes >= w.total_with_ds && !((uintptr_t)workspace & 255))
+  if (w.ds_bytes && workspace && workspace_bytes >= w.total_with_ds && !((uintptr_t)workspace & 255))
     w.copies.ds = (char*)workspace + w.total;   // room to keep dS between the two kernels
   usp_posdesc qd = {0, Lq, 0, 0};
   usp_posdesc kd[USP_MAX_RING_BLOCKS];

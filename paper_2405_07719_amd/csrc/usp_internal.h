@@ -103,6 +103,7 @@ BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_block
 // first and writes the dS blocks it forms, and the dQ kernel reads them back instead of forming S and dP again
 // (5 matrix products per tile pair instead of 7, for 2 bytes written and read per visible pair).
 struct BwdCopies { BwdCut cut; size_t dq_stride, dkdv_stride; void* ds = nullptr; };
+inline bool bwd_keeps_ds(int hs) { return hs >= 128; }   // see plan_bwd
 inline size_t bwd_ds_bytes(int bs, int64_t Lq, int64_t Lk, int hq, int n_blocks) {
   return (size_t)bs * hq * n_blocks * (size_t)((Lk + 255) / 256 * 8) * (size_t)((Lq + 255) / 256 * 8) * 2048;
 }

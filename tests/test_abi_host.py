@@ -107,3 +107,8 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     plain = usp.usp_ring_attn_bwd_workspace_bytes(2, 333, 700, 4, 2, 128, 3)
     assert usp.usp_ring_attn_bwd_workspace_bytes_with_ds(2, 333, 700, 4, 2, 128, 3) - plain == 2 * 4 * 3 * 512 * 768 * 2
     assert usp.usp_ring_attn_bwd_workspace_bytes_with_ds(2, 333, 700, 4, 3, 128, 3) == 0     # heads do not divide
+    # head size 64: forming S and dP a second time is cheaper than moving dS, no room is asked for
+    p64 = usp.problem(1, 32768, 32, 8, 64, 8, 1, True)
+    assert usp.usp_attn_bwd_workspace_bytes_with_ds(p64, 1) == usp.usp_attn_bwd_workspace_bytes(p64, 1) > 0
+    assert (usp.usp_ring_attn_bwd_workspace_bytes_with_ds(2, 333, 700, 4, 2, 64, 3)
+            == usp.usp_ring_attn_bwd_workspace_bytes(2, 333, 700, 4, 2, 64, 3))

@@ -324,7 +324,7 @@ def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R, 
     assert (nbytes == 0) == (hq == hkv)
     if keep_ds:
         n_ds = usp.usp_ring_attn_bwd_workspace_bytes_with_ds(bs, Lq, Lq, hq, hkv, hs, R)
-        assert n_ds >= nbytes + bs * hq * R * Lq * Lq * 2
+        assert n_ds >= nbytes + bs * hq * R * Lq * Lq * 2 if hs >= 128 else n_ds == nbytes   # head size 128 only
         nbytes = n_ds
     ws = torch.full((max(nbytes, 256),), 0xFF, dtype=torch.uint8, device="cuda")
     runs = []
