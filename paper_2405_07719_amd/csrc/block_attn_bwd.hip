@@ -107,6 +107,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 // instruction of the writer fills whole 128-byte lines.  In the reader's LDS the second half sits 1152 bytes after
 // the first (an odd multiple of 128: the two 16-lane groups of a transpose read then hit different banks).
 constexpr int kDsHalfLds = 1152, kDsBlockLds = kDsHalfLds + 1024;
+// Cache policy of the dS stores: non-temporal (bit 1 of the buffer instructions' policy operand).  Nothing reads the
+// blocks before the next kernel, and kept as ordinary dirty lines they push the Q / dO rows out of the L2s.  (With
+// whole lines per store instruction this is 2-3 % faster over the kernel pair than the default policy; when a
+// store instruction filled half lines it was 10 % slower.)
+constexpr int kDsStoreAux = 2;
 
 // transpose-read address of this lane inside a [rows][VSTR] tile: see the forward kernel
 template <int VSTR>
@@ -822,7 +827,7 @@ void bwd_dkdv_kernel(const BwdArgs) {
           // next instructions from overwriting them only in this form.  (With the block's offset in a scalar
           // register, the data registers were reused at once and some blocks came out holding the next step's
           // values, now and then: measured, the results differed from run to run.)
-          __builtin_amdgcn_raw_buffer_store_b128(u32x4{e[0], o[0], e[1], o[1]}, ds_blk, ds_lane_off + 1024 * st, 0, 0);
+          __builtin_amdgcn_raw_buffer_store_b128(u32x4{e[0], o[0], e[1], o[1]}, ds_blk, ds_lane_off + 1024 * st, 0, kDsStoreAux);
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
