@@ -486,7 +486,8 @@ void bwd_dq_ds_kernel(const BwdArgs) {
       if (seen) {
         const char* blk0 = dsg + (size_t)(NB * tile_of(it)) * ds_kt_stride + lane * 16;
 #pragma unroll
-        for (int j = 0; j < 2 * NB; ++j) dreg[j] = *(const u32x4*)(blk0 + (j >> 1) * ds_kt_stride + (j & 1) * 1024);
+        for (int j = 0; j < 2 * NB; ++j)   // read once: streamed past the caches
+          dreg[j] = __builtin_nontemporal_load((const u32x4*)(blk0 + (j >> 1) * ds_kt_stride + (j & 1) * 1024));
       }
     };
     char* const ds_s = ds_all + wave * (NB * kDsBlockLds);
