@@ -26,7 +26,9 @@ What each function follows in the paper (arxiv 2405.07719):
 Pins (tests/test_oracle_pins.py): brute-force loops on tiny inputs, closed forms
 (Q = 0, constant V, single key), softmax normalisation, an independent library
 routine on the un-masked/causal special cases, central finite differences for
-the backward, the paper's worked zigzag example (Sec. 3: 16 tokens, 4 GPUs, GPU0
+the backward (also with scrambled explicit positions: scalar-loop gradient, central
+differences of block_attention, a rank's rows = its share of the full gradient),
+the paper's worked zigzag example (Sec. 3: 16 tokens, 4 GPUs, GPU0
 holds tokens 0,1,14,15), the balanced pair count, the 7x imbalance of the even
 split on 4 GPUs, and reshape/transpose second opinions for the layout maps.
 Nothing here is "parity unpinned".

@@ -222,6 +222,111 @@ def test_backward_against_torch_autograd():
     np.testing.assert_allclose(dv, tv.grad.numpy(), atol=1e-12)
 
 
+def brute_backward(q, k, v, d_o, qpos, kpos, causal, scale):
+    """Gradient of sum(O * dO) for Eq. 1 by scalar loops: weights w_ij from math.exp over the visible keys,
+    dV_j += w_ij dO_i, dS_ij = w_ij (dO_i.V_j - sum_j' w_ij' dO_i.V_j'), dQ_i += scale dS_ij K_j, dK_j += scale dS_ij Q_i."""
+    bs, nq, hq, hs = q.shape
+    nk, hkv = k.shape[1], k.shape[2]
+    g = hq // hkv
+    dq, dk, dv = np.zeros(q.shape), np.zeros(k.shape), np.zeros(v.shape)
+    for b in range(bs):
+        for h in range(hq):
+            kv = h // g
+            for i in range(nq):
+                js = [j for j in range(nk) if not causal or kpos[j] <= qpos[i]]
+                if not js:
+                    continue
+                sc = [scale * sum(q[b, i, h, e] * k[b, j, kv, e] for e in range(hs)) for j in js]
+                mx = max(sc)
+                den = sum(math.exp(s - mx) for s in sc)
+                w = [math.exp(s - mx) / den for s in sc]
+                dp = [sum(d_o[b, i, h, e] * v[b, j, kv, e] for e in range(hs)) for j in js]
+                dbar = sum(wi * di for wi, di in zip(w, dp))
+                for wi, di, j in zip(w, dp, js):
+                    ds = wi * (di - dbar)
+                    for e in range(hs):
+                        dv[b, j, kv, e] += wi * d_o[b, i, h, e]
+                        dq[b, i, h, e] += scale * ds * k[b, j, kv, e]
+                        dk[b, j, kv, e] += scale * ds * q[b, i, h, e]
+    return dq, dk, dv
+
+
+# scrambled, non-contiguous positions: the query at position 0 sees no key (smallest key position is 1), positions
+# repeat (4, 4) and the orders of queries and keys differ, so a backward that ignores or swaps qpos / kpos fails
+_QPOS = np.array([9, 0, 4, 4, 15, 2, 7])
+_KPOS = np.array([3, 12, 4, 7, 1, 8])
+
+
+def _scrambled_case(hq=4, hkv=2, hs=3):
+    rng = np.random.default_rng(23)
+    q = rng.standard_normal((2, _QPOS.size, hq, hs))
+    k = rng.standard_normal((2, _KPOS.size, hkv, hs))
+    v = rng.standard_normal((2, _KPOS.size, hkv, hs))
+    d_o = rng.standard_normal((2, _QPOS.size, hq, hs))
+    return q, k, v, d_o
+
+
+def test_backward_with_positions_matches_brute_force():
+    q, k, v, d_o = _scrambled_case()
+    dq, dk, dv = orc.attention_backward(q, k, v, d_o, True, scale=0.45, qpos=_QPOS, kpos=_KPOS)
+    bq, bk, bv = brute_backward(q, k, v, d_o, _QPOS, _KPOS, True, 0.45)
+    np.testing.assert_allclose(dq, bq, atol=1e-13)
+    np.testing.assert_allclose(dk, bk, atol=1e-13)
+    np.testing.assert_allclose(dv, bv, atol=1e-13)
+    assert np.all(dq[:, 1] == 0.0)                       # the row that sees no key has a zero gradient
+    # and the positions matter at all: default positions give something else
+    dq0, dk0, dv0 = orc.attention_backward(q, k, v, d_o, True, scale=0.45)
+    assert np.abs(dq0 - dq).max() > 1e-3 and np.abs(dk0 - dk).max() > 1e-3 and np.abs(dv0 - dv).max() > 1e-3
+
+
+def test_backward_with_positions_matches_central_differences_of_block_attention():
+    q, k, v, d_o = _scrambled_case(hq=2, hkv=1, hs=2)
+
+    def loss():
+        o, _ = orc.block_attention(q, k, v, _QPOS, _KPOS, True, scale=0.7)
+        return float((o * d_o).sum())
+
+    dq, dk, dv = orc.attention_backward(q, k, v, d_o, True, scale=0.7, qpos=_QPOS, kpos=_KPOS)
+    eps = 1e-6
+    for name, x, g in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        num = np.zeros_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = x[idx]
+            x[idx] = old + eps
+            lp = loss()
+            x[idx] = old - eps
+            lm = loss()
+            x[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        np.testing.assert_allclose(g, num, rtol=1e-6, atol=1e-8, err_msg=name)
+
+
+@pytest.mark.parametrize("ring,ulysses", [(2, 2), (4, 1), (1, 4)])
+def test_backward_of_a_rank_rows_is_its_share_of_the_full_gradient(ring, ulysses):
+    # P and D are row quantities, so the gradient restricted to the query rows of one Algorithm-2 shard is that
+    # rank's dQ and its contribution to dK / dV; the contributions of all ranks add up to the full gradient
+    bs, L, hc, hk, hs = 1, 32, 4, 2, 4
+    rng = np.random.default_rng(31)
+    q = rng.standard_normal((bs, L, hc, hs))
+    k = rng.standard_normal((bs, L, hk, hs))
+    v = rng.standard_normal((bs, L, hk, hs))
+    d_o = rng.standard_normal((bs, L, hc, hs))
+    fq, fk, fv = orc.attention_backward(q, k, v, d_o, True)
+    sk, sv = np.zeros_like(k), np.zeros_like(v)
+    kperm = rng.permutation(L)                           # keys handed over in another order than their positions
+    for r in range(ring):
+        for u in range(ulysses):
+            rows = orc.zigzag_positions(L, ring, ulysses, r, u)
+            dq, dk, dv = orc.attention_backward(q[:, rows], k[:, kperm], v[:, kperm], d_o[:, rows], True, qpos=rows, kpos=kperm)
+            np.testing.assert_allclose(dq, fq[:, rows], atol=1e-13)
+            sk[:, kperm] += dk
+            sv[:, kperm] += dv
+    np.testing.assert_allclose(sk, fk, atol=1e-12)
+    np.testing.assert_allclose(sv, fv, atol=1e-12)
+
+
 # ------------------------------------------------------------------ Algorithm 2
 def _golden_rows():
     rows = []
