@@ -234,9 +234,10 @@ int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void*
  * would travel the ring with the block) -> all-to-all of dQ.  After the last rank the dK/dV accumulators
  * are converted and all-to-all'ed back.
  * dq is complete for the ranks in range (each fills its head slice of its Ulysses group's shards).
- * dk/dv: for every ring row and every Ulysses column touched by the range, the column's head slice is
- * OVERWRITTEN with the sum of the contributions of the ranks in range; complete dk/dv therefore needs
- * rank_begin = 0, rank_end = N (or all R ring rows of one column for that column's head slice).
+ * dk/dv: for every Ulysses column u that has a rank (r,u) in range, the column's head slice of ALL N shards is
+ * OVERWRITTEN with the sum of the contributions of the column's ranks in range; the head slices of columns
+ * without a rank in range are not written.  Complete dk/dv therefore needs rank_begin = 0, rank_end = N (or
+ * all R ring rows of one column for that column's head slice).
  * The fp32 accumulators may be held in several copies (one per slice of the work that a short or narrow problem is
  * cut into, each written with plain stores and added up by the conversion pass; the workspace query knows): the
  * results do not depend on the order in which workgroups finish.

@@ -13,6 +13,8 @@ What each function follows in the paper (arxiv 2405.07719):
   (Sec. 3, the GQA/MQA paragraph).  LSE is the natural log of the softmax
   denominator (the paper never defines it; this is the usual definition).
 * attention_backward -- the textbook gradient of Eq. 1 (the paper gives none).
+* attention_backward_columns -- the same gradient for selected key columns only, from
+  rows whose log-sum-exp and delta are given (for problems too large for the above).
 * zigzag_positions -- Sec. 3, Algorithm 2: split the sequence into 2R chunks, ring
   rank r keeps chunks r and 2R-1-r, Ulysses rank u keeps the u-th of U equal pieces.
 * a2a_seq_to_head / a2a_head_to_seq -- Sec. 3, Algorithm 1 steps 2-4 and 6
@@ -154,6 +156,44 @@ def attention_backward(q, k, v, d_o, causal, scale=None, qpos=None, kpos=None):
             dk[b, :, h // g, :] += scale * (ds.T @ qh)
             dv[b, :, h // g, :] += p.T @ doh
     return dq, dk, dv
+
+
+def attention_backward_columns(q, d_o, lse, delta, qpos, k_cols, v_cols, col_pos, causal, scale=None):
+    """dK, dV of SELECTED key columns from the given query rows (textbook gradient of Eq. 1, column by column).
+
+    For problems too large for attention_backward: the softmax of a row is fixed by its log-sum-exp over ALL its
+    visible keys, so with lse [bs, hq, nq] (from block_attention over every key) and delta_i = sum_e dO_ie O_ie
+    [bs, hq, nq] the weight of one (row, key) pair needs nothing else:
+      P_ij = exp(scale q_i.k_j - lse_i) if key j is visible to row i, else 0
+      dV_j = sum_i P_ij dO_i;   dS_ij = P_ij (dO_i.v_j - delta_i);   dK_j = scale sum_i dS_ij q_i
+    summed over the query heads of the KV head's group.  q, d_o [bs, nq, hq, hs] at positions qpos; k_cols, v_cols
+    [bs, nc, hkv, hs] at positions col_pos.  Returns dk, dv [bs, nc, hkv, hs]: the given rows' contribution.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    d_o = np.asarray(d_o, dtype=np.float64)
+    k_cols = np.asarray(k_cols, dtype=np.float64)
+    v_cols = np.asarray(v_cols, dtype=np.float64)
+    lse = np.asarray(lse, dtype=np.float64)
+    delta = np.asarray(delta, dtype=np.float64)
+    bs, nq, hq, hs = q.shape
+    hkv = k_cols.shape[2]
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(hs)
+    vis = _visible(np.asarray(qpos, dtype=np.int64), np.asarray(col_pos, dtype=np.int64), causal)
+    dk = np.zeros_like(k_cols)
+    dv = np.zeros_like(v_cols)
+    for b in range(bs):
+        for h in range(hq):
+            kh, vh = k_cols[b, :, h // g, :], v_cols[b, :, h // g, :]
+            qh, doh = q[b, :, h, :], d_o[b, :, h, :]
+            live = np.isfinite(lse[b, h])                               # rows that see no key at all have P = 0
+            with np.errstate(invalid="ignore"):
+                p = np.where(vis & live[:, None], np.exp((qh @ kh.T) * scale - np.where(live, lse[b, h], 0.0)[:, None]), 0.0)
+            ds = p * (doh @ vh.T - delta[b, h][:, None])
+            dk[b, :, h // g, :] += scale * (ds.T @ qh)
+            dv[b, :, h // g, :] += p.T @ doh
+    return dk, dv
 
 
 # --------------------------------------------------------------------------- #

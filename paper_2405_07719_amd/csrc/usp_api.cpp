@@ -629,11 +629,14 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
     if (st != USP_OK) return st;
   }
 
-  // dK, dV of every block the range touched (all ring rows of the columns in range)
+  // dK, dV of every block the range touched: all ring rows of the columns whose ranks were run.  A range that
+  // straddles ring rows without covering every column (say [U-1, U+1)) leaves columns between c0 and c1 unvisited:
+  // their accumulators were never written, and their head slices of dk / dv stay as the caller left them.
   for (int r = 0; r < R; ++r)
     for (int u = c0; u < c1; ++u) {
       const int rank = r * U + u;
       const size_t sl = slot(r, u);
+      if (!touched[sl]) continue;
       char* kdst = ws + f.k_head + sl * f.kv_block_bytes;
       char* vdst = ws + f.v_head + sl * f.kv_block_bytes;
       st = launch_bwd_convert2((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), kdst,

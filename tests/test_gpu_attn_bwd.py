@@ -190,6 +190,53 @@ def test_usp_bwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal, 
             assert tl.max_abs(g[rank], r[:, prob.rank_positions(rank)]) <= GRAD_TOL, (name_, rank)
 
 
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
+def test_usp_bwd_rank_range_straddling_ring_rows(usp, keep_ds):
+    """Ranks [U-1, U+1) = (ring row 0, column U-1) and (ring row 1, column 0): the columns in between are not
+    visited.  The visited columns' head slices of dk / dv hold the two ranks' contributions (the oracle's gradient
+    restricted to each rank's query rows and heads); every other head slice of dq / dk / dv is left untouched."""
+    bs, L, hc, hk, hs, U, R = 1, 1024, 8, 4, 128, 4, 2
+    prob = tl.Problem(97, bs, L, hc, hk, hs, U, R, True, True, tl.BF16, with_do=True)
+    p = usp.problem(bs, L, hc, hk, hs, U, R, True, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
+    q, k, v, d_o = (prob.seq_layout_dev(n) for n in ("q", "k", "v", "do"))
+    o = torch.empty_like(q)
+    lse = torch.empty((prob.N, bs, hc // U, L // R), dtype=torch.float32, device="cuda")
+    ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
+    usp.usp_attn_fwd(p, q, k, v, o, lse, 0, prob.N, ws)
+    ws2 = _bwd_workspace(usp, p, 2, keep_ds)
+    SENT = 777.0                                          # exactly representable in bf16
+    dq = torch.full(q.shape, SENT, dtype=torch.bfloat16, device="cuda")
+    dk = torch.full(k.shape, SENT, dtype=torch.bfloat16, device="cuda")
+    dv = torch.full(v.shape, SENT, dtype=torch.bfloat16, device="cuda")
+    usp.usp_attn_bwd(p, q, k, v, o, lse, d_o, dq, dk, dv, U - 1, U + 1, ws2)
+    torch.cuda.synchronize()
+    gq, gk, gv = tl.to_f64(dq), tl.to_f64(dk), tl.to_f64(dv)        # [N][bs][L/N][heads][hs]
+    hq, hkv = hc // U, hk // U
+    allpos = np.arange(L)
+    seen_q = np.zeros(gq.shape, dtype=bool)
+    seen_kv = np.zeros(gk.shape, dtype=bool)
+    for rank in (U - 1, U):
+        r, u = divmod(rank, U)
+        rows = orc.ring_block_positions(L, R, r)
+        qh, kh = slice(u * hq, (u + 1) * hq), slice(u * hkv, (u + 1) * hkv)
+        rq, rk, rv = orc.attention_backward(prob.val["q"][:, rows, qh], prob.val["k"][:, :, kh], prob.val["v"][:, :, kh],
+                                            prob.val["do"][:, rows, qh], True, None, rows, allpos)
+        full_q = np.zeros((bs, L, hq, hs))
+        full_q[:, rows] = rq
+        for shard in range(prob.N):
+            pos = prob.rank_positions(shard)
+            if shard // U == r:                           # dQ goes to the shards of the rank's own ring row
+                assert tl.max_abs(gq[shard][:, :, qh], full_q[:, pos]) <= GRAD_TOL, ("dq", rank, shard)
+                seen_q[shard][:, :, qh] = True
+            assert tl.max_abs(gk[shard][:, :, kh], rk[:, pos]) <= GRAD_TOL, ("dk", rank, shard)
+            assert tl.max_abs(gv[shard][:, :, kh], rv[:, pos]) <= GRAD_TOL, ("dv", rank, shard)
+            seen_kv[shard][:, :, kh] = True
+    assert (~seen_q).any() and (~seen_kv).any()
+    assert np.all(gq[~seen_q] == SENT), "dq written outside the head slices of the ranks in range"
+    assert np.all(gk[~seen_kv] == SENT), "dk written for a column no rank in range visited"
+    assert np.all(gv[~seen_kv] == SENT), "dv written for a column no rank in range visited"
+
+
 def test_usp_bwd_rejects_bad_arguments(usp):
     p32 = usp.problem(1, 256, 4, 4, 64, 2, 2, False, dtype=usp.USP_FP32)
     assert usp.usp_attn_bwd_workspace_bytes(p32, 1) == 0          # bf16 only

@@ -327,6 +327,31 @@ def test_backward_of_a_rank_rows_is_its_share_of_the_full_gradient(ring, ulysses
     np.testing.assert_allclose(sv, fv, atol=1e-12)
 
 
+def test_backward_columns_match_brute_force_and_the_full_gradient():
+    # selected key columns, from a subset of the query rows, with scrambled positions and a row that sees nothing
+    q, k, v, d_o = _scrambled_case()
+    o, lse = orc.block_attention(q, k, v, _QPOS, _KPOS, True, scale=0.45)
+    delta = np.einsum("bihe,bihe->bhi", d_o, o)
+    cols = np.array([4, 0, 3])
+    dk, dv = orc.attention_backward_columns(q, d_o, lse, delta, _QPOS, k[:, cols], v[:, cols], _KPOS[cols], True, scale=0.45)
+    _, bk, bv = brute_backward(q, k, v, d_o, _QPOS, _KPOS, True, 0.45)
+    np.testing.assert_allclose(dk, bk[:, cols], atol=1e-13)
+    np.testing.assert_allclose(dv, bv[:, cols], atol=1e-13)
+    # a subset of the rows gives that subset's contribution: the two halves add up to the whole
+    a, b = np.array([0, 2, 5]), np.array([1, 3, 4, 6])
+    parts = [orc.attention_backward_columns(q[:, r], d_o[:, r], lse[:, :, r], delta[:, :, r], _QPOS[r], k[:, cols], v[:, cols],
+                                            _KPOS[cols], True, scale=0.45) for r in (a, b)]
+    np.testing.assert_allclose(parts[0][0] + parts[1][0], bk[:, cols], atol=1e-13)
+    np.testing.assert_allclose(parts[0][1] + parts[1][1], bv[:, cols], atol=1e-13)
+    # not causal: every column sees every row
+    o2, lse2 = orc.block_attention(q, k, v, _QPOS, _KPOS, False, scale=0.45)
+    delta2 = np.einsum("bihe,bihe->bhi", d_o, o2)
+    dk2, dv2 = orc.attention_backward_columns(q, d_o, lse2, delta2, _QPOS, k[:, cols], v[:, cols], _KPOS[cols], False, scale=0.45)
+    _, fk, fv = brute_backward(q, k, v, d_o, _QPOS, _KPOS, False, 0.45)
+    np.testing.assert_allclose(dk2, fk[:, cols], atol=1e-13)
+    np.testing.assert_allclose(dv2, fv[:, cols], atol=1e-13)
+
+
 # ------------------------------------------------------------------ Algorithm 2
 def _golden_rows():
     rows = []
