@@ -86,8 +86,7 @@ def load():
     lib.usp_attn_bwd_workspace_bytes_with_ds.restype = C.c_size_t
     lib.usp_attn_bwd_workspace_bytes_with_ds.argtypes = [P(usp_problem), I]
     lib.usp_attn_bwd.argtypes = [P(usp_problem), V, V, V, V, V, V, V, V, V, I, I, V, C.c_size_t, V]
-    lib.usp_calib_mfma.argtypes = [I, I, V, C.c_size_t, P(C.c_double), V]
-    for name in ("usp_ring_attn_bwd", "usp_ring_attn_fwd", "usp_calib_mfma", "usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
+    for name in ("usp_ring_attn_bwd", "usp_ring_attn_fwd", "usp_validate", "usp_local_positions", "usp_layout_a2a", "usp_block_attn_fwd", "usp_lse_merge",
                  "usp_attn_fwd", "usp_attn_bwd", "usp_attn_delta", "usp_block_attn_bwd"):
         getattr(lib, name).restype = I
     _lib = lib
@@ -203,17 +202,6 @@ def usp_block_attn_bwd(q, k, v, d_o, lse, delta, dq, dk, dv, bs, Lq, Lk, hq, hkv
                                      C.byref(qpos) if qpos is not None else None,
                                      C.byref(kpos) if kpos is not None else None, int(bool(accumulate)),
                                      _stream(stream)), "usp_block_attn_bwd")
-
-
-USP_CALIB_SINK_BYTES = 256 * 512 * 4
-
-
-def usp_calib_mfma(mode, iters, sink, stream=None):
-    """Enqueue one calibration launch (0 pure MFMA, 1 attention mix); returns its MFMA flop count."""
-    flop = C.c_double(0.0)
-    _check(load().usp_calib_mfma(mode, iters, _ptr(sink), sink.numel() * sink.element_size(), C.byref(flop),
-                                 _stream(stream)), "usp_calib_mfma")
-    return flop.value
 
 
 def usp_ring_attn_bwd(q, k_blocks, v_blocks, kpos_blocks, d_o, lse, delta, dq, dk_blocks, dv_blocks, bs, Lq, Lk, hq, hkv,

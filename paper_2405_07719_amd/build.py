@@ -9,7 +9,10 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libusp.so")
-SOURCES = ["usp_api.cpp", "layout_a2a.hip", "lse_merge.hip", "block_attn_fwd.hip", "block_attn_bwd.hip", "calib_mfma.hip"]
+SOURCES = ["usp_api.cpp", "layout_a2a.hip", "lse_merge.hip", "block_attn_fwd.hip", "block_attn_bwd.hip"]
+# measurement aid for bench.py only (matrix-core calibration loops): a library of its own, not part of the product
+CALIB_LIB = os.path.join(PKG, "libusp_calib.so")
+CALIB_SOURCES = ["calib_mfma.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
@@ -20,10 +23,10 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra=()) -> str:
+def _compile(sources, lib, verbose, extra) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc, *FLAGS, *extra, "-x", "hip", *srcs, "-o", LIB]
+    srcs = [os.path.join(CSRC, s) for s in sources]
+    cmd = [hipcc, *FLAGS, *extra, "-x", "hip", *srcs, "-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -32,7 +35,12 @@ def build(verbose: bool = True, extra=()) -> str:
         print(out)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
-    return LIB
+    return lib
+
+
+def build(verbose: bool = True, extra=()) -> str:
+    _compile(CALIB_SOURCES, CALIB_LIB, verbose, extra)
+    return _compile(SOURCES, LIB, verbose, extra)
 
 
 if __name__ == "__main__":

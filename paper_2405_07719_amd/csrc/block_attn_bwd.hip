@@ -224,7 +224,7 @@ void bwd_dq_kernel(const BwdArgs) {
     const int group = w % n_groups; w /= n_groups;
     const int hg = w % a.g; w /= a.g;
     const int k_splits = ap->k_splits;
-    const int ks = w % k_splits;             // this item's slice of the visible key tiles of every block
+    const int kslice = w % k_splits;             // this item's slice of the visible key tiles of every block
     const int t = w / k_splits;
     const int qtile = a.causal ? a.n_tiles - 1 - t : t;
     const int b = group / a.hkv, kvh = group % a.hkv;
@@ -302,7 +302,7 @@ void bwd_dq_kernel(const BwdArgs) {
     tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, a.Lk, tile_row0, tile_row1);
     na = tr.a1 - tr.a0;
     nt = na + (tr.b1 - tr.b0);
-    const int it0 = (int)((int64_t)nt * ks / k_splits), it1 = (int)((int64_t)nt * (ks + 1) / k_splits);
+    const int it0 = (int)((int64_t)nt * kslice / k_splits), it1 = (int)((int64_t)nt * (kslice + 1) / k_splits);
     if (it1 == it0) continue;                // workgroup-uniform
     kg = (const char*)ap->k[blk] + kv_head_off;
     vg = (const char*)ap->v[blk] + kv_head_off;
@@ -364,7 +364,7 @@ void bwd_dq_kernel(const BwdArgs) {
     unsigned own_ticket = kNoDraw;
     if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
     if (qrow < a.Lq) {
-      float* dst = a.dq + (size_t)ks * ap->dq_part_stride + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
+      float* dst = a.dq + (size_t)kslice * ap->dq_part_stride + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -441,7 +441,7 @@ void bwd_dq_ds_kernel(const BwdArgs) {
     const int group = w % n_groups; w /= n_groups;
     const int hg = w % g; w /= g;
     const int k_splits = ap->k_splits;
-    const int ks = w % k_splits;
+    const int kslice = w % k_splits;
     const int t = w / k_splits;
     const int qtile = causal ? ap->n_tiles - 1 - t : t;
     const int b = group / hkv, kvh = group % hkv;
@@ -509,7 +509,7 @@ void bwd_dq_ds_kernel(const BwdArgs) {
     tr = visible_key_tiles<KT>(causal, qpos, kpos, Lk, tile_row0, tile_row1);
     na = tr.a1 - tr.a0;
     const int nt = na + (tr.b1 - tr.b0);
-    const int it0 = (int)((int64_t)nt * ks / k_splits), it1 = (int)((int64_t)nt * (ks + 1) / k_splits);
+    const int it0 = (int)((int64_t)nt * kslice / k_splits), it1 = (int)((int64_t)nt * (kslice + 1) / k_splits);
     if (it1 == it0) continue;                // workgroup-uniform
     kg = (const char*)ap->k[blk] + kv_head_off;
     dsg = (const char*)ap->ds + (((((size_t)b * hq + h) * n_blocks + blk) * ap->ds_qt8 + qtile) * ap->ds_kt * 8 + wave) * 2048;
@@ -549,7 +549,7 @@ void bwd_dq_ds_kernel(const BwdArgs) {
     if (qrow < Lq) {
       const float scale = ap->scale;
       const int accumulate = ap->accumulate;
-      float* dst = ap->dq + (size_t)ks * ap->dq_part_stride + (((size_t)b * Lq + qrow) * hq + h) * HS + 4 * hl;
+      float* dst = ap->dq + (size_t)kslice * ap->dq_part_stride + (((size_t)b * Lq + qrow) * hq + h) * HS + 4 * hl;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -967,21 +967,21 @@ BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_block
   const int g = hq / hkv;
   const int64_t unsplit = ((Lk + 255) / 256) * hkv * bs * n_blocks;
   c.heads_per_wg = g;
-  if (unsplit < 2 * 256) {
+  if (unsplit < 2 * kPlanCUs) {
     c.heads_per_wg = 1;
     for (int h = g - 1; h > 1; --h)
-      if (g % h == 0 && unsplit * (g / h) >= 4 * 256) { c.heads_per_wg = h; break; }
+      if (g % h == 0 && unsplit * (g / h) >= 4 * kPlanCUs) { c.heads_per_wg = h; break; }
   }
   c.k_splits = c.q_splits = 1;
   if (cut_items) {
     const int64_t dq_items = ((Lq + 255) / 256) * hq * bs;
     const int64_t key_tiles = (int64_t)n_blocks * ((Lk + 31) / 32), query_tiles = (Lq + 31) / 32;
-    if (dq_items < 2 * 256)
-      c.k_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (2 * 256 + dq_items - 1) / dq_items, key_tiles / 32}));
+    if (dq_items < 2 * kPlanCUs)
+      c.k_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (2 * kPlanCUs + dq_items - 1) / dq_items, key_tiles / 32}));
     const int64_t dkdv_items = unsplit * (g / c.heads_per_wg);
-    if (dkdv_items < 2 * 256)
-      c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (2 * 256 + dkdv_items - 1) / dkdv_items, query_tiles / 16}));
-    else if (dkdv_items < 8 * 256 && c.heads_per_wg > 1)
+    if (dkdv_items < 2 * kPlanCUs)
+      c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (2 * kPlanCUs + dkdv_items - 1) / dkdv_items, query_tiles / 16}));
+    else if (dkdv_items < 8 * kPlanCUs && c.heads_per_wg > 1)
       c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>(2, query_tiles / 16));
   }
   return c;

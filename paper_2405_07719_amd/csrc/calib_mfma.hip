@@ -9,7 +9,9 @@
 //           two MFMAs ahead.  Pseudo-random operand bits: the matrix core's power draw, and with it the clock the
 //           chip sustains, depends on the data.
 // Both: 256 workgroups of 8 waves (two waves per SIMD), no global memory traffic inside the loop.
+// Built into its own library (libusp_calib.so) that only bench.py loads: not part of the product's ABI.
 #include "attn_device.h"
+#include "calib_mfma.h"
 #include "usp_internal.h"
 
 namespace usp {
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(kCalibThreads) void calib_attention_mix(float* sink
 
 }  // namespace
 
-int launch_calib_mfma(int mode, int iters, float* sink, double* flop, hipStream_t stream) {
+static int launch_calib_mfma(int mode, int iters, float* sink, double* flop, hipStream_t stream) {
   iters &= ~1;   // the attention mix runs two steps per loop trip
   // every wave issues 32 MFMAs of 2 * 32 * 32 * 16 flop per iteration in both modes
   *flop = (double)kCalibGroups * (kCalibThreads / 64) * (double)iters * 32.0 * 32768.0;
@@ -153,3 +155,12 @@ int launch_calib_mfma(int mode, int iters, float* sink, double* flop, hipStream_
 }
 
 }  // namespace usp
+
+extern "C" __attribute__((visibility("default"))) int usp_calib_mfma(int mode, int iters, void* sink,
+                                                                     size_t sink_bytes, double* flop, void* stream) {
+  if (!sink || !flop) return USP_ERR_NULL;
+  if (mode != 0 && mode != 1) return USP_ERR_UNSUPPORTED;
+  if (iters < 2 || iters > (1 << 24)) return USP_ERR_SHAPE;
+  if (sink_bytes < USP_CALIB_SINK_BYTES) return USP_ERR_WORKSPACE;
+  return usp::launch_calib_mfma(mode, iters, (float*)sink, flop, (hipStream_t)stream);
+}

@@ -211,7 +211,8 @@ extern "C" int usp_lse_merge(const void* const* o_parts, const float* const* lse
 // Algorithm 1 forward.  Workspace plan (all sizes rounded up to 256 B):
 //   kv_head : K and V in head layout for every (ring row, Ulysses column in range): the ring loop of
 //             a rank reads block s = (r - i) mod R of its own column u;
-//   q_head, o_head : one rank's Q / O in head layout (reused rank after rank, stream-ordered);
+//   q_head, o_head : one rank's Q / O in head layout (reused rank after rank, stream-ordered); only on the
+//             step-by-step path (the one-launch ring loop reads and writes the sequence-layout shards itself);
 //   parts   : R partial O (fp32) + R partial LSE when R > 1.
 // ---------------------------------------------------------------------------------------------
 namespace {
@@ -249,13 +250,13 @@ bool ring_in_one_launch(const usp_problem& p) { return p.dtype == USP_BF16 && p.
 // more in partial results (fp32, written and merged) than they gain, and with one or two items per CU the finish time
 // is a bin-packing matter (measured at L = 8192 and 16384: 2 and 3 pieces 1.4-1.8 x faster than none, 4 and more slower
 // again; at L = 4096: 76 / 64 / 58 us with 2 / 3 / 4).  Pieces hold at least 1024 keys, and a launch takes no more parts in
-// all than it takes blocks.  Host arithmetic only, with the chip's 256 CUs as a constant: the workspace query must
-// not need a GPU.
+// all than it takes blocks.  Host arithmetic only, with the chip's CU count as a constant (kPlanCUs): the workspace
+// query must not need a GPU.
 int key_splits(const usp_problem& p) {
   if (!ring_in_one_launch(p)) return 0;
   const int64_t Lq = p.L / p.ring;
   const int64_t items = ((Lq + 255) / 256) * (p.hc / p.ulysses) * p.bs;
-  const double ratio = 256.0 / ((double)items * (p.causal ? 0.5 : 1.0));
+  const double ratio = (double)kPlanCUs / ((double)items * (p.causal ? 0.5 : 1.0));
   if (ratio < 1.5) return 0;
   const int64_t parts_wanted = ratio >= 7.0 ? 4 : ratio >= 3.5 ? 3 : 2;
   int64_t s = (parts_wanted + p.ring - 1) / p.ring;
@@ -282,8 +283,10 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   f.part_lse_bytes = up256((size_t)p.bs * Lq * hq * sizeof(float));
   f.n_cols = n_cols;
   size_t off = 0;
-  f.q_head = off; off += qb;
-  f.o_head = off; off += qb;
+  // the one-launch ring loop reads Q from and writes O to the sequence-layout shards: no head-layout copies of them
+  const size_t qo = ring_in_one_launch(p) ? 0 : qb;
+  f.q_head = off; off += qo;
+  f.o_head = off; off += qo;
   f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.v_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   const int splits = key_splits(p);
@@ -329,8 +332,9 @@ extern "C" size_t usp_attn_fwd_workspace_bytes(const usp_problem* p, int n_ranks
   return plan_fwd(*p, cols).total;
 }
 
-extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
-                            int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream_) {
+namespace {
+int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
+                  int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream_) {
   int st = usp_validate(p);
   if (st != USP_OK) return st;
   if (!q || !k || !v || !o || !lse) return USP_ERR_NULL;
@@ -449,6 +453,12 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
     if (st != USP_OK) return st;
   }
   return USP_OK;
+}
+}  // namespace
+
+extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
+                            int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_fwd_impl(p, q, k, v, o, lse, rank_begin, rank_end, workspace, workspace_bytes, stream);
 }
 
 extern "C" int usp_attn_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
@@ -794,12 +804,4 @@ extern "C" int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, 
       if (st != USP_OK) return st;
     }
   return USP_OK;
-}
-
-extern "C" int usp_calib_mfma(int mode, int iters, void* sink, size_t sink_bytes, double* flop, void* stream) {
-  if (!sink || !flop) return USP_ERR_NULL;
-  if (mode != 0 && mode != 1) return USP_ERR_UNSUPPORTED;
-  if (iters < 2 || iters > (1 << 24)) return USP_ERR_SHAPE;
-  if (sink_bytes < kCalibSinkBytes) return USP_ERR_WORKSPACE;
-  return launch_calib_mfma(mode, iters, (float*)sink, flop, (hipStream_t)stream);
 }

@@ -9,6 +9,12 @@
 
 namespace usp {
 
+// CUs of the chip the work-splitting plans are made for (MI355X).  The plans (key splits of the forward, slices and
+// head splits of the backward) size workspaces, and the workspace queries must work without a GPU, so this is a
+// constant and the ONE place it is written; the launchers ask the device for its CU count only to size their grids
+// (a plan made for another CU count is still correct, only less well balanced).
+constexpr int kPlanCUs = 256;
+
 inline size_t dtype_size(int dt) { return dt == USP_BF16 ? 2 : (dt == USP_FP32 ? 4 : 0); }
 
 // Global position of local index i under a two-run descriptor.
@@ -123,9 +129,5 @@ int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hip
 // The same for two tensors of the same size and copy layout in one launch (src1 == nullptr: one tensor).
 int launch_bwd_convert2(const float* src0, void* dst0, const float* src1, void* dst1, size_t n, int out_dtype,
                         hipStream_t stream, int n_copies = 1, size_t copy_stride = 0, int add_to_dst = 0);
-
-// Calibration loops (mode 0 pure MFMA, 1 attention mix); sink holds kCalibSinkBytes.  *flop = MFMA flop of the launch.
-constexpr size_t kCalibSinkBytes = 256 * 512 * sizeof(float);
-int launch_calib_mfma(int mode, int iters, float* sink, double* flop, hipStream_t stream);
 
 }  // namespace usp

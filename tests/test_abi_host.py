@@ -72,13 +72,13 @@ def test_local_positions_match_algorithm2_oracle(usp, L, R, U, zz):
 def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     p = usp.problem(1, 32768, 32, 8, 128, 8, 1, True)
     one = usp.usp_attn_fwd_workspace_bytes(p, 1)
-    # Q and O in head layout (32 MiB each) + one K and one V block (8 MiB each)
-    assert one == 2 * 32 * 2**20 + 2 * 8 * 2**20
+    # one K and one V block in head layout (8 MiB each); Q and O are read from / written to the shards directly
+    assert one == 2 * 8 * 2**20
     assert usp.usp_attn_fwd_workspace_bytes(p, 8) > one
     ring = usp.problem(1, 32768, 32, 8, 128, 1, 8, True)
     w = usp.usp_attn_fwd_workspace_bytes(ring, 1)
-    # bf16, R <= 16: the ring loop is one launch, so only Q, O and the 8 K and 8 V blocks (8 MiB each)
-    assert w == 2 * 32 * 2**20 + 2 * 8 * 8 * 2**20
+    # bf16, R <= 16: the ring loop is one launch, so only the 8 K and 8 V blocks (8 MiB each)
+    assert w == 2 * 8 * 8 * 2**20
     # fp32 data runs one launch per ring step: + 8 fp32 partial O and 8 partial LSE (elements are 4 bytes now)
     ring32 = usp.problem(1, 32768, 32, 8, 128, 1, 8, True, usp.USP_SPLIT_ZIGZAG, usp.USP_FP32)
     w32 = usp.usp_attn_fwd_workspace_bytes(ring32, 1)
@@ -89,7 +89,7 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     # a short sequence (128 work items for 256 CUs): each block is cut into 3 pieces that run side by side,
     # + 3 fp32 partial O (16 MiB each) and 3 partial LSE (128 KiB each)
     short = usp.problem(1, 8192, 32, 8, 128, 8, 1, True)
-    assert usp.usp_attn_fwd_workspace_bytes(short, 1) == 2 * 8 * 2**20 + 2 * 2 * 2**20 + 3 * 16 * 2**20 + 3 * 2**17
+    assert usp.usp_attn_fwd_workspace_bytes(short, 1) == 2 * 2 * 2**20 + 3 * 16 * 2**20 + 3 * 2**17
     assert usp.usp_attn_fwd_workspace_bytes(p, 0) == 0
     # backward: Q, O, dO in head layout (32 MiB each), delta (0.5), K and V (8 each), fp32 dQ (64) and one fp32 copy of
     # dK and of dV (16 MiB each) per query head of the group: the four heads run as separate work items

@@ -204,7 +204,7 @@ def test_usp_bwd_rank_range_straddling_ring_rows(usp, keep_ds):
     ws = torch.empty(usp.usp_attn_fwd_workspace_bytes(p, prob.N), dtype=torch.uint8, device="cuda")
     usp.usp_attn_fwd(p, q, k, v, o, lse, 0, prob.N, ws)
     ws2 = _bwd_workspace(usp, p, 2, keep_ds)
-    SENT = 777.0                                          # exactly representable in bf16
+    SENT = 768.0                                          # exactly representable in bf16
     dq = torch.full(q.shape, SENT, dtype=torch.bfloat16, device="cuda")
     dk = torch.full(k.shape, SENT, dtype=torch.bfloat16, device="cuda")
     dv = torch.full(v.shape, SENT, dtype=torch.bfloat16, device="cuda")

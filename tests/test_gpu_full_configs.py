@@ -186,3 +186,94 @@ def test_full_size_stored_ds_backward_is_deterministic(usp):
         for a, b in zip(other, outs[0]):
             assert torch.equal(a.view(torch.int16), b.view(torch.int16))
     assert not any(torch.isnan(t.float()).any().item() for t in outs[0])
+
+
+# ------------------------------------------------------------------ dK / dV away from the sequence end
+_REF_CACHE = {}
+
+
+def _group_rows_reference(case, kv_local):
+    """LSE and delta of ALL the rank's rows for the query heads of one local KV head, by the oracle (one fp64 pass):
+    rows in position-contiguous segments, each against the keys up to its last position (later keys are masked)."""
+    g = case.hq // case.hkv
+    heads = case.q_heads[kv_local * g:(kv_local + 1) * g]
+    kvh = case.kv_heads[kv_local:kv_local + 1]
+    allpos = np.arange(case.L)
+    kv = case.values(inputs.TENSOR_K, allpos, kvh)
+    vv = case.values(inputs.TENSOR_V, allpos, kvh)
+    qv = case.values(inputs.TENSOR_Q, case.block_pos, heads)
+    gv = case.values(inputs.TENSOR_DO, case.block_pos, heads)
+    lse = np.empty((case.bs, g, case.Lq))
+    delta = np.empty((case.bs, g, case.Lq))
+
+    def job(args):
+        a, h = args
+        b = min(case.Lq, a + 4096)
+        pos = case.block_pos[a:b]
+        n_keys = int(pos.max()) + 1
+        o, lse[:, h:h + 1, a:b] = orc.block_attention(qv[:, a:b, h:h + 1], kv[:, :n_keys], vv[:, :n_keys], pos, allpos[:n_keys], True)
+        delta[:, h, a:b] = np.einsum("bie,bie->bi", gv[:, a:b, h], o[:, :, 0])
+
+    # the (segment, head) pieces are independent calls of the oracle: run side by side (NumPy releases the GIL)
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        list(ex.map(job, [(a, h) for a in range(0, case.Lq, 4096) for h in range(g)]))
+    return heads, kvh, qv, gv, kv, vv, lse, delta
+
+
+def _sample_key_columns(case, rng):
+    """Key positions in BOTH zigzag chunks of two ring blocks of the rank's Ulysses column (one block when R = 1, then
+    both halves of it): first and last key of each chunk, tile-boundary keys and a uniform sample."""
+    blocks = sorted({0, case.R // 2})
+    cols = set()
+    for s in blocks:
+        blk = orc.ring_block_positions(case.L, case.R, s, case.zigzag)
+        half = blk.size // 2
+        for chunk in (blk[:half], blk[half:]):
+            cols |= {int(chunk[0]), int(chunk[-1]), int(chunk[255]), int(chunk[256])}
+            cols |= {int(x) for x in rng.choice(chunk, size=(16 if len(blocks) > 1 else 32) - 4, replace=False)}
+    return np.array(sorted(cols), dtype=np.int64)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("keep_ds", [False, True], ids=["recompute", "stored_ds"])
+@pytest.mark.parametrize("name,L,U,R,rank,kv_local", [
+    ("config5_train", 65536, 2, 4, 0, 1),
+    ("config2_ulysses8", 32768, 8, 1, 0, 0),
+])
+def test_full_size_dkdv_sampled_key_columns(usp, name, L, U, R, rank, kv_local, keep_ds):
+    """dK and dV element by element on 64 key positions spread over the sequence (both zigzag chunks of two ring
+    blocks), at full size and in both backward forms: the rank's contribution to those columns against the oracle's
+    textbook gradient (LSE and delta of every row of the rank from one fp64 pass over the head group)."""
+    case = tl.OneRankCase(usp, 1100 + len(name), 1, L, 32, 8, 128, U, R, rank, with_do=True)
+    case.forward()
+    p = case.p
+    dq, dk, dv = torch.zeros_like(case.q), torch.zeros_like(case.k), torch.zeros_like(case.v)
+    ws = _bwd_workspace(usp, p, keep_ds)
+    usp.usp_attn_bwd(p, case.q, case.k, case.v, case.o, case.lse, case.d_o, dq, dk, dv, rank, rank + 1, ws)
+    torch.cuda.synchronize()
+    del ws
+    if name not in _REF_CACHE:
+        _REF_CACHE.clear()                                   # one config's reference at a time (a few hundred MB)
+        heads, kvh, qv, gv, kv, vv, lse, delta = _group_rows_reference(case, kv_local)
+        cols = _sample_key_columns(case, np.random.default_rng(17))
+        ref_dk, ref_dv = orc.attention_backward_columns(qv, gv, lse, delta, case.block_pos, kv[:, cols], vv[:, cols], cols, True)
+        _REF_CACHE[name] = (kvh, cols, lse, ref_dk, ref_dv)
+    kvh, cols, lse, ref_dk, ref_dv = _REF_CACHE[name]
+    # the library's own LSE of those heads, all rows, against the same pass
+    g = case.hq // case.hkv
+    assert tl.max_abs(case.lse[rank][:, kv_local * g:(kv_local + 1) * g].cpu().double().numpy(), lse) <= LSE_TOL
+    # where each sampled position lives in the seq-layout buffers (the oracle's Algorithm-2 map)
+    where = {}
+    for shard in range(case.N):
+        for off, pos in enumerate(case.shard_positions(shard)):
+            where[int(pos)] = (shard, off)
+    idx = [where[int(c)] for c in cols]
+    sh = torch.tensor([i[0] for i in idx], device="cuda")
+    of = torch.tensor([i[1] for i in idx], device="cuda")
+    got_dk = tl.to_f64(dk[sh, :, of, int(kvh[0]), :]).transpose(1, 0, 2)[:, :, None, :]     # [bs, cols, 1, hs]
+    got_dv = tl.to_f64(dv[sh, :, of, int(kvh[0]), :]).transpose(1, 0, 2)[:, :, None, :]
+    assert cols.size >= 64
+    assert tl.max_abs(got_dk, ref_dk) <= GRAD_TOL
+    assert tl.max_abs(got_dv, ref_dv) <= GRAD_TOL
+    assert float(np.abs(ref_dk).max()) > 0.1 and float(np.abs(ref_dv).max()) > 0.1          # the columns are not trivially zero

@@ -170,3 +170,48 @@ def test_lse_merge_rejects_bad_arguments(usp):
         usp.usp_lse_merge([x] * 65, [x] * 65, x, x, 1, 1, 1, 64, tl.FP32, tl.FP32)
     with pytest.raises(usp.UspError):
         usp.usp_lse_merge([x], [x], x, x, 1, 1, 1, 64, 9, tl.FP32)
+
+
+# ------------------------------------------------------------------------------------- layout at the sizes bench.py times
+def _big_tags(shape, mult):
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.uint16)
+    step = 1 << 26
+    for a in range(0, n, step):                          # in pieces: the 64-bit intermediates of 872 M elements are 7 GB
+        i = np.arange(a, min(n, a + step), dtype=np.uint64)
+        out[a:a + i.size] = (i * np.uint64(mult) % np.uint64(65521)).astype(np.uint16)
+    return out.reshape(shape)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,L,U,R,heads", [
+    ("config2_q_all_8_ranks", 32768, 8, 1, 32),
+    ("config4_q_all_16_ranks", 212992, 8, 2, 32),
+    ("config4_k_all_16_ranks", 212992, 8, 2, 8),
+])
+def test_layout_a2a_bit_exact_at_bench_sizes(usp, name, L, U, R, heads):
+    """The all-ranks launches bench.py times (512 MiB of traffic at config 2, 3.3 GiB at config 4), both directions,
+    bit-exact against the oracle's index map on ranks 0, N/2 and N-1 and on their Ulysses groups."""
+    bs, hs, N = 1, 128, U * R
+    p = usp.problem(bs, L, heads, heads, hs, U, R, True, usp.USP_SPLIT_ZIGZAG, tl.BF16)
+    n, hl = L // N, heads // U
+    seq = _big_tags((N, bs, n, heads, hs), 2654435761)
+    src = tl.to_device(seq, tl.BF16)
+    head = torch.zeros((N, bs, L // R, hl, hs), dtype=torch.bfloat16, device="cuda")
+    usp.usp_layout_a2a(p, heads, usp.USP_SEQ_TO_HEAD, src, head, 0, N)
+    torch.cuda.synchronize()
+    for rank in (0, N // 2, N - 1):
+        r, u = divmod(rank, U)
+        ref = orc.a2a_seq_to_head([seq[r * U + up] for up in range(U)], u)
+        assert np.array_equal(_bits(head[rank]), ref), rank
+    del src
+    # the reverse direction from head-layout tags of its own
+    htags = _big_tags((N, bs, L // R, hl, hs), 40503)
+    hsrc = tl.to_device(htags, tl.BF16)
+    back = torch.zeros((N, bs, n, heads, hs), dtype=torch.bfloat16, device="cuda")
+    usp.usp_layout_a2a(p, heads, usp.USP_HEAD_TO_SEQ, hsrc, back, 0, N)
+    torch.cuda.synchronize()
+    for r in sorted({0, R - 1}):
+        ref = orc.a2a_head_to_seq([htags[r * U + u] for u in range(U)])
+        for up in range(U):
+            assert np.array_equal(_bits(back[r * U + up]), ref[up]), (r, up)
