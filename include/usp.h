@@ -176,6 +176,18 @@ size_t usp_attn_fwd_workspace_bytes(const usp_problem* p, int n_ranks);
 int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
                  int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream);
 
+/* usp_attn_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace), same
+ * kernels, same results bit for bit.  The scratch is a static device array of USP_NOALLOC_SCRATCH_BYTES that every
+ * GPU the library runs on holds until the process ends; the call allocates and frees nothing.  A problem whose
+ * usp_attn_fwd workspace (for the Ulysses columns the rank range touches) is larger returns USP_ERR_WORKSPACE and
+ * enqueues nothing: one rank of L = 212992, U 8 x R 2 (104 MiB) fits, a whole 16-rank range of it does not.  All
+ * calls on one GPU share the one array: calls that overlap in time on one GPU (different streams) race; calls on
+ * one stream are safe.  The array keeps the last call's contents; every region is rewritten before it is read. */
+#define USP_NOALLOC_SCRATCH_BYTES ((size_t)128 << 20)
+int usp_attn_fwd_noalloc(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
+                         int rank_begin, int rank_end, void* stream);
+
 /* D_i = sum_e dO[i][e] * O[i][e] per (batch, position, head) row: the row term of the softmax gradient
  * (textbook backward of Eq. 1).  o, d_o [bs,L,h,hs] bf16 -> delta [bs,h,L] float. */
 int usp_attn_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs, void* stream);

@@ -70,6 +70,8 @@ def load():
     lib.usp_attn_fwd_workspace_bytes.restype = C.c_size_t
     lib.usp_attn_fwd_workspace_bytes.argtypes = [P(usp_problem), I]
     lib.usp_attn_fwd.argtypes = [P(usp_problem), V, V, V, V, V, I, I, V, C.c_size_t, V]
+    lib.usp_attn_fwd_noalloc.argtypes = [P(usp_problem), V, V, V, V, V, I, I, V]
+    lib.usp_attn_fwd_noalloc.restype = I
     lib.usp_attn_delta.argtypes = [V, V, V, I, L, I, I, V]
     lib.usp_block_attn_bwd.argtypes = [V, V, V, V, V, V, V, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc), P(usp_posdesc),
                                        I, V]
@@ -189,6 +191,14 @@ def usp_attn_fwd(p, q, k, v, o, lse, rank_begin, rank_end, workspace, workspace_
         workspace_bytes = workspace.numel() * workspace.element_size()
     _check(load().usp_attn_fwd(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), rank_begin, rank_end,
                                _ptr(workspace), workspace_bytes, _stream(stream)), "usp_attn_fwd")
+
+
+USP_NOALLOC_SCRATCH_BYTES = 128 << 20
+
+
+def usp_attn_fwd_noalloc(p, q, k, v, o, lse, rank_begin, rank_end, stream=None):
+    _check(load().usp_attn_fwd_noalloc(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), rank_begin, rank_end,
+                                       _stream(stream)), "usp_attn_fwd_noalloc")
 
 
 def usp_attn_delta(o, d_o, delta, bs, L, h, hs, stream=None):

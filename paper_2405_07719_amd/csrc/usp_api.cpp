@@ -461,6 +461,46 @@ extern "C" int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, 
   return attn_fwd_impl(p, q, k, v, o, lse, rank_begin, rank_end, workspace, workspace_bytes, stream);
 }
 
+// ---------------------------------------------------------------------------------------------
+// usp_attn_fwd for callers that cannot allocate: the workspace is a static device array.  Each GPU the library
+// runs on holds its own copy of the array (at its own address) until the process ends; host code never uses the
+// array's name as an address, only what hipGetSymbolAddress returned for the current device.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[USP_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+// Device address of `scratch` on the current device (asked once per device), or null.
+void* scratch_on_current_device() {
+  static std::atomic<void*> known[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  void* ptr = known[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    known[dev].store(ptr, std::memory_order_release);   // two threads that meet here store the same address
+  }
+  return ptr;
+}
+}  // namespace
+
+extern "C" int usp_attn_fwd_noalloc(const usp_problem* p, const void* q, const void* k, const void* v, void* o,
+                                    float* lse, int rank_begin, int rank_end, void* stream) {
+  int st = usp_validate(p);
+  if (st != USP_OK) return st;
+  const int N = p->ulysses * p->ring;
+  if (rank_begin < 0 || rank_end > N || rank_begin >= rank_end) return USP_ERR_UNSUPPORTED;
+  int c0, c1;
+  column_range(*p, rank_begin, rank_end, &c0, &c1);
+  if (plan_fwd(*p, c1 - c0).total > USP_NOALLOC_SCRATCH_BYTES) return USP_ERR_WORKSPACE;   // beyond the static array
+  void* ptr = scratch_on_current_device();
+  if (!ptr) return USP_ERR_LAUNCH;
+  // every region of the workspace is written by a kernel of the call before a kernel reads it: nothing to clear
+  return attn_fwd_impl(p, q, k, v, o, lse, rank_begin, rank_end, ptr, USP_NOALLOC_SCRATCH_BYTES, stream);
+}
+
 extern "C" int usp_attn_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
                               void* stream) {
   if (!o || !d_o || !delta) return USP_ERR_NULL;
