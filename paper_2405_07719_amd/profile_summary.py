@@ -23,12 +23,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_KIB = 524288.0                       # the calibration copy: 512 MiB read, 512 MiB written
 KERNELS = {"attention_fwd": "block_attn_fwd_mfma", "bwd_dq": "bwd_dq_kernel", "bwd_dkdv": "bwd_dkdv_kernel",
            "bwd_dq_ds": "bwd_dq_ds_kernel", "layout_a2a": "layout_a2a_kernel", "lse_merge": "lse_merge_kernel",
-           "copy": "copyBuffer"}
+           "attention_fwd_fp32_out": "block_attn_fwd_mfma<.., float>", "calib_pure_mfma": "calib_pure_mfma", "calib_attention_mix": "calib_attention_mix", "copy": "copyBuffer"}
 
 
 def _short(name):
     for key, pat in KERNELS.items():
         if pat in name and not (key == "bwd_dq" and "bwd_dq_ds" in name):
+            # the forward kernel's fp32-output instance (partial results of a step-by-step ring) is a row of its own
+            if key == "attention_fwd" and ("float>" in name or "EfEEv" in name):
+                return "attention_fwd_fp32_out"
             return key
     return None
 
@@ -69,6 +72,36 @@ def clocks(counter_csv, trace_csv):
     return out
 
 
+def counter_table(paths):
+    """Every counter of the given collection files as a table: one row per counter, one column per kernel (mean per
+    dispatch, summed over the chip by the profiler).  bwd_dkdv is split by its template flag (plain / writes dS)."""
+    table = collections.defaultdict(lambda: collections.defaultdict(list))
+    for path in paths:
+        with open(path) as f:
+            for r in csv.DictReader(f):
+                k = _short(r["Kernel_Name"])
+                if not k or k == "copy":
+                    continue
+                if k == "bwd_dkdv":
+                    k = "bwd_dkdv (writes dS)" if "true" in r["Kernel_Name"] else "bwd_dkdv"
+                table[r["Counter_Name"]][k].append(float(r["Counter_Value"]))
+    cols = sorted({k for c in table.values() for k in c})
+    print("| counter | " + " | ".join(cols) + " |")
+    print("|---|" + "---|" * len(cols))
+    for c in table:
+        print(f"| {c} | " + " | ".join(f"{sum(table[c][k]) / len(table[c][k]):.4g}" if table[c][k] else "" for k in cols) + " |")
+    mf = table.get("SQ_INSTS_MFMA")
+    if mf:
+        print("\nper MFMA instruction:\n")
+        print("| counter | " + " | ".join(cols) + " |")
+        print("|---|" + "---|" * len(cols))
+        for c in table:
+            if c.startswith("SQ_INSTS_") and c != "SQ_INSTS_MFMA":
+                print(f"| {c} | " + " | ".join(
+                    f"{(sum(table[c][k]) / len(table[c][k])) / (sum(mf[k]) / len(mf[k])):.3f}" if table[c][k] and mf.get(k) and sum(mf[k]) else ""
+                    for k in cols) + " |")
+
+
 def kernel_stats(path):
     rows = []
     with open(path) as f:
@@ -85,6 +118,7 @@ def main():
     ap.add_argument("--clock-counters")
     ap.add_argument("--clock-trace")
     ap.add_argument("--kernel-stats")
+    ap.add_argument("--counter-table", nargs="*", default=[], help="counter collection files to print as one table")
     ap.add_argument("--git-head", required=True)
     ap.add_argument("--out", default=os.path.join(ROOT, "profiles", "measured.json"))
     a = ap.parse_args()
@@ -121,6 +155,8 @@ def main():
             print(f"| {name[:90]} | {calls} | {avg / 1e3:.1f} | {mn / 1e3:.1f} | {mx / 1e3:.1f} | {pct:.1f} |")
             if "block_attn_fwd_mfma" in name and "attention_avg_us" not in entry:
                 entry["attention_avg_us"] = round(avg / 1e3, 1)
+    if a.counter_table:
+        counter_table(a.counter_table)
     data = {}
     if os.path.exists(a.out):
         with open(a.out) as f:
