@@ -215,13 +215,12 @@ class Workload:
             del o_parts, l_parts
             if hasattr(usp, "usp_block_attn_fwd_state"):
                 # the same ring with the running state (m, l, unnormalised O) carried from call to call: no partials
-                st_o = torch.empty((bs, Lq, hq, hs), dtype=torch.float32, device="cuda")
-                st_ml = torch.empty((2, bs, hq, Lq), dtype=torch.float32, device="cuda")
+                state = torch.empty(usp.usp_block_attn_fwd_state_bytes(bs, Lq, hq, hs), dtype=torch.uint8, device="cuda")
 
                 def attn_state():
                     for i in range(R):
-                        usp.usp_block_attn_fwd_state(qh, k_blocks[i], v_blocks[i], st_o, st_ml, o_ring, l_ring, bs, Lq, Lq,
-                                                     hq, hkv, hs, 0.0, causal, qd, kds[i], i == 0, i == R - 1, usp.USP_BF16)
+                        usp.usp_block_attn_fwd_state(qh, k_blocks[i], v_blocks[i], state, o_ring, l_ring, bs, Lq, Lq, hq, hkv,
+                                                     hs, 0.0, causal, qd, kds[i], i == 0, i == R - 1, usp.USP_BF16)
                 attn_state()
                 tms = event_ms(attn_state, max(3, steps // 2))
                 roof["stepwise_ring_state"] = {"launches": R, "ms": round(tms, 4),

@@ -14,13 +14,13 @@
  *   - arguments are validated on the host BEFORE any launch; on error nothing is enqueued;
  *   - no device memory is allocated: scratch comes from the caller (`workspace`), its
  *     size from the matching *_workspace_bytes query (host only, works without a GPU);
- *   - calls may be issued from several host threads and on several streams.  One limit: the
- *     bf16 attention kernels (forward, dQ, dK/dV) hand out their work through counters in 16 KiB static
- *     device arrays, 256 sets used in rotation, each set back at zero when its launch ends.  Two
- *     such launches that EXECUTE at the same time (different streams) must therefore be fewer
- *     than 256 attention launches apart in issue order; launches on one stream never overlap.
- *     A launch captured into a HIP graph keeps its set for every replay: replay a graph on one
- *     stream at a time.
+ *   - calls may be issued from several host threads and on several streams.  The bf16 attention kernels (forward,
+ *     dQ, dK/dV) hand out their work through sets of counters in static device arrays (256 KiB per kernel file), each
+ *     set back at zero when its launch ends.  Every stream gets a set of its own (launches on one stream never
+ *     overlap), and so does every graph capture: calls on different streams, and graph replays beside eager calls,
+ *     cannot meet in a set.  What remains: two executable graphs instantiated from ONE capture must not be replayed
+ *     at the same time; and a process that has used more than 3840 distinct streams and captures shares the last 256
+ *     sets in rotation among the later ones.
  *
  * Notation (Sec. 2, notation table): L sequence length, hc head count, hs head size,
  * bs batch.  Added: hk = KV head count (GQA), U = Ulysses degree, R = ring degree,
@@ -123,11 +123,33 @@ int usp_block_attn_fwd(const void* q, const void* k, const void* v, void* o_part
                        const usp_posdesc* qpos, const usp_posdesc* kpos, int in_dtype, int o_dtype,
                        void* stream);
 
+/* One ring step with the running state carried from call to call (Sec. 2: the blockwise loop of SP-Ring keeps, per
+ * query row, the running maximum, the running sum and the unnormalised output, and folds one K/V block after the
+ * other into them): for a ring that RECEIVES its blocks one per step there are no partial outputs to keep and no
+ * merge pass.  Call it once per arriving block, in any order of the blocks, with the same q, qpos and state:
+ *   first != 0: the state is started (not read);  otherwise it is read and continued;
+ *   last  != 0: the final o [bs,Lq,hq,hs] (o_dtype) and lse [bs,hq,Lq] float are written (normalised, natural-log
+ *               LSE; a row that saw no key in any step gets o = 0, lse = -inf) and the state is left as it was;
+ *               otherwise the state is written back and o, lse are not touched (they may be NULL).
+ * The result after the last call equals usp_block_attn_fwd per block + usp_lse_merge, and usp_ring_attn_fwd over
+ * all blocks, up to rounding.  state: DEVICE memory of usp_block_attn_fwd_state_bytes() bytes, 16-byte aligned, in
+ * a layout private to the library (registers of the kernel, as they are); valid only between calls of the same
+ * shape.  bf16 inputs; everything else as in usp_block_attn_fwd. */
+size_t usp_block_attn_fwd_state_bytes(int bs, int64_t Lq, int hq, int hs);
+int usp_block_attn_fwd_state(const void* q, const void* k, const void* v, void* state, size_t state_bytes, void* o,
+                             float* lse, int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale,
+                             int causal, const usp_posdesc* qpos, const usp_posdesc* kpos, int first, int last,
+                             int o_dtype, void* stream);
+
 /* Merge of the ring steps' partial results (implied by the blockwise formulation of Sec. 2):
  *   lse_out = ln sum_i exp(lse_i);  o_out = sum_i exp(lse_i - lse_out) * o_i;
  * parts with lse_i = -inf contribute nothing; all -inf gives (0, -inf).
  * o_parts / lse_parts: HOST arrays of n_parts DEVICE pointers, each [bs,Lq,hq,hs] (part_dtype)
- * and [bs,hq,Lq] float; 1 <= n_parts <= USP_MAX_MERGE_PARTS.  Outputs may alias part 0. */
+ * and [bs,hq,Lq] float; 1 <= n_parts <= USP_MAX_MERGE_PARTS.  hs must be a multiple of 8.
+ * Aliasing: o_out may be the very buffer of one part (same address) when part_dtype == out_dtype and hs is 64 or
+ * 128 (every thread then overwrites exactly the bytes it has read, and the threads of a row share a wavefront), and
+ * lse_out may then be that part's lse buffer; any other overlap of an output with a part is rejected
+ * (USP_ERR_UNSUPPORTED). */
 int usp_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                   float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
                   void* stream);

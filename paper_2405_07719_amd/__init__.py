@@ -62,6 +62,11 @@ def load():
     lib.usp_local_positions.argtypes = [P(usp_problem), I, I, P(usp_posdesc), P(usp_posdesc)]
     lib.usp_layout_a2a.argtypes = [P(usp_problem), I, I, V, V, I, I, V]
     lib.usp_block_attn_fwd.argtypes = [V, V, V, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc), P(usp_posdesc), I, I, V]
+    lib.usp_block_attn_fwd_state_bytes.restype = C.c_size_t
+    lib.usp_block_attn_fwd_state_bytes.argtypes = [I, L, I, I]
+    lib.usp_block_attn_fwd_state.argtypes = [V, V, V, V, C.c_size_t, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc),
+                                             P(usp_posdesc), I, I, I, V]
+    lib.usp_block_attn_fwd_state.restype = I
     lib.usp_lse_merge.argtypes = [P(V), P(V), I, V, V, I, L, I, I, I, I, V]
     lib.usp_ring_attn_fwd.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc),
                                       I, I, V]
@@ -146,6 +151,19 @@ def usp_block_attn_fwd(q, k, v, o_part, lse_part, bs, Lq, Lk, hq, hkv, hs, scale
                                      scale, int(bool(causal)), C.byref(qpos) if qpos is not None else None,
                                      C.byref(kpos) if kpos is not None else None, in_dtype, o_dtype, _stream(stream)),
            "usp_block_attn_fwd")
+
+
+def usp_block_attn_fwd_state_bytes(bs, Lq, hq, hs):
+    return int(load().usp_block_attn_fwd_state_bytes(bs, Lq, hq, hs))
+
+
+def usp_block_attn_fwd_state(q, k, v, state, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal, qpos, kpos, first, last,
+                             o_dtype, stream=None):
+    _check(load().usp_block_attn_fwd_state(_ptr(q), _ptr(k), _ptr(v), _ptr(state), state.numel() * state.element_size(),
+                                           _ptr(o), _ptr(lse), bs, Lq, Lk, hq, hkv, hs, scale, int(bool(causal)),
+                                           C.byref(qpos) if qpos is not None else None,
+                                           C.byref(kpos) if kpos is not None else None, int(bool(first)),
+                                           int(bool(last)), o_dtype, _stream(stream)), "usp_block_attn_fwd_state")
 
 
 def usp_lse_merge(o_parts, lse_parts, o_out, lse_out, bs, Lq, hq, hs, part_dtype, out_dtype, stream=None):

@@ -5,6 +5,10 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <functional>
+#include <mutex>
+#include <thread>
+#include <unordered_map>
 
 namespace usp {
 namespace dev {
@@ -146,12 +150,13 @@ __device__ inline float both_halves_sum(float x) {
 // draws from queue x mod n_queues while that has items, and from the next queues round the ring after that.  It
 // ends when it has found all queues empty.
 //
-// Every launch uses one of kTicketSlots sets of counters (the host hands them out in rotation): one per queue, and
-// one that counts the workgroups that have left.  A workgroup leaves when it finds no item, and says so; the one
-// that leaves last (nobody draws after it) puts the whole set back to zero, so it is zero again at the next launch,
-// graph replays included.  Two launches may share a set only if they do not execute at the same time; with the
-// rotation that takes kTicketSlots launches issued between the two.
-constexpr int kTicketSlots = 256;
+// Every launch uses one of kTicketSlots sets of counters: one per queue, and one that counts the workgroups that
+// have left.  A workgroup leaves when it finds no item, and says so; the one that leaves last (nobody draws after it)
+// puts the whole set back to zero, so it is zero again at the next launch, graph replays included.  Two launches may
+// share a set only if they do not execute at the same time: the host gives every stream (and every graph capture) a
+// set of its own, see ticket_slot_for().
+constexpr int kTicketSlots = 4096;      // 256 KiB of counters per kernel file
+constexpr int kTicketKeyed = 3840;      // sets that belong to one stream (or one graph capture) each; the rest rotate
 constexpr int kMaxItemQueues = 8;
 constexpr int kSlotStride = 16;          // counters per set: eight queues, "left", padding to 64 bytes
 constexpr unsigned kNoDraw = ~0u;
@@ -248,9 +253,52 @@ inline int compute_units() {
   }
   return n;
 }
-inline int next_ticket_slot() {
-  static std::atomic<unsigned> issued{0};
-  return (int)(issued.fetch_add(1, std::memory_order_relaxed) % dev::kTicketSlots);
+// The set of counters a launch uses.  Two launches may share a set only if they never execute at the same time.
+// Launches on ONE stream never do, so a set belongs to a stream: the first kTicketKeyed - 1 distinct streams seen by
+// the process each get a set of their own, for good (stream handles of destroyed streams come back, and so do their
+// sets).  A launch recorded into a graph executes whenever and wherever the graph is replayed, so a capture gets a
+// set of its own too (keyed by the capture's id and the stream being captured); the per-thread default stream is a
+// different stream in every thread and is keyed by the thread as well.  What can still collide: two executable
+// graphs instantiated from one capture replayed at the same time, and, once more than kTicketKeyed - 1 streams and
+// captures have been seen, the later ones, which share the last kTicketSlots - kTicketKeyed sets in rotation as all
+// launches once did (two of THOSE collide only if they execute at the same time and are fewer than that many
+// launches apart).
+inline int ticket_slot_for(hipStream_t stream) {
+  struct Key {
+    const void* stream;
+    unsigned long long capture;
+    size_t thread;
+    bool operator==(const Key& o) const { return stream == o.stream && capture == o.capture && thread == o.thread; }
+  };
+  struct KeyHash {
+    size_t operator()(const Key& k) const {
+      return std::hash<const void*>()(k.stream) ^ (std::hash<unsigned long long>()(k.capture) * 0x9E3779B97F4A7C15ull) ^
+             (k.thread * 0xC2B2AE3D27D4EB4Full);
+    }
+  };
+  static std::mutex mu;
+  static std::unordered_map<Key, int, KeyHash> slots;
+  static std::atomic<unsigned> overflow{0};
+  Key key{(const void*)stream, 0ull, 0};
+  if (stream == hipStreamPerThread) key.thread = std::hash<std::thread::id>()(std::this_thread::get_id()) | 1u;
+  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+  unsigned long long id = 0;
+  if (stream != nullptr && hipStreamGetCaptureInfo(stream, &status, &id) == hipSuccess) {
+    if (status == hipStreamCaptureStatusActive) key.capture = id + 1;
+  } else {
+    (void)hipGetLastError();   // the legacy default stream cannot be captured; nothing to report
+  }
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = slots.find(key);
+    if (it != slots.end()) return it->second;
+    if ((int)slots.size() < dev::kTicketKeyed) {
+      const int slot = (int)slots.size();
+      slots.emplace(key, slot);
+      return slot;
+    }
+  }
+  return dev::kTicketKeyed + (int)(overflow.fetch_add(1, std::memory_order_relaxed) % (dev::kTicketSlots - dev::kTicketKeyed));
 }
 
 }  // namespace usp

@@ -1028,7 +1028,7 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     const int64_t grid = (int64_t)a.n_tiles * hq * bs * a.k_splits;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
     // one workgroup per CU (256 VGPRs x 8 waves fill it), fewer when there are fewer items
-    a.ticket_slot = next_ticket_slot();
+    a.ticket_slot = ticket_slot_for(stream);
     a.n_items = (int)grid;
     a.n_queues = std::gcd(dev::kMaxItemQueues, bs * hkv);
     const unsigned n_wgs = (unsigned)std::min<int64_t>(grid, compute_units());
@@ -1062,7 +1062,7 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
     const int64_t grid = unsplit * (a.g / a.heads_per_wg) * a.q_splits;
     if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
     // one workgroup per CU (256 VGPRs x 8 waves fill it), fewer when there are fewer items
-    a.ticket_slot = next_ticket_slot();
+    a.ticket_slot = ticket_slot_for(stream);
     a.n_items = (int)grid;
     // workgroups that walk the same query head share its Q / dO rows through the XCD's L2: one queue per
     // (KV group, head split) value, the two fastest indices of the item number

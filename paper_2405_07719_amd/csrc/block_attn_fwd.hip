@@ -68,7 +68,16 @@ struct AttnArgs {
   int lk_blk[kMaxBlocks];
   void* o_part[kMaxBlocks];
   float* lse_part[kMaxBlocks];
+  // Running state of a ring that delivers its blocks one per call (launch_block_attn_fwd_state): the online-softmax
+  // state of every query row (running maximum m, sum l, unnormalised O^T accumulator) in the kernel's own register
+  // layout, one record of state_record_floats() per 32-row block of a (batch, head): read at the start of an item
+  // unless state_first, written at its end instead of O and LSE unless state_last.  Null: no state (all other paths).
+  float* state;
+  int state_first, state_last;
 };
+
+// floats of one 32-row state record: the O^T accumulator (hs / 32 x 16 registers x 64 lanes), then m and l per lane
+constexpr size_t state_record_floats(int hs) { return (size_t)(hs / 32) * 16 * 64 + 2 * 64; }
 
 // The scalar arguments as one work item of the MFMA kernel sees them (read anew for every item, see the kernel).
 struct ItemArgs {
@@ -97,9 +106,10 @@ __device__ inline size_t qo_offset(const Args& a, int b, int row, int h, int hs)
 // bf16 MFMA kernel, software pipelined: while the softmax of key tile j runs on the vector ALU,
 // the matrix core already computes the scores of tile j+1, then P(j) V(j).
 // -------------------------------------------------------------------------------------------
-template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false>
 __global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64), amdgpu_waves_per_eu(WPE, WPE)))
 void block_attn_fwd_mfma(const AttnArgs) {
+  static_assert(!STATE || NQB == 1, "the state record is laid out for one 32-row block per wave");
   constexpr int NT = NWAVES * 64;
   constexpr int BM = NWAVES * NQB * 32;
   constexpr int KSTEPS = HS / 16;          // MFMA k-steps of Q K^T
@@ -217,6 +227,28 @@ void block_attn_fwd_mfma(const AttnArgs) {
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[qb][db][i] = zero;
+    }
+
+    // ---- running state of a step-by-step ring: this wave's record (one per 32-row block of the head)
+    // (an instance of its own, STATE: in the plain instance the code below is not there at all)
+    float* st_rec = nullptr;
+    if constexpr (STATE) {
+      float* const st = ap->state;
+      {
+        st_rec = st + ((((size_t)b * a.hq + h) * a.n_qtiles + qtile) * NWAVES + wave) * state_record_floats(HS);
+        if (!ap->state_first) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const f32x4 v4 = *(const f32x4*)(st_rec + ((db * 4 + j) * 64 + lane) * 4);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) oacc[0][db][4 * j + e] = v4[e];
+            }
+          m_run[0] = st_rec[DB * 16 * 64 + lane];
+          l_run[0] = st_rec[DB * 16 * 64 + 64 + lane];
+        }
+      }
     }
 
     // wave-level bounds for the mask decision
@@ -457,6 +489,18 @@ void block_attn_fwd_mfma(const AttnArgs) {
     if (threadIdx.x == 0) own_ticket = queues.begin(empty_queues);
     // ---- epilogue: normalise, write O (a row that saw no key at all: l = 0 -> O = 0, LSE = -inf)
     // ---- write O (this lane: query l32, dims 32 db + 8 j + 4 hl + 0..3) and LSE
+    if (STATE && !ap->state_last) {
+      // not the last ring step: the state goes back as it is (each store instruction of a wave fills 1 KiB)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const f32x4 v4 = {oacc[0][db][4 * j], oacc[0][db][4 * j + 1], oacc[0][db][4 * j + 2], oacc[0][db][4 * j + 3]};
+          *(f32x4*)(st_rec + ((db * 4 + j) * 64 + lane) * 4) = v4;
+        }
+      st_rec[DB * 16 * 64 + lane] = m_run[0];
+      st_rec[DB * 16 * 64 + 64 + lane] = l_run[0];
+    } else
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
       const float l_tot = both_halves_sum(l_run[qb]);
@@ -562,7 +606,7 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
   }
 }
 
-template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT>
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false>
 int launch_mfma(AttnArgs a, hipStream_t stream) {
   constexpr int BM = NWAVES * NQB * 32;
   constexpr int KSTR = HS * 2 + 48, VSTR = HS * 2 + 64;
@@ -570,11 +614,11 @@ int launch_mfma(AttnArgs a, hipStream_t stream) {
   a.n_qtiles = (a.Lq + BM - 1) / BM;
   const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs * (a.per_block ? a.n_blocks : 1);
   if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
-  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT>;
+  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT, STATE>;
   static LdsLimitRaised lds_limit;   // per kernel instance
   if (!raise_dynamic_lds_limit((const void*)kern, lds, lds_limit)) return USP_ERR_LAUNCH;
   // one workgroup per CU (its registers and LDS fill a CU), fewer when there are fewer items
-  a.ticket_slot = next_ticket_slot();
+  a.ticket_slot = ticket_slot_for(stream);
   a.n_items = (int)grid;
   a.n_queues = std::gcd(dev::kMaxItemQueues, a.bs * a.hkv);
   const int n_wgs = (int)std::min<int64_t>(grid, compute_units());
@@ -596,7 +640,7 @@ int launch_fp32(AttnArgs a, hipStream_t stream) {
 int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
-                         int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq) {
+                         int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq, const RingState* state) {
   if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
   if (in_dtype == USP_FP32 && (n_blocks != 1 || seq)) return USP_ERR_UNSUPPORTED;
   AttnArgs a;
@@ -613,6 +657,10 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
   }
   a.n_blocks = n_blocks;
   a.per_block = 0;
+  a.state = state ? state->state : nullptr;
+  a.state_first = state ? state->first : 0;
+  a.state_last = state ? state->last : 0;
+  if (state && in_dtype != USP_BF16) return USP_ERR_DTYPE;
   for (int j = 0; j < kMaxBlocks; ++j) {
     a.lk_blk[j] = (int)Lk;
     a.o_part[j] = nullptr;
@@ -632,6 +680,13 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
     if (hs == 128) return o_dtype == USP_FP32 ? launch_fp32<128, float>(a, stream) : launch_fp32<128, __bf16>(a, stream);
     return o_dtype == USP_FP32 ? launch_fp32<64, float>(a, stream) : launch_fp32<64, __bf16>(a, stream);
   }
+  if (a.state) {   // the instance that reads and writes the running state of a step-by-step ring
+    if (hs == 128)
+      return o_dtype == USP_FP32 ? launch_mfma<128, 1, 8, 64, 2, float, true>(a, stream)
+                                 : launch_mfma<128, 1, 8, 64, 2, __bf16, true>(a, stream);
+    return o_dtype == USP_FP32 ? launch_mfma<64, 1, 8, 64, 2, float, true>(a, stream)
+                               : launch_mfma<64, 1, 8, 64, 2, __bf16, true>(a, stream);
+  }
   // 256 query rows per workgroup (8 waves x 32), 64-key tiles, two waves per SIMD
   if (hs == 128)
     return o_dtype == USP_FP32 ? launch_mfma<128, 1, 8, 64, 2, float>(a, stream)
@@ -645,6 +700,11 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
                           const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream) {
   return launch_ring_attn_fwd(q, &k, &v, &kpos, 1, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal, qpos, in_dtype,
                               o_dtype, stream);
+}
+
+size_t attn_fwd_state_bytes(int bs, int64_t Lq, int hq, int hs) {
+  // one record per 32-row block, query tiles of 256 rows rounded up (the kernel's item shape)
+  return (size_t)bs * hq * (size_t)((Lq + 255) / 256) * 8 * state_record_floats(hs) * sizeof(float);
 }
 
 int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
@@ -671,6 +731,8 @@ int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const v
   }
   a.n_blocks = n_blocks;
   a.per_block = 1;
+  a.state = nullptr;
+  a.state_first = a.state_last = 0;
   a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
   a.Lq = (int)Lq; a.Lk = (int)Lk;
   a.n_qtiles = 0;

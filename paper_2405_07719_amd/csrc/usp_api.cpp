@@ -129,6 +129,37 @@ extern "C" int usp_block_attn_fwd(const void* q, const void* k, const void* v, v
                                in_dtype, o_dtype, (hipStream_t)stream);
 }
 
+extern "C" size_t usp_block_attn_fwd_state_bytes(int bs, int64_t Lq, int hq, int hs) {
+  if (bs < 1 || Lq < 1 || hq < 1 || (hs != 64 && hs != 128) || Lq >= (int64_t)1 << 31) return 0;
+  return attn_fwd_state_bytes(bs, Lq, hq, hs);
+}
+
+extern "C" int usp_block_attn_fwd_state(const void* q, const void* k, const void* v, void* state, size_t state_bytes,
+                                        void* o, float* lse, int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
+                                        float scale, int causal, const usp_posdesc* qpos, const usp_posdesc* kpos,
+                                        int first, int last, int o_dtype, void* stream) {
+  if (!q || !k || !v || !state) return USP_ERR_NULL;
+  if (last && (!o || !lse)) return USP_ERR_NULL;
+  if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
+  if (hq % hkv) return USP_ERR_DEGREE;
+  if (hs != 64 && hs != 128) return USP_ERR_UNSUPPORTED;
+  if (o_dtype != USP_BF16 && o_dtype != USP_FP32) return USP_ERR_DTYPE;
+  if (!(scale >= 0.0f) || isinf(scale)) return USP_ERR_UNSUPPORTED;
+  if (Lq >= (int64_t)1 << 31 || Lk >= (int64_t)1 << 31) return USP_ERR_UNSUPPORTED;
+  if (state_bytes < attn_fwd_state_bytes(bs, Lq, hq, hs) || ((uintptr_t)state & 15)) return USP_ERR_WORKSPACE;
+  usp_posdesc qd = {0, Lq, 0, 0}, kd = {0, Lk, 0, 0};
+  if (causal) {
+    if (!qpos || !kpos) return USP_ERR_NULL;
+    if (!desc_ok(qpos, Lq) || !desc_ok(kpos, Lk)) return USP_ERR_SHAPE;
+    qd = *qpos;
+    kd = *kpos;
+  }
+  if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  const RingState rs = {(float*)state, first ? 1 : 0, last ? 1 : 0};
+  return launch_ring_attn_fwd(q, &k, &v, &kd, 1, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal ? 1 : 0, qd, USP_BF16,
+                              o_dtype, (hipStream_t)stream, nullptr, &rs);
+}
+
 extern "C" int usp_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                                  const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                                  int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
@@ -203,6 +234,22 @@ extern "C" int usp_lse_merge(const void* const* o_parts, const float* const* lse
   if (hs % 8) return USP_ERR_UNSUPPORTED;
   if ((part_dtype != USP_BF16 && part_dtype != USP_FP32) || (out_dtype != USP_BF16 && out_dtype != USP_FP32))
     return USP_ERR_DTYPE;
+  // An output may be the very buffer of a part only where the kernel is in-place safe: same element size (a thread
+  // overwrites exactly the bytes it has read) and a row's threads inside one wavefront (hs / 4 divides 64), so that
+  // the row's reads of the part's LSE precede the one store to it.  Any other overlap would read overwritten data.
+  {
+    const size_t rows = (size_t)bs * (size_t)Lq * hq;
+    const size_t ob = rows * hs * dtype_size(out_dtype), pb = rows * hs * dtype_size(part_dtype), lb = rows * sizeof(float);
+    const bool in_place_ok = part_dtype == out_dtype && (hs == 64 || hs == 128);
+    auto overlap = [](const void* a, size_t na, const void* b, size_t nb) {
+      return (const char*)a < (const char*)b + nb && (const char*)b < (const char*)a + na;
+    };
+    for (int i = 0; i < n_parts; ++i) {
+      if (overlap(o_out, ob, o_parts[i], pb) && !(in_place_ok && o_out == o_parts[i])) return USP_ERR_UNSUPPORTED;
+      if (overlap(lse_out, lb, lse_parts[i], lb) && !(in_place_ok && lse_out == lse_parts[i])) return USP_ERR_UNSUPPORTED;
+      if (overlap(o_out, ob, lse_parts[i], lb) || overlap(lse_out, lb, o_parts[i], pb)) return USP_ERR_UNSUPPORTED;
+    }
+  }
   return launch_lse_merge(o_parts, lse_parts, n_parts, o_out, lse_out, bs, Lq, hq, hs, part_dtype, out_dtype,
                           (hipStream_t)stream);
 }

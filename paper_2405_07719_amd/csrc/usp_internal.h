@@ -80,10 +80,16 @@ struct SeqLayoutIO { int rows_per_shard, heads, head0; };
 int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                      float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
                      hipStream_t stream, const SeqLayoutIO* seq = nullptr);
+// Optional: the running online-softmax state of a ring that delivers its blocks one call at a time (bf16 instance):
+// attn_fwd_state_bytes() bytes in the kernel's own layout; first: the state is not read (the call starts it);
+// last: the state is not written, the call writes the normalised O and the LSE instead.
+struct RingState { float* state; int first, last; };
+size_t attn_fwd_state_bytes(int bs, int64_t Lq, int hq, int hs);
 int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
-                         int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq = nullptr);
+                         int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq = nullptr,
+                         const RingState* state = nullptr);
 // Key split: the same query rows against n_blocks blocks, every (query tile, head, batch, block) its own work item of
 // ONE launch, each block's result (fp32 O, LSE) in its own partial, to be merged by launch_lse_merge.  Block j holds
 // lk_blocks[j] <= Lk keys (all Lk when lk_blocks is null); Lk is the batch stride, in rows, of every block's tensors.

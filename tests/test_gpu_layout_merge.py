@@ -215,3 +215,33 @@ def test_layout_a2a_bit_exact_at_bench_sizes(usp, name, L, U, R, heads):
         ref = orc.a2a_head_to_seq([htags[r * U + u] for u in range(U)])
         for up in range(U):
             assert np.array_equal(_bits(back[r * U + up]), ref[up]), (r, up)
+
+
+def test_lse_merge_in_place_on_part_0_and_rejected_overlaps(usp):
+    """Outputs aliasing part 0: allowed (and correct) with equal dtypes at head size 64 / 128; rejected when the
+    element sizes differ, at other head sizes, or when the buffers overlap without being the same."""
+    rng = np.random.default_rng(9)
+    for hs in (128, 64):
+        n, bs, Lq, hq = 3, 2, 333, 3
+        o, lse = _rand_parts(rng, n, bs, Lq, hq, hs, neg_inf_frac=0.1)
+        ref_o, ref_l = orc.lse_merge(o, lse)
+        d_o = [torch.from_numpy(x).cuda() for x in o]
+        d_l = [torch.from_numpy(x).cuda() for x in lse]
+        usp.usp_lse_merge(d_o, d_l, d_o[0], d_l[0], bs, Lq, hq, hs, tl.FP32, tl.FP32)       # in place on part 0
+        torch.cuda.synchronize()
+        tl.assert_lse_close(tl.to_f64(d_l[0]), ref_l, 1e-5)
+        assert tl.max_abs(tl.to_f64(d_o[0]), ref_o) <= 1e-5
+    x = torch.zeros((1, 64, 2, 128), dtype=torch.float32, device="cuda")
+    l = torch.zeros((1, 2, 64), dtype=torch.float32, device="cuda")
+    l2 = torch.zeros_like(l)
+    with pytest.raises(usp.UspError) as e:            # fp32 part, bf16 output in the same buffer
+        usp.usp_lse_merge([x], [l], x, l2, 1, 64, 2, 128, tl.FP32, tl.BF16)
+    assert e.value.status == 6
+    flat = torch.zeros(2 * x.numel(), dtype=torch.float32, device="cuda")
+    with pytest.raises(usp.UspError):                 # overlapping, not identical
+        usp.usp_lse_merge([flat[:x.numel()]], [l], flat[16:], l2, 1, 64, 2, 128, tl.FP32, tl.FP32)
+    y = torch.zeros((1, 64, 2, 40), dtype=torch.float32, device="cuda")
+    with pytest.raises(usp.UspError):                 # head size 40: a row's threads straddle wavefronts
+        usp.usp_lse_merge([y], [l], y, l2, 1, 64, 2, 40, tl.FP32, tl.FP32)
+    usp.usp_lse_merge([y], [l], torch.empty_like(y), l2, 1, 64, 2, 40, tl.FP32, tl.FP32)   # ... but fine out of place
+    torch.cuda.synchronize()

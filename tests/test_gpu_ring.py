@@ -357,3 +357,99 @@ def test_ring_attn_bwd_ws_copies_instead_of_atomics(usp, bs, L, hq, hkv, hs, R, 
         with pytest.raises(usp.UspError):
             usp.usp_ring_attn_bwd_ws(q, kb, vb, kd, d_o, lse, delta, dq2, dk2, dv2, bs, Lq, Lq, hq, hkv, hs, 0.0, True, qd,
                                      False, flags, ws, nbytes - 256)
+
+
+# ------------------------------------------------------------------ one block per call, running state in and out
+def _run_state_ring(usp, q, kb, vb, kd, qd, bs, Lq, lks, hq, hkv, hs, causal, o_dtype, poison=True):
+    """One usp_block_attn_fwd_state call per block, in the order given; returns (o, lse) of the last call."""
+    n = usp.usp_block_attn_fwd_state_bytes(bs, Lq, hq, hs)
+    assert n >= bs * hq * Lq * (hs + 2) * 4
+    # the state starts as NaN bytes (the first call must not read it), and so do the outputs (only the last call writes)
+    state = torch.full((n,), 0xFF, dtype=torch.uint8, device="cuda")
+    tdt = torch.float32 if o_dtype == tl.FP32 else torch.bfloat16
+    o = torch.full((bs, Lq, hq, hs), float("nan"), dtype=tdt, device="cuda")
+    lse = torch.full((bs, hq, Lq), float("nan"), dtype=torch.float32, device="cuda")
+    for i in range(len(kb)):
+        last = i == len(kb) - 1
+        usp.usp_block_attn_fwd_state(q, kb[i], vb[i], state, o if last else None, lse if last else None, bs, Lq, lks[i],
+                                     hq, hkv, hs, 0.0, causal, qd if causal else None, kd[i] if causal else None,
+                                     i == 0, last, o_dtype)
+        if not last:
+            torch.cuda.synchronize()
+            assert bool(torch.isnan(o.float()).all()) and bool(torch.isnan(lse).all())   # untouched before the last step
+    torch.cuda.synchronize()
+    return tl.to_f64(o), tl.to_f64(lse)
+
+
+@pytest.mark.parametrize("name,bs,L,hq,hkv,hs,R,r,zigzag,causal,order", [
+    ("zigzag_r1_of_4", 1, 2048, 4, 2, 128, 4, 1, True, True, (1, 0, 3, 2)),
+    ("zigzag_r0_of_4_rows_dead_in_three_steps", 1, 2048, 2, 1, 128, 4, 0, True, True, (3, 2, 1, 0)),
+    ("contig_r2_of_4_empty_blocks_first", 1, 2048, 2, 2, 128, 4, 2, False, True, (3, 2, 1, 0)),
+    ("noncausal_3_blocks_ragged", 2, 1500, 2, 1, 128, 3, 1, False, False, (1, 0, 2)),
+    ("hs64_r3_of_8", 1, 2048, 4, 4, 64, 8, 3, True, True, (3, 2, 1, 0, 7, 6, 5, 4)),
+    ("single_block_first_and_last", 1, 512, 2, 1, 128, 1, 0, True, True, (0,)),
+])
+@pytest.mark.parametrize("o_dtype", [tl.BF16, tl.FP32])
+def test_block_attn_fwd_state_ring_matches_oracle(usp, name, bs, L, hq, hkv, hs, R, r, zigzag, causal, order, o_dtype):
+    """A ring that receives one block per step: R calls with the running state carried between them equal the
+    oracle's plain attention over all keys (and the one-launch ring loop, up to rounding)."""
+    q, kb, vb, kd, qd, ref_o, ref_l = _ring_case(usp, 79, bs, L, hq, hkv, hs, R, r, zigzag, causal, order)
+    Lq = L // R
+    got_o, got_l = _run_state_ring(usp, q, kb, vb, kd, qd, bs, Lq, [Lq] * len(order), hq, hkv, hs, causal, o_dtype)
+    assert not np.isnan(got_o).any() and not np.isnan(got_l).any()
+    tl.assert_lse_close(got_l, ref_l, 1e-3)
+    assert tl.max_abs(got_o, ref_o) <= 2e-2
+    dead = np.isneginf(ref_l)
+    assert np.all(got_o[np.transpose(dead, (0, 2, 1))] == 0.0)
+    o1 = torch.empty((bs, Lq, hq, hs), dtype=torch.float32 if o_dtype == tl.FP32 else torch.bfloat16, device="cuda")
+    l1 = torch.empty((bs, hq, Lq), dtype=torch.float32, device="cuda")
+    usp.usp_ring_attn_fwd(q, kb, vb, kd if causal else None, o1, l1, bs, Lq, Lq, hq, hkv, hs, 0.0, causal,
+                          qd if causal else None, tl.BF16, o_dtype)
+    torch.cuda.synchronize()
+    tl.assert_lse_close(got_l, tl.to_f64(l1), 1e-4)
+    assert tl.max_abs(got_o, tl.to_f64(o1)) <= 1e-2
+
+
+def test_block_attn_fwd_state_every_mask_case_in_key_pieces(usp):
+    """Every mask case of the block kernel's tests, with the keys of the block handed over in three pieces (a ragged
+    one among them): rows are dead in some pieces and live in others."""
+    from tests.test_gpu_attn_fwd import BLOCK_CASES
+    for case in BLOCK_CASES:
+        name, bs, Lq, Lk, hq, hkv, hs, causal, qd, kd = case
+        qdesc = usp.usp_posdesc(*(list(qd) + [0] * (4 - len(qd)))) if qd else None
+        kdesc = usp.usp_posdesc(*(list(kd) + [0] * (4 - len(kd)))) if kd else None
+        qpos = np.array(qdesc.positions()) if causal else np.arange(Lq)
+        kpos = np.array(kdesc.positions()) if causal else np.arange(Lk)
+        qs, qv = tl.gen(44, inputs.TENSOR_Q, bs, np.arange(Lq), np.arange(hq), hs, tl.BF16)
+        ks, kv = tl.gen(44, inputs.TENSOR_K, bs, np.arange(Lk), np.arange(hkv), hs, tl.BF16)
+        vs, vv = tl.gen(44, inputs.TENSOR_V, bs, np.arange(Lk), np.arange(hkv), hs, tl.BF16)
+        ref_o, ref_l = orc.block_attention(qv, kv, vv, qpos, kpos, causal)
+        q = tl.to_device(qs, tl.BF16)
+        cuts = [0, Lk // 3 + 5, (2 * Lk) // 3, Lk]
+        kb, vb, kds, lks = [], [], [], []
+        for a, b in zip(cuts, cuts[1:]):
+            kb.append(tl.to_device(ks[:, a:b], tl.BF16))
+            vb.append(tl.to_device(vs[:, a:b], tl.BF16))
+            kds.append(_desc_of(usp, kpos[a:b]) if causal else None)
+            lks.append(b - a)
+        got_o, got_l = _run_state_ring(usp, q, kb, vb, kds, qdesc, bs, Lq, lks, hq, hkv, hs, causal, tl.FP32)
+        assert not np.isnan(got_o).any() and not np.isnan(got_l).any(), name
+        tl.assert_lse_close(got_l, ref_l, 1e-3)
+        assert tl.max_abs(got_o, ref_o) <= 2e-2, name
+        dead = np.isneginf(ref_l)
+        assert np.all(got_o[np.transpose(dead, (0, 2, 1))] == 0.0), name
+
+
+def test_block_attn_fwd_state_rejects_bad_arguments(usp):
+    x = torch.zeros(1 << 16, device="cuda").bfloat16()
+    l = torch.zeros(64, device="cuda")
+    qd = usp.usp_posdesc(0, 8, 0, 0)
+    state = torch.zeros(usp.usp_block_attn_fwd_state_bytes(1, 8, 1, 128), dtype=torch.uint8, device="cuda")
+    assert usp.usp_block_attn_fwd_state_bytes(1, 8, 1, 96) == 0
+    with pytest.raises(usp.UspError) as e:                  # state too small
+        usp.usp_block_attn_fwd_state(x, x, x, state[:1024], x, l, 1, 8, 8, 1, 1, 128, 0.0, True, qd, qd, True, True, tl.BF16)
+    assert e.value.status == 5
+    with pytest.raises(usp.UspError):                       # last step without outputs
+        usp.usp_block_attn_fwd_state(x, x, x, state, None, None, 1, 8, 8, 1, 1, 128, 0.0, True, qd, qd, True, True, tl.BF16)
+    with pytest.raises(usp.UspError):                       # causal without descriptors
+        usp.usp_block_attn_fwd_state(x, x, x, state, x, l, 1, 8, 8, 1, 1, 128, 0.0, True, None, None, True, True, tl.BF16)
