@@ -172,9 +172,18 @@ class Workload:
         k_blocks = [kh[(r - i) % R] for i in range(R)]
         v_blocks = [vh[(r - i) % R] for i in range(R)]
 
-        def attn_only():      # what the step launches: the rank's whole ring loop, R resident blocks, one launch
-            usp.usp_ring_attn_fwd(qh, k_blocks, v_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, causal, qd,
-                                  usp.USP_BF16, usp.USP_BF16)
+        # what the step launches: the rank's whole ring loop over its R resident blocks in one launch, V staged in
+        # key-tile-transposed layout by the all-to-all (a block [bs, Lq, hkv, hs] is the sequence layout of a
+        # one-rank problem, so the same layout call transposes it here)
+        pb = usp.problem(bs, Lq, hkv, hkv, hs, 1, 1, False, usp.USP_SPLIT_CONTIG, usp.USP_BF16)
+        vt_blocks = []
+        for vb_ in v_blocks:
+            t = torch.empty((bs, hkv, (Lq + 63) // 64, hs, 64), dtype=torch.bfloat16, device="cuda")
+            usp.usp_layout_a2a(pb, hkv, usp.USP_SEQ_TO_HEAD_VT, vb_, t, 0, 1)
+            vt_blocks.append(t)
+
+        def attn_only():
+            usp.usp_ring_attn_fwd_vt(qh, k_blocks, vt_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, causal, qd)
 
         for _ in range(warmup):
             attn_only()

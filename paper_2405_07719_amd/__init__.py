@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libusp.so")
 USP_OK = 0
 USP_BF16, USP_FP32 = 0, 1
 USP_SPLIT_CONTIG, USP_SPLIT_ZIGZAG = 0, 1
-USP_SEQ_TO_HEAD, USP_HEAD_TO_SEQ = 0, 1
+USP_SEQ_TO_HEAD, USP_HEAD_TO_SEQ, USP_SEQ_TO_HEAD_VT = 0, 1, 2
 USP_MAX_MERGE_PARTS = 64
 USP_MAX_RING_BLOCKS = 16
 
@@ -70,6 +70,8 @@ def load():
     lib.usp_lse_merge.argtypes = [P(V), P(V), I, V, V, I, L, I, I, I, I, V]
     lib.usp_ring_attn_fwd.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc),
                                       I, I, V]
+    lib.usp_ring_attn_fwd_vt.argtypes = [V, P(V), P(V), P(usp_posdesc), I, V, V, I, L, L, I, I, I, F, I, P(usp_posdesc), V]
+    lib.usp_ring_attn_fwd_vt.restype = I
     lib.usp_ring_attn_fwd_partials.argtypes = [V, P(V), P(V), P(usp_posdesc), P(C.c_int32), I, P(V), P(V), I, L, L, I, I,
                                                I, F, I, P(usp_posdesc), V]
     lib.usp_attn_fwd_workspace_bytes.restype = C.c_size_t
@@ -183,6 +185,17 @@ def usp_ring_attn_fwd(q, k_blocks, v_blocks, kpos_blocks, o, lse, bs, Lq, Lk, hq
     _check(load().usp_ring_attn_fwd(_ptr(q), ka, va, kd, n, _ptr(o), _ptr(lse), bs, Lq, Lk, hq, hkv, hs, scale,
                                     int(bool(causal)), C.byref(qpos) if qpos is not None else None, in_dtype,
                                     o_dtype, _stream(stream)), "usp_ring_attn_fwd")
+
+
+def usp_ring_attn_fwd_vt(q, k_blocks, vt_blocks, kpos_blocks, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal, qpos,
+                         stream=None):
+    n = len(k_blocks)
+    ka = (C.c_void_p * n)(*[_ptr(x) for x in k_blocks])
+    va = (C.c_void_p * n)(*[_ptr(x) for x in vt_blocks])
+    kd = (usp_posdesc * n)(*kpos_blocks) if kpos_blocks is not None else None
+    _check(load().usp_ring_attn_fwd_vt(_ptr(q), ka, va, kd, n, _ptr(o), _ptr(lse), bs, Lq, Lk, hq, hkv, hs, scale,
+                                       int(bool(causal)), C.byref(qpos) if qpos is not None else None,
+                                       _stream(stream)), "usp_ring_attn_fwd_vt")
 
 
 def usp_ring_attn_fwd_partials(q, k_blocks, v_blocks, kpos_blocks, lk_blocks, o_parts, lse_parts, bs, Lq, Lk, hq, hkv,

@@ -106,10 +106,16 @@ __device__ inline size_t qo_offset(const Args& a, int b, int row, int h, int hs)
 // bf16 MFMA kernel, software pipelined: while the softmax of key tile j runs on the vector ALU,
 // the matrix core already computes the scores of tile j+1, then P(j) V(j).
 // -------------------------------------------------------------------------------------------
-template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false>
+// VT: the V blocks come in key-tile-transposed layout (usp.h: USP_SEQ_TO_HEAD_VT): per (batch, KV head) tiles of 64
+// keys stored [hs][64 keys], the keys of each group of 16 in the order 0-3, 8-11, 4-7, 12-15.  The A operand of
+// O^T = V^T P^T (rows = head dims, 8 keys per lane) is then ONE 16-byte row read per product instead of two LDS
+// transpose reads: 32 LDS reads per step and wave (the minimum: one fragment per product) instead of 48, and the
+// LDS pipe, which issues a read every ~7 cycles whatever its width, was the busiest unit of the kernel.
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false, bool VT = false>
 __global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64), amdgpu_waves_per_eu(WPE, WPE)))
 void block_attn_fwd_mfma(const AttnArgs) {
   static_assert(!STATE || NQB == 1, "the state record is laid out for one 32-row block per wave");
+  static_assert(!VT || KT == 64, "the transposed V layout is made of 64-key tiles");
   constexpr int NT = NWAVES * 64;
   constexpr int BM = NWAVES * NQB * 32;
   constexpr int KSTEPS = HS / 16;          // MFMA k-steps of Q K^T
@@ -117,8 +123,11 @@ void block_attn_fwd_mfma(const AttnArgs) {
   constexpr int KB = KT / 32;              // 32-key blocks of S^T
   constexpr int PS = KT / 16;              // MFMA k-steps of P V
   constexpr int KSTR = HS * 2 + 48;        // LDS row stride of K in bytes: an odd number of 16 B chunks, no bank conflicts on the row reads
-  constexpr int VSTR = HS * 2 + 64;        // V rows: an odd multiple of 64 B, no bank conflicts on the transpose reads
-  constexpr int KBYTES = KT * KSTR, VBYTES = KT * VSTR;
+  // V rows: an odd multiple of 64 B, no bank conflicts on the transpose reads; transposed tiles: rows of KT keys
+  // (128 B) padded to an odd number of 16 B chunks like the K rows
+  constexpr int VSTR = VT ? KT * 2 + 16 : HS * 2 + 64;
+  constexpr int KBYTES = KT * KSTR, VBYTES = VT ? HS * VSTR : KT * VSTR;
+  constexpr int VT_TILE_BYTES = HS * KT * 2;   // one transposed tile in global memory: [HS][KT] bf16, contiguous
   constexpr int CHUNKS = KT * HS / 8;      // 16 B chunks per tile (K and V alike)
   constexpr int CPT = CHUNKS / NT;         // chunks per thread
   constexpr float kRescaleThreshold = 8.0f;   // in log2 units: P stays below 2^8
@@ -195,6 +204,8 @@ void block_attn_fwd_mfma(const AttnArgs) {
 
     const __bf16* qg = (const __bf16*)a.q;
     const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes; + key * hkv * HS * 2
+    // transposed V: the tiles of (batch, KV head) are contiguous; a.Lk (the batch stride in rows) gives their number
+    const size_t vt_head_off = ((size_t)b * a.hkv + kvh) * (size_t)((a.Lk + KT - 1) / KT) * VT_TILE_BYTES;
     int Lk_b = a.Lk;   // keys of the current block (a.Lk stays the batch stride of every block's tensors)
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane = query l32, dims 16*ks + 8*hl .. +7
@@ -280,6 +291,27 @@ void block_attn_fwd_mfma(const AttnArgs) {
     auto stash = [&](char* buf, int stride, const u32x4* reg) {
 #pragma unroll
       for (int c = 0; c < CPT; ++c) *(u32x4*)(buf + (st_row + c * ROWS_PER_PASS) * stride + st_col * 16) = reg[c];
+    };
+    // transposed V tiles: 16 KiB (8 KiB at head size 64) contiguous in global memory, chunk c of the tile goes to
+    // row c / 8 (a head dim), 16 B column c % 8 of the LDS tile
+    auto fetch_vt = [&](const char* base, int it, u32x4* reg) {
+      const char* tb = base + (size_t)tile_of(it) * VT_TILE_BYTES;
+      const __amdgpu_buffer_rsrc_t tile = __builtin_amdgcn_make_buffer_rsrc((void*)tb, 0, VT_TILE_BYTES, kRawBufferFlags);
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile, (tid + c * NT) * 16, 0, 0);
+    };
+    auto stash_vt = [&](char* buf, const u32x4* reg) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int ch = tid + c * NT;
+        *(u32x4*)(buf + (ch >> 3) * VSTR + (ch & 7) * 16) = reg[c];
+      }
+    };
+    auto fetch_v = [&](const char* base, int it, u32x4* reg) {
+      if constexpr (VT) fetch_vt(base, it, reg); else fetch(base, it, reg);
+    };
+    auto stash_v = [&](char* buf, const u32x4* reg) {
+      if constexpr (VT) stash_vt(buf, reg); else stash(buf, VSTR, reg);
     };
 
     // ---- S^T = K Q^T for the tile in K buffer kb_ (rows = keys, cols = queries)
@@ -377,7 +409,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
 
       // ---- global prefetch: K two tiles ahead, V one tile ahead
       if (has2) fetch(kg, it + 2, kreg);
-      if (has1) fetch(vg, it + 1, vreg);
+      if (has1) fetch_v(vg, it + 1, vreg);
       // keep the loads up here: left alone, the scheduler sinks them to just before the LDS stores below to
       // save registers, and every step then waits out a full global-memory latency
       __builtin_amdgcn_sched_barrier(0);
@@ -418,10 +450,16 @@ void block_attn_fwd_mfma(const AttnArgs) {
       for (int s = 0; s < PS; ++s) {
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const char* p0 = vlane + (16 * s) * VSTR + db * 64;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          bf16x8 vf;
+          if constexpr (VT) {
+            // row = head dim 32 db + l32, 16 bytes = the lane half's 8 keys of k-step s in the operand's order
+            vf = *(const bf16x8*)(vbuf + (it & 1) * VBYTES + (db * 32 + l32) * VSTR + 32 * s + 16 * hl);
+          } else {
+            const char* p0 = vlane + (16 * s) * VSTR + db * 64;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * VSTR));
+            vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          }
 #pragma unroll
           for (int qb = 0; qb < NQB; ++qb)
             oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][s], oacc[qb][db], 0, 0, 0);
@@ -430,7 +468,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
 
       // ---- hand the prefetched tiles to LDS: K(it+2) replaces K(it), V(it+1) replaces V(it-1)
       if (has2) stash(kbuf + (it & 1) * KBYTES, KSTR, kreg);
-      if (has1) stash(vbuf + ((it + 1) & 1) * VBYTES, VSTR, vreg);
+      if (has1) stash_v(vbuf + ((it + 1) & 1) * VBYTES, vreg);
       __syncthreads();
     };
 
@@ -444,14 +482,14 @@ void block_attn_fwd_mfma(const AttnArgs) {
       nt = na + (tr.b1 - tr.b0);
       if (nt == 0) continue;         // nothing of this block is visible to the query tile (workgroup-uniform)
       kg = (const char*)ap->k[blk] + kv_head_off;
-      vg = (const char*)ap->v[blk] + kv_head_off;
+      vg = (const char*)ap->v[blk] + (VT ? vt_head_off : kv_head_off);
 
       // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0.  (Every step ends on a barrier, so the previous
       //      block's last reads of these buffers are over.)
       fetch(kg, 0, kreg);
-      fetch(vg, 0, vreg);
+      fetch_v(vg, 0, vreg);
       stash(kbuf, KSTR, kreg);
-      stash(vbuf, VSTR, vreg);
+      stash_v(vbuf, vreg);
       if (nt > 1) {
         fetch(kg, 1, kreg);
         stash(kbuf + KBYTES, KSTR, kreg);
@@ -606,15 +644,15 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
   }
 }
 
-template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false>
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false, bool VT = false>
 int launch_mfma(AttnArgs a, hipStream_t stream) {
   constexpr int BM = NWAVES * NQB * 32;
-  constexpr int KSTR = HS * 2 + 48, VSTR = HS * 2 + 64;
-  constexpr size_t lds = 2 * (size_t)KT * (KSTR + VSTR);
+  constexpr int KSTR = HS * 2 + 48, VSTR = VT ? KT * 2 + 16 : HS * 2 + 64;
+  constexpr size_t lds = 2 * ((size_t)KT * KSTR + (VT ? (size_t)HS * VSTR : (size_t)KT * VSTR));
   a.n_qtiles = (a.Lq + BM - 1) / BM;
   const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs * (a.per_block ? a.n_blocks : 1);
   if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
-  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT, STATE>;
+  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT, STATE, VT>;
   static LdsLimitRaised lds_limit;   // per kernel instance
   if (!raise_dynamic_lds_limit((const void*)kern, lds, lds_limit)) return USP_ERR_LAUNCH;
   // one workgroup per CU (its registers and LDS fill a CU), fewer when there are fewer items
@@ -640,7 +678,8 @@ int launch_fp32(AttnArgs a, hipStream_t stream) {
 int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
-                         int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq, const RingState* state) {
+                         int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq, const RingState* state,
+                         bool v_transposed) {
   if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
   if (in_dtype == USP_FP32 && (n_blocks != 1 || seq)) return USP_ERR_UNSUPPORTED;
   AttnArgs a;
@@ -679,6 +718,12 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
   if (in_dtype == USP_FP32) {
     if (hs == 128) return o_dtype == USP_FP32 ? launch_fp32<128, float>(a, stream) : launch_fp32<128, __bf16>(a, stream);
     return o_dtype == USP_FP32 ? launch_fp32<64, float>(a, stream) : launch_fp32<64, __bf16>(a, stream);
+  }
+  if (state && v_transposed) return USP_ERR_UNSUPPORTED;
+  if (v_transposed) {   // V blocks in key-tile-transposed layout (bf16 in and out)
+    if (in_dtype != USP_BF16 || o_dtype != USP_BF16) return USP_ERR_DTYPE;
+    return hs == 128 ? launch_mfma<128, 1, 8, 64, 2, __bf16, false, true>(a, stream)
+                     : launch_mfma<64, 1, 8, 64, 2, __bf16, false, true>(a, stream);
   }
   if (a.state) {   // the instance that reads and writes the running state of a step-by-step ring
     if (hs == 128)

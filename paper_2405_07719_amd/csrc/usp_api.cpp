@@ -91,10 +91,13 @@ extern "C" int usp_layout_a2a(const usp_problem* p, int heads, int dir, const vo
   if (st != USP_OK) return st;
   if (!src || !dst) return USP_ERR_NULL;
   if (heads < 1 || heads % p->ulysses) return USP_ERR_DEGREE;
-  if (dir != USP_SEQ_TO_HEAD && dir != USP_HEAD_TO_SEQ) return USP_ERR_UNSUPPORTED;
+  if (dir != USP_SEQ_TO_HEAD && dir != USP_HEAD_TO_SEQ && dir != USP_SEQ_TO_HEAD_VT) return USP_ERR_UNSUPPORTED;
   const int n = p->ulysses * p->ring;
   if (rank_begin < 0 || rank_end > n || rank_begin > rank_end) return USP_ERR_UNSUPPORTED;
+  if (dir == USP_SEQ_TO_HEAD_VT && p->dtype != USP_BF16) return USP_ERR_DTYPE;
   if (rank_begin == rank_end) return USP_OK;
+  if (dir == USP_SEQ_TO_HEAD_VT)
+    return launch_layout_a2a_vt(*p, heads, src, dst, rank_begin, rank_end, 0, (hipStream_t)stream);
   return launch_layout_a2a(*p, heads, dir, src, dst, rank_begin, rank_end, 0, (hipStream_t)stream);
 }
 
@@ -160,10 +163,34 @@ extern "C" int usp_block_attn_fwd_state(const void* q, const void* k, const void
                               o_dtype, (hipStream_t)stream, nullptr, &rs);
 }
 
+namespace {
+int ring_attn_fwd_impl(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                       const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
+                       int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
+                       int in_dtype, int o_dtype, void* stream, bool v_transposed);
+}  // namespace
+
 extern "C" int usp_ring_attn_fwd(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                                  const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                                  int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
                                  int in_dtype, int o_dtype, void* stream) {
+  return ring_attn_fwd_impl(q, k_blocks, v_blocks, kpos_blocks, n_blocks, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal,
+                            qpos, in_dtype, o_dtype, stream, false);
+}
+
+extern "C" int usp_ring_attn_fwd_vt(const void* q, const void* const* k_blocks, const void* const* vt_blocks,
+                                    const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs,
+                                    int64_t Lq, int64_t Lk, int hq, int hkv, int hs, float scale, int causal,
+                                    const usp_posdesc* qpos, void* stream) {
+  return ring_attn_fwd_impl(q, k_blocks, vt_blocks, kpos_blocks, n_blocks, o, lse, bs, Lq, Lk, hq, hkv, hs, scale, causal,
+                            qpos, USP_BF16, USP_BF16, stream, true);
+}
+
+namespace {
+int ring_attn_fwd_impl(const void* q, const void* const* k_blocks, const void* const* v_blocks,
+                       const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
+                       int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc* qpos,
+                       int in_dtype, int o_dtype, void* stream, bool v_transposed) {
   if (!q || !k_blocks || !v_blocks || !o || !lse) return USP_ERR_NULL;
   if (n_blocks < 1 || n_blocks > USP_MAX_RING_BLOCKS) return USP_ERR_UNSUPPORTED;
   if (bs < 1 || Lq < 1 || Lk < 1 || hq < 1 || hkv < 1) return USP_ERR_SHAPE;
@@ -186,9 +213,13 @@ extern "C" int usp_ring_attn_fwd(const void* q, const void* const* k_blocks, con
     }
   }
   if (scale == 0.0f) scale = 1.0f / sqrtf((float)hs);
+  if (v_transposed)
+    for (int j = 0; j < n_blocks; ++j)
+      if ((uintptr_t)v_blocks[j] & 15) return USP_ERR_UNSUPPORTED;
   return launch_ring_attn_fwd(q, k_blocks, v_blocks, kd, n_blocks, o, lse, bs, Lq, Lk, hq, hkv, hs, scale,
-                              causal ? 1 : 0, qd, in_dtype, o_dtype, (hipStream_t)stream);
+                              causal ? 1 : 0, qd, in_dtype, o_dtype, (hipStream_t)stream, nullptr, nullptr, v_transposed);
 }
+}  // namespace
 
 extern "C" int usp_ring_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                                           const usp_posdesc* kpos_blocks, const int32_t* lk_blocks, int n_blocks,
@@ -268,8 +299,9 @@ inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct FwdPlan {
   size_t q_head, o_head, k_head, v_head, o_parts, lse_parts, total;
-  size_t kv_block_bytes, part_o_bytes, part_lse_bytes;
+  size_t kv_block_bytes, v_block_bytes, part_o_bytes, part_lse_bytes;
   int n_cols;
+  bool v_transposed;   // V blocks are staged in key-tile-transposed layout (the one-launch ring loop reads them so)
 };
 
 // Ulysses columns touched by ranks [rb, re): all U when the range spans more than one ring row.
@@ -334,9 +366,13 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   const size_t qo = ring_in_one_launch(p) ? 0 : qb;
   f.q_head = off; off += qo;
   f.o_head = off; off += qo;
-  f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
-  f.v_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   const int splits = key_splits(p);
+  // The one-launch ring loop (not the key-split launch, whose pieces' partials are fp32 instances) takes V in
+  // key-tile-transposed layout: tiles of 64 keys, the last one padded.
+  f.v_transposed = ring_in_one_launch(p) && splits == 0;
+  f.v_block_bytes = f.v_transposed ? vt_block_bytes(p.bs, (int64_t)Lq, (int)hkv, p.hs) : f.kv_block_bytes;
+  f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
+  f.v_head = off; off += up256(f.v_block_bytes * p.ring * n_cols);
   const size_t parts = splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
   f.o_parts = off; off += f.part_o_bytes * parts;
   f.lse_parts = off; off += f.part_lse_bytes * parts;
@@ -350,8 +386,30 @@ namespace {
 
 // K and V of every (ring row, Ulysses column in [c0, c1)) to head layout, packed by slot r * n_cols + (u - c0).
 int stage_kv_blocks(const usp_problem& p, const void* k, const void* v, char* k_head, char* v_head, size_t block_bytes,
-                    int c0, int c1, hipStream_t stream) {
+                    int c0, int c1, hipStream_t stream, size_t vt_block_bytes_ = 0) {
   const int U = p.ulysses, R = p.ring, n_cols = c1 - c0;
+  if (vt_block_bytes_) {
+    // K as rows, V in key-tile-transposed layout: one launch each, same ranks and slots
+    int st = USP_OK;
+    const void* ksrc[1] = {k};
+    if (n_cols == U) {
+      void* kdst[1] = {k_head};
+      st = launch_layout_a2a_multi(p, p.hk, USP_SEQ_TO_HEAD, 1, ksrc, kdst, 0, U * R, -1, stream);
+      if (st == USP_OK) st = launch_layout_a2a_vt(p, p.hk, v, v_head, 0, U * R, -1, stream);
+    } else if (n_cols == 1) {
+      void* kdst[1] = {k_head};
+      st = launch_layout_a2a_multi(p, p.hk, USP_SEQ_TO_HEAD, 1, ksrc, kdst, c0, U * R, -1, stream, U);
+      if (st == USP_OK) st = launch_layout_a2a_vt(p, p.hk, v, v_head, c0, U * R, -1, stream, U);
+    } else {
+      for (int r = 0; r < R && st == USP_OK; ++r) {
+        void* kdst[1] = {k_head + (size_t)r * n_cols * block_bytes};
+        st = launch_layout_a2a_multi(p, p.hk, USP_SEQ_TO_HEAD, 1, ksrc, kdst, r * U + c0, r * U + c1, -1, stream);
+        if (st == USP_OK)
+          st = launch_layout_a2a_vt(p, p.hk, v, v_head + (size_t)r * n_cols * vt_block_bytes_, r * U + c0, r * U + c1, -1, stream);
+      }
+    }
+    return st;
+  }
   // K and V have one geometry: both go through the same launches
   const void* src[2] = {k, v};
   int st = USP_OK;
@@ -403,7 +461,8 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
   // Steps 3-4 of Algorithm 1 for every K/V block the ranks in range will visit.  The workspace slot of
   // block (r, u) is r * n_cols + (u - c0): with all U columns that is the rank order (one launch per
   // tensor); with one column the ranks r * U + u are a stride-U sequence (again one launch per tensor).
-  st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream);
+  st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream,
+                       f.v_transposed ? f.v_block_bytes : 0);
   if (st != USP_OK) return st;
 
   for (int rank = rank_begin; rank < rank_end; ++rank) {
@@ -424,9 +483,9 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
       for (int i = 0; i < R; ++i) {
         const int s = ((r - i) % R + R) % R;
         usp_local_positions(p, s, u, nullptr, &kds[i]);
-        const size_t slot = ((size_t)s * (c1 - c0) + (u - c0)) * f.kv_block_bytes;
-        kb[i] = ws + f.k_head + slot;
-        vb[i] = ws + f.v_head + slot;
+        const size_t slot = (size_t)s * (c1 - c0) + (u - c0);
+        kb[i] = ws + f.k_head + slot * f.kv_block_bytes;
+        vb[i] = ws + f.v_head + slot * f.v_block_bytes;
       }
       // Steps 2 and 6 for Q and O ride on the kernel's own accesses: it reads each Q row once and writes each O
       // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
@@ -465,7 +524,8 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
         continue;
       }
       st = launch_ring_attn_fwd((const char*)q + group_off, kb, vb, kds, R, (char*)o + group_off, lse_rank, p->bs, Lq,
-                                Lq, hq, hkv, p->hs, scale, p->causal ? 1 : 0, qd, p->dtype, p->dtype, stream, &seq);
+                                Lq, hq, hkv, p->hs, scale, p->causal ? 1 : 0, qd, p->dtype, p->dtype, stream, &seq,
+                                nullptr, f.v_transposed);
       if (st != USP_OK) return st;
       continue;
     }

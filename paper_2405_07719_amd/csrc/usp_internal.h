@@ -89,7 +89,15 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
                          const usp_posdesc* kpos_blocks, int n_blocks, void* o, float* lse, int bs, int64_t Lq,
                          int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
                          int in_dtype, int o_dtype, hipStream_t stream, const SeqLayoutIO* seq = nullptr,
-                         const RingState* state = nullptr);
+                         const RingState* state = nullptr, bool v_transposed = false);
+// The key-tile-transposed layout of V blocks (USP_SEQ_TO_HEAD_VT): bytes of one rank's block, and the launch that
+// writes it for ranks rank_begin, rank_begin + rank_step, ... (packed back to back at dst when head_rank_base < 0,
+// else indexed by rank - head_rank_base), straight from the sequence-layout shards.  bf16 data only.
+inline size_t vt_block_bytes(int bs, int64_t Lk, int hkv, int hs) {
+  return (size_t)bs * hkv * (size_t)((Lk + 63) / 64) * 64 * hs * 2;
+}
+int launch_layout_a2a_vt(const usp_problem& p, int heads, const void* src, void* dst, int rank_begin, int rank_end,
+                         int head_rank_base, hipStream_t stream, int rank_step = 1);
 // Key split: the same query rows against n_blocks blocks, every (query tile, head, batch, block) its own work item of
 // ONE launch, each block's result (fp32 O, LSE) in its own partial, to be merged by launch_lse_merge.  Block j holds
 // lk_blocks[j] <= Lk keys (all Lk when lk_blocks is null); Lk is the batch stride, in rows, of every block's tensors.

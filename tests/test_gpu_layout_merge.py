@@ -245,3 +245,50 @@ def test_lse_merge_in_place_on_part_0_and_rejected_overlaps(usp):
         usp.usp_lse_merge([y], [l], y, l2, 1, 64, 2, 40, tl.FP32, tl.FP32)
     usp.usp_lse_merge([y], [l], torch.empty_like(y), l2, 1, 64, 2, 40, tl.FP32, tl.FP32)   # ... but fine out of place
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------- key-tile-transposed head layout
+_VT_ORDER = np.array([0, 1, 2, 3, 8, 9, 10, 11, 4, 5, 6, 7, 12, 13, 14, 15])
+
+
+def vt_of_head_layout(head):
+    """The format of USP_SEQ_TO_HEAD_VT written out: head [bs, Lq, h, hs] -> [bs, h, tiles, hs, 64], place j of tile t
+    = row 64 t + 16 (j // 16) + order[j % 16], zeros past the last row."""
+    bs, Lq, h, hs = head.shape
+    tiles = (Lq + 63) // 64
+    padded = np.zeros((bs, tiles * 64, h, hs), dtype=head.dtype)
+    padded[:, :Lq] = head
+    j = np.arange(64)
+    src = 16 * (j // 16) + _VT_ORDER[j % 16]
+    t = padded.reshape(bs, tiles, 64, h, hs)[:, :, src]          # [bs, tiles, place, h, hs]
+    return np.ascontiguousarray(np.transpose(t, (0, 3, 1, 4, 2)))  # [bs, h, tiles, hs, place]
+
+
+@pytest.mark.parametrize("bs,L,heads,hs,U,R", [
+    (1, 4096, 8, 128, 8, 1),      # K/V of the Ulysses-only config, scaled down
+    (2, 1200, 6, 128, 3, 2),      # ring blocks of 600 rows: a ragged last tile (24 rows), shards of 200 rows
+    (1, 2048, 16, 64, 2, 4),      # head size 64
+    (3, 80, 4, 128, 1, 4),        # blocks shorter than one tile
+])
+def test_layout_a2a_transposed_tiles_bit_exact(usp, bs, L, heads, hs, U, R):
+    N = U * R
+    p = usp.problem(bs, L, heads, heads, hs, U, R, True, usp.USP_SPLIT_ZIGZAG, tl.BF16)
+    n, Lq, hl = L // N, L // R, heads // U
+    seq = _tags((N, bs, n, heads, hs), tl.BF16)
+    src = tl.to_device(seq, tl.BF16)
+    tiles = (Lq + 63) // 64
+    vt = torch.full((N, bs, hl, tiles, hs, 64), -1.0, dtype=torch.bfloat16, device="cuda")
+    usp.usp_layout_a2a(p, heads, usp.USP_SEQ_TO_HEAD_VT, src, vt, 0, N)
+    torch.cuda.synchronize()
+    got = _bits(vt)
+    for r in range(R):
+        for u in range(U):
+            head = orc.a2a_seq_to_head([seq[r * U + up] for up in range(U)], u)      # the oracle's all-to-all ...
+            assert np.array_equal(got[r * U + u], vt_of_head_layout(head)), (r, u)    # ... in the tile format
+    # a sub-range touches only its ranks
+    vt2 = torch.full_like(vt, -1.0)
+    usp.usp_layout_a2a(p, heads, usp.USP_SEQ_TO_HEAD_VT, src, vt2, N - 1, N)
+    torch.cuda.synchronize()
+    got2 = _bits(vt2)
+    sentinel = _bits(torch.full((1,), -1.0, dtype=torch.bfloat16))[0]
+    assert np.array_equal(got2[N - 1], got[N - 1]) and np.all(got2[:N - 1] == sentinel)

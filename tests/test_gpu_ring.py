@@ -453,3 +453,37 @@ def test_block_attn_fwd_state_rejects_bad_arguments(usp):
         usp.usp_block_attn_fwd_state(x, x, x, state, None, None, 1, 8, 8, 1, 1, 128, 0.0, True, qd, qd, True, True, tl.BF16)
     with pytest.raises(usp.UspError):                       # causal without descriptors
         usp.usp_block_attn_fwd_state(x, x, x, state, x, l, 1, 8, 8, 1, 1, 128, 0.0, True, None, None, True, True, tl.BF16)
+
+
+# ------------------------------------------------------------------ V blocks in key-tile-transposed layout
+@pytest.mark.parametrize("name,bs,L,hq,hkv,hs,R,r,zigzag,causal,order", [
+    ("zigzag_r1_of_4", 1, 2048, 4, 2, 128, 4, 1, True, True, (1, 0, 3, 2)),
+    ("noncausal_3_blocks_ragged", 2, 1500, 2, 1, 128, 3, 1, False, False, (1, 0, 2)),
+    ("hs64_r3_of_8", 1, 2048, 4, 4, 64, 8, 3, True, True, (3, 2, 1, 0, 7, 6, 5, 4)),
+    ("one_block_ragged_causal", 1, 1000, 4, 1, 128, 1, 0, True, True, (0,)),
+])
+def test_ring_attn_fwd_vt_equals_row_major_v(usp, name, bs, L, hq, hkv, hs, R, r, zigzag, causal, order):
+    """The ring loop with V in key-tile-transposed layout (made by usp_layout_a2a from the same blocks): bit-equal to
+    the ring loop on row-major V, and within tolerance of the oracle."""
+    q, kb, vb, kd, qd, ref_o, ref_l = _ring_case(usp, 83, bs, L, hq, hkv, hs, R, r, zigzag, causal, order)
+    Lq = Lk = L // R
+    # a block [bs, Lk, hkv, hs] is the sequence layout of a one-rank problem: its VT form comes from the layout call
+    pb = usp.problem(bs, Lk, hkv, hkv, hs, 1, 1, False, usp.USP_SPLIT_CONTIG, tl.BF16)
+    tiles = (Lk + 63) // 64
+    vt = []
+    for v in vb:
+        t = torch.full((bs, hkv, tiles, hs, 64), float("nan"), dtype=torch.bfloat16, device="cuda")
+        usp.usp_layout_a2a(pb, hkv, usp.USP_SEQ_TO_HEAD_VT, v, t, 0, 1)
+        vt.append(t)
+    o0 = torch.full((bs, Lq, hq, hs), float("nan"), dtype=torch.bfloat16, device="cuda")
+    l0 = torch.full((bs, hq, Lq), float("nan"), dtype=torch.float32, device="cuda")
+    o1, l1 = o0.clone(), l0.clone()
+    usp.usp_ring_attn_fwd(q, kb, vb, kd if causal else None, o0, l0, bs, Lq, Lk, hq, hkv, hs, 0.0, causal,
+                          qd if causal else None, tl.BF16, tl.BF16)
+    usp.usp_ring_attn_fwd_vt(q, kb, vt, kd if causal else None, o1, l1, bs, Lq, Lk, hq, hkv, hs, 0.0, causal,
+                             qd if causal else None)
+    torch.cuda.synchronize()
+    assert torch.equal(o0.view(torch.int16), o1.view(torch.int16))
+    assert torch.equal(l0.view(torch.int32), l1.view(torch.int32))
+    tl.assert_lse_close(tl.to_f64(l1), ref_l, 1e-3)
+    assert tl.max_abs(tl.to_f64(o1), ref_o) <= 2e-2
