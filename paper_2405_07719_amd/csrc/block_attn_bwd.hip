@@ -730,12 +730,6 @@ void bwd_dkdv_kernel(const BwdArgs) {
     };
     const int tr_off = tr_lane_offset<USTR>(lane);
     const int row_off = l32 * USTR + hl * 16;
-    // B operand of the extra k-step: k indices 0..2 are one (lanes of the lower half hold k 0..7), the rest zero;
-    // the upper 16 bytes of the A rows' extra step are zeroed once (nothing else writes them)
-    bf16x8 ones;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)((hl == 0 && e < 3) ? 1.f : 0.f);
-
     // The query heads of the KV group that this workgroup walks (all g of them when the grid is large enough
     // without splitting them: then nobody else adds to these keys' dK/dV and the epilogue is a plain store).
     for (int hh = 0; hh < a.heads_per_wg; ++hh) {
@@ -756,31 +750,62 @@ void bwd_dkdv_kernel(const BwdArgs) {
     __syncthreads();
     for (int it = it0; it < it1; ++it) {
       const bool more = it + 1 < it1;
-      if (more) fetch(it + 1);
-      __builtin_amdgcn_sched_barrier(0);     // keep the loads above the compute (the scheduler would sink them)
       const char* base = lds + (it & 1) * STAGE;
       const char* q_s = base;
       const char* o_s = base + QT * USTR;
       const int q0 = tile_of(it) * QT;
 
       // S = Q K^T and dP = dO V^T: rows = queries, cols = keys
+      // Operand reads run ahead of the products that use them (read just in time, every product waited out a full LDS
+      // latency): the Q fragment of k-step ks + 1 is read before the S product of ks (two registers sets), the dO and V
+      // fragments of ks + 1 right after the dP product of ks has taken its operands (one set).  Three full sets do
+      // not fit: the prefetched Q rows were spilled, with a wait for the global load on the spot.
       f32x16 s, dp;
       zero16(s);
       zero16(dp);
+      bf16x8 qa[2], oa, vb;
+      qa[0] = *(const bf16x8*)(q_s + row_off);
+      oa = *(const bf16x8*)(o_s + row_off);
+      vb = *(const bf16x8*)(v_row);
+      // the extra k-step's B operand (k indices 0..2 one, the rest zero), made anew in every step from a lane index
+      // the compiler cannot see through: kept across the loop it is four more registers
+      bf16x8 ones_now;
+      {
+        int hz = hl;
+        asm volatile("" : "+v"(hz));
+        const u32x4 w = {hz == 0 ? 0x3F803F80u : 0u, hz == 0 ? 0x00003F80u : 0u, 0u, 0u};
+        ones_now = __builtin_bit_cast(bf16x8, w);
+      }
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
-        const bf16x8 qa = *(const bf16x8*)(q_s + row_off + ks * 32);
-        const bf16x8 oa = *(const bf16x8*)(o_s + row_off + ks * 32);
-        const bf16x8 vb = *(const bf16x8*)(v_row + ks * 32);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, vb, dp, 0, 0, 0);
+      for (int ks = 0; ks <= KSTEPS; ++ks) {
+        const int cur = ks & 1, nxt = cur ^ 1;
+        // k-step KSTEPS is the extra one (row statistics: s -= LSE / scale, dp -= D): its A rows lie in the padding
+        if (ks < KSTEPS) qa[nxt] = *(const bf16x8*)(q_s + row_off + (ks + 1 < KSTEPS ? (ks + 1) * 32 : XOFF));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[cur], ks < KSTEPS ? kf[ks < KSTEPS ? ks : 0] : ones_now, s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, ks < KSTEPS ? vb : ones_now, dp, 0, 0, 0);
+        if (ks < KSTEPS) {
+          oa = *(const bf16x8*)(o_s + row_off + (ks + 1 < KSTEPS ? (ks + 1) * 32 : XOFF));
+          if (ks + 1 < KSTEPS) vb = *(const bf16x8*)(v_row + (ks + 1) * 32);
+        }
       }
-      {   // the extra k-step: s -= LSE / scale, dp -= D
-        const bf16x8 qa = *(const bf16x8*)(q_s + row_off + XOFF);
-        const bf16x8 oa = *(const bf16x8*)(o_s + row_off + XOFF);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, ones, s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(oa, ones, dp, 0, 0, 0);
+      // pin that order (left alone, the scheduler pulls every read back to just before its product to save registers)
+      __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+#pragma unroll
+      for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+
+      // The next tile's rows are fetched HERE, not at the top of the step: the first 18 products are where the
+      // registers run out (the operand reads cannot be issued ahead), and the two prefetch registers are not live there.
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) fetch(it + 1);
+      __builtin_amdgcn_sched_barrier(0);
 
       // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile.
       // P and dS overwrite s and dp in place; the mask (rare: tiles on the causal boundary or ragged) sits
@@ -837,6 +862,18 @@ void bwd_dkdv_kernel(const BwdArgs) {
           dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ot, pf, dv[db], 0, 0, 0);
           dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[db], 0, 0, 0);
         }
+      }
+      // Here too the transpose reads of the next pair of products may be asked to go before the current pair (the
+      // registers of S and dP are free by now).  Measured side by side: the instance that writes dS gains 1.4 % of the
+      // whole backward, the plain one loses 0.4-0.9 % (its schedule comes out differently): only the former asks.
+      if constexpr (WRITE_DS) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < 2 * DB - 1; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
       }
       if (more) stash((it + 1) & 1);
       __syncthreads();
