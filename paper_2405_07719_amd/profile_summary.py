@@ -23,15 +23,21 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_KIB = 524288.0                       # the calibration copy: 512 MiB read, 512 MiB written
 KERNELS = {"attention_fwd": "block_attn_fwd_mfma", "bwd_dq": "bwd_dq_kernel", "bwd_dkdv": "bwd_dkdv_kernel",
            "bwd_dq_ds": "bwd_dq_ds_kernel", "layout_a2a": "layout_a2a_kernel", "lse_merge": "lse_merge_kernel",
-           "attention_fwd_fp32_out": "block_attn_fwd_mfma<.., float>", "calib_pure_mfma": "calib_pure_mfma", "calib_attention_mix": "calib_attention_mix", "copy": "copyBuffer"}
+           "attention_fwd_fp32_out": "block_attn_fwd_mfma<.., float>", "attention_fwd_state": "block_attn_fwd_mfma<.., STATE>", "calib_pure_mfma": "calib_pure_mfma", "calib_attention_mix": "calib_attention_mix", "copy": "copyBuffer"}
 
 
 def _short(name):
     for key, pat in KERNELS.items():
         if pat in name and not (key == "bwd_dq" and "bwd_dq_ds" in name):
-            # the forward kernel's fp32-output instance (partial results of a step-by-step ring) is a row of its own
-            if key == "attention_fwd" and ("float>" in name or "EfEEv" in name):
-                return "attention_fwd_fp32_out"
+            if key == "attention_fwd":
+                # instances of the forward kernel (the profiler prints some names mangled, some demangled): bf16 out
+                # without the ring state = the launch of the one-launch ring loop; fp32 out = partial results of a
+                # step-by-step ring or of a key split; the rest = the state-carrying step kernel
+                if "DF16bLb0E" in name:
+                    return "attention_fwd"
+                if "float" in name or "EfLb" in name:
+                    return "attention_fwd_fp32_out"
+                return "attention_fwd_state"
             return key
     return None
 
