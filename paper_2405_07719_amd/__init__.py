@@ -54,6 +54,10 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2405_07719_amd.build` "
                            "(there is no CPU fallback)")
+    # torch first: it ships a HIP runtime of its own, and the tensors and streams passed in belong to that one.
+    # Loaded after torch, the library binds to the runtime already in the process; loaded before it, the library
+    # would bring in the system's copy, torch its own, and launches on torch's buffers fail ("HIP launch error").
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     P, I, L, F, V = C.POINTER, C.c_int, C.c_int64, C.c_float, C.c_void_p
     lib.usp_status_str.restype = C.c_char_p

@@ -17,6 +17,7 @@ def load():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2405_07719_amd.build`")
+        import torch  # noqa: F401  (first: the process must hold ONE HIP runtime, the one torch ships)
         lib = C.CDLL(LIB_PATH)
         lib.usp_calib_mfma.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.c_void_p]
         lib.usp_calib_mfma.restype = C.c_int

@@ -112,3 +112,16 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     assert usp.usp_attn_bwd_workspace_bytes_with_ds(p64, 1) == usp.usp_attn_bwd_workspace_bytes(p64, 1) > 0
     assert (usp.usp_ring_attn_bwd_workspace_bytes_with_ds(2, 333, 700, 4, 2, 64, 3)
             == usp.usp_ring_attn_bwd_workspace_bytes(2, 333, 700, 4, 2, 64, 3))
+
+
+def test_loading_the_binding_first_leaves_one_hip_runtime_in_the_process():
+    """torch ships a HIP runtime of its own; a process that loaded the library before torch once held two of them
+    (the system's and torch's), and launches on torch's buffers then failed.  load() imports torch first."""
+    import subprocess
+    import sys
+    code = ("import paper_2405_07719_amd as u; u.load(); import torch\n"
+            "m = {l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l}\n"
+            "print(len(m))")
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    assert out.returncode == 0, out.stderr[-500:]
+    assert out.stdout.strip() == "1"
