@@ -202,6 +202,31 @@ void block_attn_fwd_mfma(const AttnArgs) {
     const int tile_row1 = min(a.Lq, tile_row0 + BM);
     const int wave_row0 = tile_row0 + wave * (NQB * 32);
 
+    if constexpr (STATE) {
+      // A middle step of a step-by-step ring in which this query tile sees no key of the block (under the zigzag
+      // split half of a rank's rows see nothing of most blocks): the rows' state stays as it is, so it is neither
+      // read nor written back, and the item ends here.  (The first step writes the initial state, the last one the
+      // output: those walk every item.)
+      if (!ap->state_first && !ap->state_last) {
+        bool any = false;
+        for (int blk = 0; blk < a.n_blocks; ++blk) {
+          const PosDesc32 kp = {ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
+          const TileRanges t = visible_key_tiles<KT>(a.causal, a.qpos, kp, a.Lk, tile_row0, tile_row1);
+          any = any || (t.a1 - t.a0) + (t.b1 - t.b0) > 0;
+        }
+        if (!any) {   // workgroup-uniform
+          if (threadIdx.x == 0) {
+            const ItemQueues queues = {ap->ticket_slot, n_items, (int)gridDim.x, ap->n_queues};
+            const unsigned own_ticket = queues.begin(empty_queues);
+            unsigned empty = empty_queues;
+            next_item[turn] = queues.finish(own_ticket, empty);
+            empty_queues = empty;
+          }
+          continue;
+        }
+      }
+    }
+
     const __bf16* qg = (const __bf16*)a.q;
     const size_t kv_head_off = ((size_t)b * a.Lk * a.hkv + kvh) * HS * 2;   // bytes; + key * hkv * HS * 2
     // transposed V: the tiles of (batch, KV head) are contiguous; a.Lk (the batch stride in rows) gives their number
