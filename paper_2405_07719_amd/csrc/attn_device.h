@@ -161,7 +161,7 @@ constexpr int kMaxItemQueues = 8;
 constexpr int kSlotStride = 16;          // counters per set: eight queues, "left", padding to 64 bytes
 constexpr unsigned kNoDraw = ~0u;
 constexpr int kFirstRun = 8;            // see ItemQueues::first_item
-static __device__ unsigned g_work_ticket[kTicketSlots * kSlotStride];
+static __device__ __attribute__((aligned(64))) unsigned g_work_ticket[kTicketSlots * kSlotStride];   // a set = one 64-byte line
 
 // the XCD (accelerator complex die) this wave runs on, 0..7
 __device__ inline int xcd_id() { return (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u); }   // XCC_ID[3:0]
@@ -213,13 +213,22 @@ struct ItemQueues {
     }
     while (n_queues > 1) {
       // a look at the other queues (a hint; the draw decides): the first one round the ring that still has items
+      // The eight counters of the set lie in 32 bytes: two 16-byte loads that go past the caches, as an atomic load
+      // of agent scope does (cache policy sc1), bring them all in one round trip to memory.  (One atomic load per
+      // queue, each waited for before the next, cost a workgroup that finds everything empty, as each one does at
+      // the end of a launch, 8 us; eight independent atomic loads cost the memory channel that holds the line more
+      // than they saved when many workgroups ran out of items together.)
+      const __amdgpu_buffer_rsrc_t set = __builtin_amdgcn_make_buffer_rsrc((void*)counter(0), 0, kMaxItemQueues * 4, kRawBufferFlags);
+      constexpr int kPastCaches = 16;   // sc1
+      const u32x4 d0 = __builtin_amdgcn_raw_buffer_load_b128(set, 0, 0, kPastCaches);
+      const u32x4 d1 = __builtin_amdgcn_raw_buffer_load_b128(set, 16, 0, kPastCaches);
+      const unsigned drawn[kMaxItemQueues] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
       int best = -1, best_away = kMaxItemQueues;
 #pragma unroll
       for (int q = 0; q < kMaxItemQueues; ++q) {
         if (q >= n_queues || ((empty >> q) & 1u)) continue;
-        const unsigned drawn = __hip_atomic_load(counter(q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int away = (q - q0 + n_queues) % n_queues;
-        if (drawn < items_of(q) && away < best_away) { best = q; best_away = away; }
+        if (drawn[q] < items_of(q) && away < best_away) { best = q; best_away = away; }
       }
       if (best < 0) break;
       const unsigned t = add1(counter(best));
