@@ -65,6 +65,11 @@ struct AttnArgs {
   // their number of keys, and the item's O (fp32, dense) and LSE go to the block's own partial result.  Otherwise
   // (per_block = 0) an item walks all blocks, every block holds Lk keys and the result goes to o / lse.
   int per_block;
+  // Mixed launch (launch_attn_fwd_mixed, kernel instance MIXED): the first n_split_items items are (query tile, head,
+  // batch, ONE block) items as above, over the n_split_tiles query tiles that come first in item order (the heaviest
+  // under a causal mask), each with its partial result; the items after them are whole items over the other query
+  // tiles, which walk all blocks and write o / lse.  Every block holds lk_blk[j] keys.
+  int n_split_items, n_split_tiles;
   int lk_blk[kMaxBlocks];
   void* o_part[kMaxBlocks];
   float* lse_part[kMaxBlocks];
@@ -111,10 +116,11 @@ __device__ inline size_t qo_offset(const Args& a, int b, int row, int h, int hs)
 // O^T = V^T P^T (rows = head dims, 8 keys per lane) is then ONE 16-byte row read per product instead of two LDS
 // transpose reads: 32 LDS reads per step and wave (the minimum: one fragment per product) instead of 48, and the
 // LDS pipe, which issues a read every ~7 cycles whatever its width, was the busiest unit of the kernel.
-template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false, bool VT = false>
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false, bool VT = false, bool MIXED = false>
 __global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64), amdgpu_waves_per_eu(WPE, WPE)))
 void block_attn_fwd_mfma(const AttnArgs) {
   static_assert(!STATE || NQB == 1, "the state record is laid out for one 32-row block per wave");
+  static_assert(!MIXED || (!STATE && !VT && sizeof(OutT) == 2), "the mixed launch writes bf16 results and fp32 partials");
   static_assert(!VT || KT == 64, "the transposed V layout is made of 64-key tiles");
   constexpr int NT = NWAVES * 64;
   constexpr int BM = NWAVES * NQB * 32;
@@ -184,15 +190,21 @@ void block_attn_fwd_mfma(const AttnArgs) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep what derives from it in scalar registers
     const int l32 = lane & 31, hl = lane >> 5;
+    bool per_block = ap->per_block != 0;
+    if constexpr (MIXED) {
+      per_block = w < ap->n_split_items;     // the split items come first
+      if (!per_block) w -= ap->n_split_items;
+    }
     const int group = w % n_groups; w /= n_groups;
     const int hg = w % a.g;
     int t = w / a.g;
     int blk0 = 0, blk1 = a.n_blocks;         // the blocks this item walks
-    const bool per_block = ap->per_block != 0;
     if (per_block) {
       blk0 = t % a.n_blocks;
       blk1 = blk0 + 1;
       t /= a.n_blocks;
+    } else if constexpr (MIXED) {
+      t += ap->n_split_tiles;
     }
     const int qtile = a.causal ? a.n_qtiles - 1 - t : t;
     const int b = group / a.hkv, kvh = group % a.hkv;
@@ -500,7 +512,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
     const std::integral_constant<bool, true> steady;
     const std::integral_constant<bool, false> draining;
     for (int blk = blk0; blk < blk1; ++blk) {
-      if (per_block) Lk_b = ap->lk_blk[blk];
+      if (per_block || MIXED) Lk_b = ap->lk_blk[blk];
       kpos = PosDesc32{ap->kpos[blk].start0, ap->kpos[blk].len0, ap->kpos[blk].start1, ap->kpos[blk].len1};
       tr = visible_key_tiles<KT>(a.causal, a.qpos, kpos, Lk_b, tile_row0, tile_row1);
       na = tr.a1 - tr.a0;
@@ -563,6 +575,27 @@ void block_attn_fwd_mfma(const AttnArgs) {
         }
       st_rec[DB * 16 * 64 + lane] = m_run[0];
       st_rec[DB * 16 * 64 + 64 + lane] = l_run[0];
+    } else if (MIXED && per_block) {
+      // a split item of a mixed launch: its partial result, fp32, dense
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const float l_tot = both_halves_sum(l_run[qb]);
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        const int qrow = wave_row0 + qb * 32 + l32;
+        if (qrow < a.Lq) {
+          float* dst = (float*)ap->o_part[blk0] + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const f32x4 v4 = {oacc[qb][db][4 * j] * inv, oacc[qb][db][4 * j + 1] * inv, oacc[qb][db][4 * j + 2] * inv,
+                                oacc[qb][db][4 * j + 3] * inv};
+              *(f32x4*)(dst + db * 32 + j * 8) = v4;
+            }
+          if (hl == 0)
+            ap->lse_part[blk0][((size_t)b * a.hq + h) * a.Lq + qrow] = l_tot > 0.f ? m_run[qb] * a.scale + __logf(l_tot) : -INFINITY;
+        }
+      }
     } else
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
@@ -570,7 +603,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
       const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
       const int qrow = wave_row0 + qb * 32 + l32;
       if (qrow < a.Lq) {
-        OutT* dst = per_block ? (OutT*)ap->o_part[blk0] + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl
+        OutT* dst = (per_block && !MIXED) ? (OutT*)ap->o_part[blk0] + (((size_t)b * a.Lq + qrow) * a.hq + h) * HS + 4 * hl
                               : (OutT*)a.o + qo_offset(a, b, qrow, h, HS) + 4 * hl;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -588,7 +621,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
           }
         if (hl == 0) {
           const float lse = l_tot > 0.f ? m_run[qb] * a.scale + __logf(l_tot) : -INFINITY;
-          (per_block ? ap->lse_part[blk0] : a.lse)[((size_t)b * a.hq + h) * a.Lq + qrow] = lse;
+          ((per_block && !MIXED) ? ap->lse_part[blk0] : a.lse)[((size_t)b * a.hq + h) * a.Lq + qrow] = lse;
         }
       }
     }
@@ -669,15 +702,22 @@ __global__ __launch_bounds__(64) void block_attn_fwd_fp32(const AttnArgs a) {
   }
 }
 
-template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false, bool VT = false>
+template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STATE = false, bool VT = false, bool MIXED = false>
 int launch_mfma(AttnArgs a, hipStream_t stream) {
   constexpr int BM = NWAVES * NQB * 32;
   constexpr int KSTR = HS * 2 + 48, VSTR = VT ? KT * 2 + 16 : HS * 2 + 64;
   constexpr size_t lds = 2 * ((size_t)KT * KSTR + (VT ? (size_t)HS * VSTR : (size_t)KT * VSTR));
   a.n_qtiles = (a.Lq + BM - 1) / BM;
-  const int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs * (a.per_block ? a.n_blocks : 1);
+  int64_t grid = (int64_t)a.n_qtiles * a.hq * a.bs * (a.per_block ? a.n_blocks : 1);
+  if constexpr (MIXED) {
+    if (a.n_split_tiles < 0 || a.n_split_tiles > a.n_qtiles) return USP_ERR_UNSUPPORTED;
+    const int64_t split = (int64_t)a.n_split_tiles * a.hq * a.bs * a.n_blocks;
+    grid = split + (int64_t)(a.n_qtiles - a.n_split_tiles) * a.hq * a.bs;
+    if (split > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
+    a.n_split_items = (int)split;
+  }
   if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
-  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT, STATE, VT>;
+  auto kern = block_attn_fwd_mfma<HS, NQB, NWAVES, KT, WPE, OutT, STATE, VT, MIXED>;
   static LdsLimitRaised lds_limit;   // per kernel instance
   if (!raise_dynamic_lds_limit((const void*)kern, lds, lds_limit)) return USP_ERR_LAUNCH;
   // one workgroup per CU (its registers and LDS fill a CU), fewer when there are fewer items
@@ -721,6 +761,7 @@ int launch_ring_attn_fwd(const void* q, const void* const* k_blocks, const void*
   }
   a.n_blocks = n_blocks;
   a.per_block = 0;
+  a.n_split_items = a.n_split_tiles = 0;
   a.state = state ? state->state : nullptr;
   a.state_first = state ? state->first : 0;
   a.state_last = state ? state->last : 0;
@@ -781,7 +822,7 @@ int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const v
                              const usp_posdesc* kpos_blocks, const int* lk_blocks, int n_blocks, float* const* o_parts,
                              float* const* lse_parts, int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
                              float scale, int causal, const usp_posdesc& qpos, hipStream_t stream,
-                             const SeqLayoutIO* seq) {
+                             const SeqLayoutIO* seq, const MixedLaunch* mixed) {
   if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
   AttnArgs a;
   a.seq_n = seq ? seq->rows_per_shard : 0;
@@ -801,6 +842,7 @@ int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const v
   }
   a.n_blocks = n_blocks;
   a.per_block = 1;
+  a.n_split_items = a.n_split_tiles = 0;
   a.state = nullptr;
   a.state_first = a.state_last = 0;
   a.bs = bs; a.hq = hq; a.hkv = hkv; a.g = hq / hkv;
@@ -813,6 +855,14 @@ int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const v
   a.scale = scale;
   a.scale_log2 = scale * 1.4426950408889634f;
   a.qpos = PosDesc32{(int)qpos.start0, (int)qpos.len0, (int)qpos.start1, (int)qpos.len1};
+  if (mixed) {
+    a.o = mixed->o;
+    a.lse = mixed->lse;
+    a.per_block = 0;
+    a.n_split_tiles = mixed->n_split_tiles;
+    return hs == 128 ? launch_mfma<128, 1, 8, 64, 2, __bf16, false, false, true>(a, stream)
+                     : launch_mfma<64, 1, 8, 64, 2, __bf16, false, false, true>(a, stream);
+  }
   return hs == 128 ? launch_mfma<128, 1, 8, 64, 2, float>(a, stream) : launch_mfma<64, 1, 8, 64, 2, float>(a, stream);
 }
 

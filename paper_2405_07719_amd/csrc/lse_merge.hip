@@ -21,7 +21,8 @@ struct MergeArgs {
   float* lse_out;
   int64_t Lq;
   int n_parts, hq, hs, bs;
-  int64_t rows_per_batch;   // Lq * hq
+  int64_t row0;             // first row that is merged (0 = all rows)
+  int64_t rows_per_batch;   // (Lq - row0) * hq
   // SEQ instances: o_out is the first sequence-layout shard of the rank's Ulysses group, [U][bs][rows_per_shard]
   // [seq_heads][hs]; the rank's heads begin at seq_head0 (Algorithm 1's last all-to-all rides on the merge's stores)
   int rows_per_shard, seq_heads, seq_head0;
@@ -51,10 +52,10 @@ __global__ __launch_bounds__(kThreads) void lse_merge_kernel(MergeArgs a) {
   if (row_all >= a.rows_per_batch * a.bs) return;
   const int b = (int)(row_all / a.rows_per_batch);
   const int64_t row = row_all - (int64_t)b * a.rows_per_batch;           // row = i * hq + h
-  const int64_t i = row / a.hq;
-  const int h = (int)(row - i * a.hq);
+  const int64_t i = a.row0 + row / a.hq;
+  const int h = (int)(row - (i - a.row0) * a.hq);
   const int64_t li = ((int64_t)b * a.hq + h) * a.Lq + i;
-  const int64_t off = vec * 4;
+  const int64_t off = ((((int64_t)b * a.Lq + i) * a.hq + h) * vec_per_row + (vec - row_all * vec_per_row)) * 4;
 
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   float lse_out;
@@ -125,7 +126,8 @@ void launch_typed(const MergeArgs& a, dim3 grid, hipStream_t stream) {
 
 int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                      float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
-                     hipStream_t stream, const SeqLayoutIO* seq) {
+                     hipStream_t stream, const SeqLayoutIO* seq, int64_t row0) {
+  if (row0 < 0 || row0 >= Lq) return USP_ERR_UNSUPPORTED;
   MergeArgs a;
   a.rows_per_shard = seq ? seq->rows_per_shard : 0;
   a.seq_heads = seq ? seq->heads : 0;
@@ -141,7 +143,8 @@ int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, 
   a.n_parts = n_parts;
   a.hq = hq;
   a.hs = hs;
-  a.rows_per_batch = Lq * hq;
+  a.row0 = row0;
+  a.rows_per_batch = (Lq - row0) * hq;
   a.bs = bs;
   const int64_t vecs = (int64_t)bs * a.rows_per_batch * (hs / 4);
   const int64_t gx = (vecs + kThreads - 1) / kThreads;

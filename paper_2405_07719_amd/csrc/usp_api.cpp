@@ -4,7 +4,9 @@
 #include <math.h>
 
 #include <algorithm>
+#include <functional>
 #include <string.h>
+#include <vector>
 
 #include "usp_internal.h"
 
@@ -345,6 +347,72 @@ int key_splits(const usp_problem& p) {
   return s * p.ring > 1 ? (int)s : 0;
 }
 
+// Between the two regimes (more than one work item per CU, yet the heaviest item longer than a CU's fair share: a
+// causal Ulysses-only rank of four heads at L = 18000 ... 32000) only the heaviest query tiles are cut: the LAST
+// `tiles` query tiles of the rank run as two items each, one per half of the keys, with fp32 partial results that
+// are merged afterwards; the other tiles stay whole items of the same launch (launch_attn_fwd_partials with
+// MixedLaunch).  How many tiles, if any, is decided by playing the launch through on the host: the kernel's own
+// dealing (the first items given one per workgroup, the rest drawn in order by whoever is free), 8 us per item, 1.85
+// us per tile of 64 keys, 3 us for a whole item that crosses the cut, and the merge of the cut rows at 5 TB/s + 10 us.
+// Returns the number of cut tiles (0: leave the choice to key_splits()).  Host arithmetic only.
+struct HeavySplit { int tiles; int64_t cut; };   // cut: first key of the second half (a multiple of 64)
+HeavySplit heavy_split(const usp_problem& p) {
+  HeavySplit none = {0, 0};
+  if (!ring_in_one_launch(p) || p.ring != 1 || !p.causal) return none;
+  const int64_t L = p.L;
+  const int T = (int)((L + 255) / 256), n = (p.hc / p.ulysses) * p.bs;
+  const int64_t items = (int64_t)T * n;
+  if (items <= kPlanCUs || items > 2 * kPlanCUs || L < 4096) return none;
+  const int64_t cut = ((L / 2) + 63) / 64 * 64;
+  const double kItem = 8.0, kTile = 1.85, kCross = 3.0;
+  auto tiles_of = [&](int64_t keys) { return (double)((keys + 63) / 64); };
+  auto vis = [&](int i) { return std::min<int64_t>(L, (int64_t)(i + 1) * 256); };   // keys seen by query tile i (R = 1: positions in order)
+  auto play = [&](const std::vector<double>& w) {
+    std::vector<double> free_at;   // a min-heap of the workgroups' finish times
+    free_at.reserve(kPlanCUs);
+    double end = 0.0;
+    size_t j = 0;
+    for (; j < w.size() && (int)j < kPlanCUs; ++j) free_at.push_back(w[j]);
+    std::make_heap(free_at.begin(), free_at.end(), std::greater<double>());
+    for (; j < w.size(); ++j) {
+      std::pop_heap(free_at.begin(), free_at.end(), std::greater<double>());
+      free_at.back() += w[j];
+      std::push_heap(free_at.begin(), free_at.end(), std::greater<double>());
+    }
+    for (double t : free_at) end = std::max(end, t);
+    return end;
+  };
+  auto launch_time = [&](int k) {   // the last k query tiles cut at `cut` (k = T: every tile, k = 0: none)
+    std::vector<double> w;
+    w.reserve((size_t)items + (size_t)k * n);
+    for (int t = 0; t < k; ++t) {
+      const int64_t v = vis(T - 1 - t);
+      for (int piece = 0; piece < 2; ++piece)
+        for (int h = 0; h < n; ++h)
+          w.push_back(kItem + kTile * tiles_of(piece == 0 ? std::min(v, cut) : std::max<int64_t>(0, v - cut)));
+    }
+    for (int t = k; t < T; ++t) {
+      const int64_t v = vis(T - 1 - t);
+      for (int h = 0; h < n; ++h) w.push_back(kItem + kTile * tiles_of(v) + (k > 0 && v > cut ? kCross : 0.0));
+    }
+    double us = play(w);
+    if (k > 0) {
+      const double rows = (double)std::min<int64_t>(L, (int64_t)k * 256) * n;
+      us += 10.0 + rows * p.hs * (2.0 * 2.0 * 4.0 + 2.0) / 5.0e6;   // two fp32 partials written and read, bf16 out
+    }
+    return us;
+  };
+  int best = 0;
+  double best_us = launch_time(0);
+  for (int eighths = 1; eighths <= 8; ++eighths) {
+    const int k = std::max(1, T * eighths / 8);
+    const double us = launch_time(k);
+    if (us < 0.97 * best_us) { best = k; best_us = us; }   // a cut has to pay for its complexity
+  }
+  if (best == 0 || best == T) return none;   // cutting everything is key_splits()' case
+  return HeavySplit{best, cut};
+}
+
 // Positions of the keys [a, b) of a block whose positions are d.
 usp_posdesc piece_of(const usp_posdesc& d, int64_t a, int64_t b) {
   if (a >= d.len0) return usp_posdesc{d.start1 + (a - d.len0), b - a, 0, 0};
@@ -366,14 +434,15 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   const size_t qo = ring_in_one_launch(p) ? 0 : qb;
   f.q_head = off; off += qo;
   f.o_head = off; off += qo;
-  const int splits = key_splits(p);
-  // The one-launch ring loop (not the key-split launch, whose pieces' partials are fp32 instances) takes V in
+  const HeavySplit heavy = heavy_split(p);
+  const int splits = heavy.tiles ? 0 : key_splits(p);
+  // The one-launch ring loop (not the key-split launches, whose instances read V rows) takes V in
   // key-tile-transposed layout: tiles of 64 keys, the last one padded.
-  f.v_transposed = ring_in_one_launch(p) && splits == 0;
+  f.v_transposed = ring_in_one_launch(p) && splits == 0 && heavy.tiles == 0;
   f.v_block_bytes = f.v_transposed ? vt_block_bytes(p.bs, (int64_t)Lq, (int)hkv, p.hs) : f.kv_block_bytes;
   f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.v_head = off; off += up256(f.v_block_bytes * p.ring * n_cols);
-  const size_t parts = splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
+  const size_t parts = heavy.tiles ? 2 : splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
   f.o_parts = off; off += f.part_o_bytes * parts;
   f.lse_parts = off; off += f.part_lse_bytes * parts;
   f.total = off;
@@ -491,6 +560,37 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
       // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
       const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
       const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * es;
+      const HeavySplit heavy = heavy_split(*p);
+      if (heavy.tiles) {
+        // Medium length (R = 1): the last heavy.tiles query tiles in two items each, one per half of the keys, with
+        // partial results; every other tile a whole item of the same launch that writes its finished rows itself.
+        // Then the merge of the cut rows, straight to the sequence-layout shards.
+        const void* kp[2];
+        const void* vp[2];
+        usp_posdesc pd[2];
+        int lk[2];
+        float* o_ptrs[2];
+        float* l_ptrs[2];
+        for (int n = 0; n < 2; ++n) {
+          const int64_t a0 = n == 0 ? 0 : heavy.cut, a1 = n == 0 ? heavy.cut : Lq;
+          const size_t row_off = (size_t)a0 * hkv * p->hs * es;
+          kp[n] = (const char*)kb[0] + row_off;
+          vp[n] = (const char*)vb[0] + row_off;
+          pd[n] = piece_of(kds[0], a0, a1);
+          lk[n] = (int)(a1 - a0);
+          o_ptrs[n] = (float*)(ws + f.o_parts + (size_t)n * f.part_o_bytes);
+          l_ptrs[n] = (float*)(ws + f.lse_parts + (size_t)n * f.part_lse_bytes);
+        }
+        const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy.tiles};
+        st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, 2, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq, hkv,
+                                      p->hs, scale, 1, qd, stream, &seq, &mixed);
+        if (st != USP_OK) return st;
+        const int64_t row0 = ((Lq + 255) / 256 - heavy.tiles) * 256;
+        st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, 2, (char*)o + group_off, lse_rank,
+                              p->bs, Lq, hq, p->hs, USP_FP32, p->dtype, stream, &seq, row0);
+        if (st != USP_OK) return st;
+        continue;
+      }
       const int splits = key_splits(*p);
       if (splits > 0) {
         // Short sequence: every block in `splits` pieces, each (query tile, head, piece) its own work item of one

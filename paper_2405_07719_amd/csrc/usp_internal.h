@@ -77,9 +77,10 @@ int launch_layout_a2a_multi(const usp_problem& p, int heads, int dir, int n_tens
 // tensors; head0 is the rank's first head.  Attention kernels: bf16 instance only.  Merge: fp32 partials only (the
 // merged O goes to the shards, the merged LSE stays [bs,hq,Lq]).
 struct SeqLayoutIO { int rows_per_shard, heads, head0; };
+// row0 > 0: only the rows [row0, Lq) of every batch are merged (and written); the tensors keep their full shapes.
 int launch_lse_merge(const void* const* o_parts, const float* const* lse_parts, int n_parts, void* o_out,
                      float* lse_out, int bs, int64_t Lq, int hq, int hs, int part_dtype, int out_dtype,
-                     hipStream_t stream, const SeqLayoutIO* seq = nullptr);
+                     hipStream_t stream, const SeqLayoutIO* seq = nullptr, int64_t row0 = 0);
 // Optional: the running online-softmax state of a ring that delivers its blocks one call at a time (bf16 instance):
 // attn_fwd_state_bytes() bytes in the kernel's own layout; first: the state is not read (the call starts it);
 // last: the state is not written, the call writes the normalised O and the LSE instead.
@@ -101,11 +102,16 @@ int launch_layout_a2a_vt(const usp_problem& p, int heads, const void* src, void*
 // Key split: the same query rows against n_blocks blocks, every (query tile, head, batch, block) its own work item of
 // ONE launch, each block's result (fp32 O, LSE) in its own partial, to be merged by launch_lse_merge.  Block j holds
 // lk_blocks[j] <= Lk keys (all Lk when lk_blocks is null); Lk is the batch stride, in rows, of every block's tensors.
+// With `mixed`, only the n_split_tiles query tiles that come first in item order (the LAST tiles of the block under a
+// causal mask, the first ones otherwise) are cut so; the other query tiles are whole items of the same launch that walk
+// all blocks and write their finished rows (bf16, through `seq` when given) to mixed->o and mixed->lse.  The partials
+// then hold the rows of the cut tiles only, to be merged over that row range.
+struct MixedLaunch { void* o; float* lse; int n_split_tiles; };
 int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                              const usp_posdesc* kpos_blocks, const int* lk_blocks, int n_blocks, float* const* o_parts,
                              float* const* lse_parts, int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
                              float scale, int causal, const usp_posdesc& qpos, hipStream_t stream,
-                             const SeqLayoutIO* seq = nullptr);
+                             const SeqLayoutIO* seq = nullptr, const MixedLaunch* mixed = nullptr);
 int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int bs, int64_t Lq,
                           int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
                           const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream);

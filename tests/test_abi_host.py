@@ -91,6 +91,13 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     short = usp.problem(1, 8192, 32, 8, 128, 8, 1, True)
     assert usp.usp_attn_fwd_workspace_bytes(short, 1) == 2 * 2 * 2**20 + 3 * 16 * 2**20 + 3 * 2**17
     assert usp.usp_attn_fwd_workspace_bytes(p, 0) == 0
+    # medium length (320 work items for 256 CUs, the heaviest longer than a CU's share): the last query tiles are cut in
+    # two, which takes K and V as rows (5 MiB each) + 2 fp32 partial O (40 MiB each) + 2 partial LSE (320 KiB each) ...
+    medium = usp.problem(1, 20480, 32, 8, 128, 8, 1, True)
+    assert usp.usp_attn_fwd_workspace_bytes(medium, 1) == 2 * 5 * 2**20 + 2 * 40 * 2**20 + 2 * 320 * 2**10
+    # ... a little longer and nothing is cut (K rows and transposed V tiles, 7 MiB each); nor without the causal mask
+    assert usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 28672, 32, 8, 128, 8, 1, True), 1) == 2 * 7 * 2**20
+    assert usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 20480, 32, 8, 128, 8, 1, False), 1) == 2 * 5 * 2**20
     # backward: Q, O, dO in head layout (32 MiB each), delta (0.5), K and V (8 each), fp32 dQ (64) and one fp32 copy of
     # dK and of dV (16 MiB each) per query head of the group: the four heads run as separate work items
     assert usp.usp_attn_bwd_workspace_bytes(p, 1) == (3 * 32 + 2 * 8 + 64 + 2 * 4 * 16) * 2**20 + 2**19

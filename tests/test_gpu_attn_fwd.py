@@ -186,6 +186,10 @@ def test_usp_fwd_causal_gqa_all_factorisations(usp, U, R, zigzag):
     ("key_split_3_pieces_noncausal", 1, 4096, 8, 4, 128, 2, 1, False),
     ("key_split_4_pieces_batch_of_two", 2, 4096, 4, 2, 128, 2, 1, True),   # ratio 8: four pieces of 1024 keys
     ("key_split_head_size_64", 1, 2048, 4, 2, 64, 2, 1, True),
+    # medium length, more than one work item per CU but the heaviest longer than a CU's share: only the last query
+    # tiles are cut in two (partial results, merged over their rows), the others stay whole items of the same launch
+    ("heavy_tiles_cut_head_size_64", 1, 5120, 16, 4, 64, 1, 1, True),      # 5 of 20 tiles cut
+    ("heavy_tiles_cut_batch_of_two", 2, 4608, 8, 2, 128, 1, 1, True),      # 6 of 18 tiles cut
 ])
 def test_usp_fwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
     prob = tl.Problem(300 + len(name), bs, L, hc, hk, hs, U, R, causal, True, tl.BF16)

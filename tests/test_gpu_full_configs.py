@@ -37,6 +37,10 @@ def _check_forward_rows(case, rows):
     ("config3_ring8_rank0", 32768, 1, 8, 0, 256),
     ("config3_ring8_rank7", 32768, 1, 8, 7, 64),
     ("config4_hybrid208k", 212992, 8, 2, 0, 256),
+    # between the short-sequence key split and full grids: the heaviest query tiles cut in two, the rest whole
+    ("medium_20480_last_tiles_cut", 20480, 8, 1, 0, 192),
+    ("medium_24576_last_tiles_cut", 24576, 8, 1, 5, 192),
+    ("medium_28672", 28672, 8, 1, 0, 64),
 ])
 def test_full_size_forward_one_rank(usp, name, L, U, R, rank, samples):
     case = tl.OneRankCase(usp, 1000 + len(name), 1, L, 32, 8, 128, U, R, rank)
