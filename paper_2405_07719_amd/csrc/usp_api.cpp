@@ -348,29 +348,72 @@ int key_splits(const usp_problem& p) {
 }
 
 // Between the two regimes (more than one work item per CU, yet the heaviest item longer than a CU's fair share: a
-// causal Ulysses-only rank of four heads at L = 18000 ... 32000) only the heaviest query tiles are cut: the LAST
-// `tiles` query tiles of the rank run as two items each, one per half of the keys, with fp32 partial results that
-// are merged afterwards; the other tiles stay whole items of the same launch (launch_attn_fwd_partials with
-// MixedLaunch).  How many tiles, if any, is decided by playing the launch through on the host: the kernel's own
-// dealing (the first items given one per workgroup, the rest drawn in order by whoever is free), 8 us per item, 1.85
-// us per tile of 64 keys, 3 us for a whole item that crosses the cut, and the merge of the cut rows at 5 TB/s + 10 us.
-// Returns the number of cut tiles (0: leave the choice to key_splits()).  Host arithmetic only.
-struct HeavySplit { int tiles; int64_t cut; };   // cut: first key of the second half (a multiple of 64)
-HeavySplit heavy_split(const usp_problem& p) {
-  HeavySplit none = {0, 0};
-  if (!ring_in_one_launch(p) || p.ring != 1 || !p.causal) return none;
-  const int64_t L = p.L;
-  const int T = (int)((L + 255) / 256), n = (p.hc / p.ulysses) * p.bs;
+// causal rank of four heads with 18000 ... 28000 queries) only the heaviest query tiles are cut: the LAST `tiles` query
+// tiles of the rank run as one item per piece of the keys (the two halves of the one block when R = 1, else the R ring
+// blocks), with fp32 partial results that are merged afterwards; the other tiles stay whole items of the same launch
+// (launch_attn_fwd_partials with MixedLaunch).  How many tiles, if any, is decided by playing the launch through on
+// the host: the kernel's own dealing (the first items given one per workgroup, the rest drawn in order by whoever is
+// free), 8 us per item, 1.85 us per tile of 64 keys, 3 us each time a whole item moves on to another piece, and the
+// merge of the cut rows at 5 TB/s + 10 us.  Host arithmetic only; the same for every Ulysses column of a ring row.
+constexpr int kMaxHeavyPieces = USP_MAX_RING_BLOCKS;
+struct HeavyPieces { int n; int64_t first[kMaxHeavyPieces], last[kMaxHeavyPieces]; int block[kMaxHeavyPieces]; };
+
+// The pieces of ring rank r's keys, in the order its ring loop visits them: piece j = keys [first, last) of the block
+// of ring step block[j].
+HeavyPieces heavy_pieces(const usp_problem& p) {
+  HeavyPieces hp;
+  const int64_t Lq = p.L / p.ring;
+  if (p.ring == 1) {
+    const int64_t cut = ((Lq / 2) + 63) / 64 * 64;
+    hp.n = 2;
+    hp.first[0] = 0; hp.last[0] = cut; hp.block[0] = 0;
+    hp.first[1] = cut; hp.last[1] = Lq; hp.block[1] = 0;
+  } else {
+    hp.n = p.ring;
+    for (int i = 0; i < p.ring; ++i) { hp.first[i] = 0; hp.last[i] = Lq; hp.block[i] = i; }
+  }
+  return hp;
+}
+
+// Positions of the keys [a, b) of a block whose positions are d.
+usp_posdesc piece_of(const usp_posdesc& d, int64_t a, int64_t b) {
+  if (a >= d.len0) return usp_posdesc{d.start1 + (a - d.len0), b - a, 0, 0};
+  const int64_t n0 = std::min(b, d.len0) - a;
+  return usp_posdesc{d.start0 + a, n0, d.start1, (b - a) - n0};
+}
+
+// Number of query tiles of ring rank r to cut (0: none, leave the launch to key_splits()).
+int heavy_tiles(const usp_problem& p, int r) {
+  if (!ring_in_one_launch(p) || !p.causal) return 0;
+  const int64_t Lq = p.L / p.ring;
+  const int T = (int)((Lq + 255) / 256), n = (p.hc / p.ulysses) * p.bs;
   const int64_t items = (int64_t)T * n;
-  if (items <= kPlanCUs || items > 2 * kPlanCUs || L < 4096) return none;
-  const int64_t cut = ((L / 2) + 63) / 64 * 64;
+  if (items <= kPlanCUs || items > 2 * kPlanCUs || Lq < 4096) return 0;
+  const HeavyPieces hp = heavy_pieces(p);
+  usp_posdesc qd, pd[kMaxHeavyPieces];
+  ring_block_desc(p, r, &qd);
+  for (int j = 0; j < hp.n; ++j) {
+    usp_posdesc kd;
+    ring_block_desc(p, ((r - hp.block[j]) % p.ring + p.ring) % p.ring, &kd);
+    pd[j] = piece_of(kd, hp.first[j], hp.last[j]);
+  }
   const double kItem = 8.0, kTile = 1.85, kCross = 3.0;
-  auto tiles_of = [&](int64_t keys) { return (double)((keys + 63) / 64); };
-  auto vis = [&](int i) { return std::min<int64_t>(L, (int64_t)(i + 1) * 256); };   // keys seen by query tile i (R = 1: positions in order)
+  auto pos_of = [&](int64_t i) { return i < qd.len0 ? qd.start0 + i : qd.start1 + (i - qd.len0); };
+  // 64-key tiles of piece j that query tile i walks: under kpos <= qpos the visible keys of each run are a prefix of it
+  std::vector<double> tiles((size_t)T * hp.n);
+  for (int i = 0; i < T; ++i) {
+    const int64_t a = (int64_t)i * 256, b = std::min<int64_t>(Lq, a + 256);
+    int64_t qmax = std::max(pos_of(a), pos_of(b - 1));
+    if (a < qd.len0 && b > qd.len0) qmax = std::max({qmax, pos_of(qd.len0 - 1), pos_of(qd.len0)});
+    for (int j = 0; j < hp.n; ++j) {
+      const int64_t c0 = std::clamp<int64_t>(qmax - pd[j].start0 + 1, 0, pd[j].len0);
+      const int64_t c1 = std::clamp<int64_t>(qmax - pd[j].start1 + 1, 0, pd[j].len1);
+      tiles[(size_t)i * hp.n + j] = (double)((c0 + 63) / 64 + (c1 + 63) / 64);
+    }
+  }
   auto play = [&](const std::vector<double>& w) {
     std::vector<double> free_at;   // a min-heap of the workgroups' finish times
     free_at.reserve(kPlanCUs);
-    double end = 0.0;
     size_t j = 0;
     for (; j < w.size() && (int)j < kPlanCUs; ++j) free_at.push_back(w[j]);
     std::make_heap(free_at.begin(), free_at.end(), std::greater<double>());
@@ -379,45 +422,56 @@ HeavySplit heavy_split(const usp_problem& p) {
       free_at.back() += w[j];
       std::push_heap(free_at.begin(), free_at.end(), std::greater<double>());
     }
+    double end = 0.0;
     for (double t : free_at) end = std::max(end, t);
     return end;
   };
-  auto launch_time = [&](int k) {   // the last k query tiles cut at `cut` (k = T: every tile, k = 0: none)
+  auto launch_time = [&](int k) {   // the last k query tiles cut (k = T: every tile, k = 0: none)
     std::vector<double> w;
-    w.reserve((size_t)items + (size_t)k * n);
-    for (int t = 0; t < k; ++t) {
-      const int64_t v = vis(T - 1 - t);
-      for (int piece = 0; piece < 2; ++piece)
-        for (int h = 0; h < n; ++h)
-          w.push_back(kItem + kTile * tiles_of(piece == 0 ? std::min(v, cut) : std::max<int64_t>(0, v - cut)));
-    }
+    w.reserve((size_t)items + (size_t)k * n * hp.n);
+    for (int t = 0; t < k; ++t)
+      for (int j = 0; j < hp.n; ++j)
+        for (int h = 0; h < n; ++h) w.push_back(kItem + kTile * tiles[(size_t)(T - 1 - t) * hp.n + j]);
     for (int t = k; t < T; ++t) {
-      const int64_t v = vis(T - 1 - t);
-      for (int h = 0; h < n; ++h) w.push_back(kItem + kTile * tiles_of(v) + (k > 0 && v > cut ? kCross : 0.0));
+      double sum = 0.0;
+      int walked = 0;
+      for (int j = 0; j < hp.n; ++j) {
+        sum += tiles[(size_t)(T - 1 - t) * hp.n + j];
+        walked += tiles[(size_t)(T - 1 - t) * hp.n + j] > 0.0;
+      }
+      // (the one-launch ring loop pays the change of block too, so it is charged whether or not anything is cut)
+      const double cross = (p.ring > 1 || k > 0) ? kCross * std::max(0, walked - 1) : 0.0;
+      for (int h = 0; h < n; ++h) w.push_back(kItem + kTile * sum + cross);
     }
     double us = play(w);
     if (k > 0) {
-      const double rows = (double)std::min<int64_t>(L, (int64_t)k * 256) * n;
-      us += 10.0 + rows * p.hs * (2.0 * 2.0 * 4.0 + 2.0) / 5.0e6;   // two fp32 partials written and read, bf16 out
+      const double rows = (double)std::min<int64_t>(Lq, (int64_t)k * 256) * n;
+      us += 10.0 + rows * p.hs * (hp.n * 2.0 * 4.0 + 2.0) / 5.0e6;   // the fp32 partials written and read, bf16 out
     }
     return us;
   };
+  // A cut has to pay for itself: 3 % by this model when the pieces are the halves of one block, where the model's
+  // choice was the measured optimum at every length tried; 8 % when they are ring blocks of unequal visible parts,
+  // where it promises 5 % more than is measured (the uncut launch's long tail runs on few CUs at a higher clock, and
+  // the cut launch reads V as rows, not as transposed tiles).
+  const double need = p.ring == 1 ? 0.97 : 0.92;
+  const double uncut_us = launch_time(0);
   int best = 0;
-  double best_us = launch_time(0);
+  double best_us = uncut_us;
   for (int eighths = 1; eighths <= 8; ++eighths) {
     const int k = std::max(1, T * eighths / 8);
     const double us = launch_time(k);
-    if (us < 0.97 * best_us) { best = k; best_us = us; }   // a cut has to pay for its complexity
+    if (us < best_us) { best = k; best_us = us; }
   }
-  if (best == 0 || best == T) return none;   // cutting everything is key_splits()' case
-  return HeavySplit{best, cut};
+  if (best_us >= need * uncut_us) return 0;
+  return best == T ? 0 : best;   // cutting everything is key_splits()' case
 }
 
-// Positions of the keys [a, b) of a block whose positions are d.
-usp_posdesc piece_of(const usp_posdesc& d, int64_t a, int64_t b) {
-  if (a >= d.len0) return usp_posdesc{d.start1 + (a - d.len0), b - a, 0, 0};
-  const int64_t n0 = std::min(b, d.len0) - a;
-  return usp_posdesc{d.start0 + a, n0, d.start1, (b - a) - n0};
+// Whether any ring rank of the problem cuts tiles: then V is staged as rows and the workspace holds the partials.
+bool heavy_any(const usp_problem& p) {
+  for (int r = 0; r < p.ring; ++r)
+    if (heavy_tiles(p, r) > 0) return true;
+  return false;
 }
 
 FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
@@ -434,15 +488,16 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   const size_t qo = ring_in_one_launch(p) ? 0 : qb;
   f.q_head = off; off += qo;
   f.o_head = off; off += qo;
-  const HeavySplit heavy = heavy_split(p);
-  const int splits = heavy.tiles ? 0 : key_splits(p);
+  const bool heavy = heavy_any(p);
+  const int splits = key_splits(p);
   // The one-launch ring loop (not the key-split launches, whose instances read V rows) takes V in
   // key-tile-transposed layout: tiles of 64 keys, the last one padded.
-  f.v_transposed = ring_in_one_launch(p) && splits == 0 && heavy.tiles == 0;
+  f.v_transposed = ring_in_one_launch(p) && splits == 0 && !heavy;
   f.v_block_bytes = f.v_transposed ? vt_block_bytes(p.bs, (int64_t)Lq, (int)hkv, p.hs) : f.kv_block_bytes;
   f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.v_head = off; off += up256(f.v_block_bytes * p.ring * n_cols);
-  const size_t parts = heavy.tiles ? 2 : splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
+  size_t parts = splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
+  if (heavy) parts = std::max<size_t>(parts, heavy_pieces(p).n);
   f.o_parts = off; off += f.part_o_bytes * parts;
   f.lse_parts = off; off += f.part_lse_bytes * parts;
   f.total = off;
@@ -560,33 +615,33 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
       // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
       const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
       const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * es;
-      const HeavySplit heavy = heavy_split(*p);
-      if (heavy.tiles) {
-        // Medium length (R = 1): the last heavy.tiles query tiles in two items each, one per half of the keys, with
-        // partial results; every other tile a whole item of the same launch that writes its finished rows itself.
-        // Then the merge of the cut rows, straight to the sequence-layout shards.
-        const void* kp[2];
-        const void* vp[2];
-        usp_posdesc pd[2];
-        int lk[2];
-        float* o_ptrs[2];
-        float* l_ptrs[2];
-        for (int n = 0; n < 2; ++n) {
-          const int64_t a0 = n == 0 ? 0 : heavy.cut, a1 = n == 0 ? heavy.cut : Lq;
-          const size_t row_off = (size_t)a0 * hkv * p->hs * es;
-          kp[n] = (const char*)kb[0] + row_off;
-          vp[n] = (const char*)vb[0] + row_off;
-          pd[n] = piece_of(kds[0], a0, a1);
-          lk[n] = (int)(a1 - a0);
+      const int heavy = heavy_tiles(*p, r);
+      if (heavy > 0) {
+        // Medium length: the last `heavy` query tiles as one item per piece of the keys (the halves of the one block, or
+        // the ring blocks), with partial results; every other tile a whole item of the same launch that writes its
+        // finished rows itself.  Then the merge of the cut rows, straight to the sequence-layout shards.
+        const HeavyPieces hp = heavy_pieces(*p);
+        const void* kp[kMaxHeavyPieces];
+        const void* vp[kMaxHeavyPieces];
+        usp_posdesc pd[kMaxHeavyPieces];
+        int lk[kMaxHeavyPieces];
+        float* o_ptrs[kMaxHeavyPieces];
+        float* l_ptrs[kMaxHeavyPieces];
+        for (int n = 0; n < hp.n; ++n) {
+          const size_t row_off = (size_t)hp.first[n] * hkv * p->hs * es;
+          kp[n] = (const char*)kb[hp.block[n]] + row_off;
+          vp[n] = (const char*)vb[hp.block[n]] + row_off;
+          pd[n] = piece_of(kds[hp.block[n]], hp.first[n], hp.last[n]);
+          lk[n] = (int)(hp.last[n] - hp.first[n]);
           o_ptrs[n] = (float*)(ws + f.o_parts + (size_t)n * f.part_o_bytes);
           l_ptrs[n] = (float*)(ws + f.lse_parts + (size_t)n * f.part_lse_bytes);
         }
-        const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy.tiles};
-        st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, 2, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq, hkv,
-                                      p->hs, scale, 1, qd, stream, &seq, &mixed);
+        const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy};
+        st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, hp.n, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq,
+                                      hkv, p->hs, scale, 1, qd, stream, &seq, &mixed);
         if (st != USP_OK) return st;
-        const int64_t row0 = ((Lq + 255) / 256 - heavy.tiles) * 256;
-        st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, 2, (char*)o + group_off, lse_rank,
+        const int64_t row0 = ((Lq + 255) / 256 - heavy) * 256;
+        st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, hp.n, (char*)o + group_off, lse_rank,
                               p->bs, Lq, hq, p->hs, USP_FP32, p->dtype, stream, &seq, row0);
         if (st != USP_OK) return st;
         continue;
