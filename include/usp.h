@@ -208,7 +208,9 @@ int usp_ring_attn_fwd_partials(const void* q, const void* const* k_blocks, const
  * usp_ring_attn_fwd (all blocks are resident on the one GPU); otherwise one usp_block_attn_fwd per ring step
  * with fp32 partials, then usp_lse_merge.  Short sequences (fewer query tiles x heads than keep 256 CUs busy for
  * as long as the last tile takes) run the single launch of usp_ring_attn_fwd_partials over two to eight parts of
- * the keys, then usp_lse_merge; the workspace query knows.
+ * the keys, then usp_lse_merge; a little longer (more than one work item per CU, the heaviest still longer than
+ * a CU's share) only the last query tiles of a causal rank are cut so, in the same launch as the whole ones, and
+ * the merge covers their rows; the workspace query knows.
  *   q, o: seq layout with hc heads; k, v: seq layout with hk heads (ALL N shards must be
  *   present: the ring reads the other ring ranks' K/V where hardware would receive them);
  *   lse: [N][bs][hc/U][L/R] float, written for the ranks in range. */
@@ -218,9 +220,12 @@ int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void*
 
 /* usp_attn_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace), same
- * kernels, same results bit for bit.  The scratch is a static device array of USP_NOALLOC_SCRATCH_BYTES that every
+ * kernels, same results bit for bit (with one exception: where usp_attn_fwd would cut a rank's heaviest query tiles
+ * and the partial results of that cut do not fit the array, the launch stays whole: same attention, another rounding
+ * order).  The scratch is a static device array of USP_NOALLOC_SCRATCH_BYTES that every
  * GPU the library runs on holds until the process ends; the call allocates and frees nothing.  A problem whose
- * usp_attn_fwd workspace (for the Ulysses columns the rank range touches) is larger returns USP_ERR_WORKSPACE and
+ * usp_attn_fwd workspace (for the Ulysses columns the rank range touches; without those optional partials) is
+ * larger returns USP_ERR_WORKSPACE and
  * enqueues nothing: one rank of L = 212992, U 8 x R 2 (104 MiB) fits, a whole 16-rank range of it does not.  All
  * calls on one GPU share the one array: calls that overlap in time on one GPU (different streams) race; calls on
  * one stream are safe.  The array keeps the last call's contents; every region is rewritten before it is read. */

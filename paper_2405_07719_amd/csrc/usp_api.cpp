@@ -474,7 +474,9 @@ bool heavy_any(const usp_problem& p) {
   return false;
 }
 
-FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
+// allow_heavy = false: as if no rank cut its heaviest tiles (the entry point without a workspace of its own falls back
+// to that when the partials would not fit its array).
+FwdPlan plan_fwd(const usp_problem& p, int n_cols, bool allow_heavy = true) {
   FwdPlan f;
   const size_t es = dtype_size(p.dtype);
   const size_t Lq = p.L / p.ring, hq = p.hc / p.ulysses, hkv = p.hk / p.ulysses;
@@ -488,7 +490,7 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols) {
   const size_t qo = ring_in_one_launch(p) ? 0 : qb;
   f.q_head = off; off += qo;
   f.o_head = off; off += qo;
-  const bool heavy = heavy_any(p);
+  const bool heavy = allow_heavy && heavy_any(p);
   const int splits = key_splits(p);
   // The one-launch ring loop (not the key-split launches, whose instances read V rows) takes V in
   // key-tile-transposed layout: tiles of 64 keys, the last one padded.
@@ -563,7 +565,8 @@ extern "C" size_t usp_attn_fwd_workspace_bytes(const usp_problem* p, int n_ranks
 
 namespace {
 int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
-                  int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream_) {
+                  int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream_,
+                  bool allow_heavy = true) {
   int st = usp_validate(p);
   if (st != USP_OK) return st;
   if (!q || !k || !v || !o || !lse) return USP_ERR_NULL;
@@ -571,7 +574,7 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
   if (rank_begin < 0 || rank_end > N || rank_begin >= rank_end) return USP_ERR_UNSUPPORTED;
   int c0, c1;
   column_range(*p, rank_begin, rank_end, &c0, &c1);
-  const FwdPlan f = plan_fwd(*p, c1 - c0);
+  const FwdPlan f = plan_fwd(*p, c1 - c0, allow_heavy);
   if (!workspace || workspace_bytes < f.total) return USP_ERR_WORKSPACE;
   if ((uintptr_t)workspace & 255) return USP_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
@@ -615,7 +618,7 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
       // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
       const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
       const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * es;
-      const int heavy = heavy_tiles(*p, r);
+      const int heavy = allow_heavy ? heavy_tiles(*p, r) : 0;
       if (heavy > 0) {
         // Medium length: the last `heavy` query tiles as one item per piece of the keys (the halves of the one block, or
         // the ring blocks), with partial results; every other tile a whole item of the same launch that writes its
@@ -756,11 +759,13 @@ extern "C" int usp_attn_fwd_noalloc(const usp_problem* p, const void* q, const v
   if (rank_begin < 0 || rank_end > N || rank_begin >= rank_end) return USP_ERR_UNSUPPORTED;
   int c0, c1;
   column_range(*p, rank_begin, rank_end, &c0, &c1);
-  if (plan_fwd(*p, c1 - c0).total > USP_NOALLOC_SCRATCH_BYTES) return USP_ERR_WORKSPACE;   // beyond the static array
+  // the partial results of a cut of the heaviest tiles are optional: without room for them the launch stays whole
+  const bool heavy_fits = plan_fwd(*p, c1 - c0, true).total <= USP_NOALLOC_SCRATCH_BYTES;
+  if (!heavy_fits && plan_fwd(*p, c1 - c0, false).total > USP_NOALLOC_SCRATCH_BYTES) return USP_ERR_WORKSPACE;   // beyond the static array
   void* ptr = scratch_on_current_device();
   if (!ptr) return USP_ERR_LAUNCH;
   // every region of the workspace is written by a kernel of the call before a kernel reads it: nothing to clear
-  return attn_fwd_impl(p, q, k, v, o, lse, rank_begin, rank_end, ptr, USP_NOALLOC_SCRATCH_BYTES, stream);
+  return attn_fwd_impl(p, q, k, v, o, lse, rank_begin, rank_end, ptr, USP_NOALLOC_SCRATCH_BYTES, stream, heavy_fits);
 }
 
 extern "C" int usp_attn_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,

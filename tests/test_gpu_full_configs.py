@@ -41,6 +41,8 @@ def _check_forward_rows(case, rows):
     ("medium_20480_last_tiles_cut", 20480, 8, 1, 0, 192),
     ("medium_24576_last_tiles_cut", 24576, 8, 1, 5, 192),
     ("medium_28672", 28672, 8, 1, 0, 64),
+    ("medium_ring4_98304_last_tiles_cut_per_block", 98304, 8, 4, 0, 192),   # pieces = the four ring blocks
+    ("medium_ring4_98304_rank_left_whole", 98304, 8, 4, 9, 64),             # ring rank 1 of the same problem: not cut
 ])
 def test_full_size_forward_one_rank(usp, name, L, U, R, rank, samples):
     case = tl.OneRankCase(usp, 1000 + len(name), 1, L, 32, 8, 128, U, R, rank)

@@ -53,3 +53,24 @@ def test_noalloc_forward_rejects_problems_beyond_the_static_array(usp):
     assert e.value.status == 5
     with pytest.raises(usp.UspError):
         usp.usp_attn_fwd_noalloc(p, x, x, x, x, x, 3, 3)       # empty rank range
+
+
+def test_noalloc_forward_without_room_for_optional_partials(usp):
+    """A rank whose heaviest query tiles usp_attn_fwd cuts into one item per ring block (four fp32 partial results, 240
+    MiB of workspace in all): the entry point without a workspace has no room for those, leaves the launch whole and
+    still gives the same attention (both against the oracle on sampled rows; the two differ only by rounding order)."""
+    import tests.test_gpu_full_configs as full
+    case = tl.OneRankCase(usp, 1234, 1, 98304, 32, 8, 128, 8, 4, 0)
+    assert usp.usp_attn_fwd_workspace_bytes(case.p, 1) > usp.USP_NOALLOC_SCRATCH_BYTES
+    case.forward()
+    rows = case.sample_rows(np.random.default_rng(9), 96)
+    full._check_forward_rows(case, rows)
+    o_ws, lse_ws = case.o, case.lse
+    case.o = torch.zeros_like(case.q)
+    case.lse = torch.zeros_like(lse_ws)
+    usp.usp_attn_fwd_noalloc(case.p, case.q, case.k, case.v, case.o, case.lse, case.rank, case.rank + 1)
+    torch.cuda.synchronize()
+    full._check_forward_rows(case, rows)
+    assert float((case.o.float() - o_ws.float()).abs().max()) <= 2e-2
+    assert float((case.lse[case.rank] - lse_ws[case.rank]).abs().max()) <= 1e-3
+
