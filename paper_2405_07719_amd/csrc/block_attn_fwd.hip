@@ -120,7 +120,7 @@ template <int HS, int NQB, int NWAVES, int KT, int WPE, typename OutT, bool STAT
 __global__ __attribute__((amdgpu_flat_work_group_size(NWAVES * 64, NWAVES * 64), amdgpu_waves_per_eu(WPE, WPE)))
 void block_attn_fwd_mfma(const AttnArgs) {
   static_assert(!STATE || NQB == 1, "the state record is laid out for one 32-row block per wave");
-  static_assert(!MIXED || (!STATE && !VT && sizeof(OutT) == 2), "the mixed launch writes bf16 results and fp32 partials");
+  static_assert(!MIXED || (!STATE && sizeof(OutT) == 2), "the mixed launch writes bf16 results and fp32 partials");
   static_assert(!VT || KT == 64, "the transposed V layout is made of 64-key tiles");
   constexpr int NT = NWAVES * 64;
   constexpr int BM = NWAVES * NQB * 32;
@@ -824,6 +824,9 @@ int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const v
                              float scale, int causal, const usp_posdesc& qpos, hipStream_t stream,
                              const SeqLayoutIO* seq, const MixedLaunch* mixed) {
   if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
+  if (mixed && mixed->v_transposed)   // a piece of transposed tiles begins with a whole tile, 16-byte aligned
+    for (int j = 0; j < n_blocks; ++j)
+      if ((uintptr_t)v_blocks[j] & 15) return USP_ERR_UNSUPPORTED;
   AttnArgs a;
   a.seq_n = seq ? seq->rows_per_shard : 0;
   a.seq_heads = seq ? seq->heads : 0;
@@ -860,6 +863,9 @@ int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const v
     a.lse = mixed->lse;
     a.per_block = 0;
     a.n_split_tiles = mixed->n_split_tiles;
+    if (mixed->v_transposed)
+      return hs == 128 ? launch_mfma<128, 1, 8, 64, 2, __bf16, false, true, true>(a, stream)
+                       : launch_mfma<64, 1, 8, 64, 2, __bf16, false, true, true>(a, stream);
     return hs == 128 ? launch_mfma<128, 1, 8, 64, 2, __bf16, false, false, true>(a, stream)
                      : launch_mfma<64, 1, 8, 64, 2, __bf16, false, false, true>(a, stream);
   }

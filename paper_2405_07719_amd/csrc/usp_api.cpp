@@ -492,9 +492,9 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols, bool allow_heavy = true) {
   f.o_head = off; off += qo;
   const bool heavy = allow_heavy && heavy_any(p);
   const int splits = key_splits(p);
-  // The one-launch ring loop (not the key-split launches, whose instances read V rows) takes V in
-  // key-tile-transposed layout: tiles of 64 keys, the last one padded.
-  f.v_transposed = ring_in_one_launch(p) && splits == 0 && !heavy;
+  // The one-launch ring loop and the launch that cuts only the heaviest tiles (not the launch that cuts every tile,
+  // whose fp32 instance reads V rows) take V in key-tile-transposed layout: tiles of 64 keys, the last one padded.
+  f.v_transposed = ring_in_one_launch(p) && splits == 0;
   f.v_block_bytes = f.v_transposed ? vt_block_bytes(p.bs, (int64_t)Lq, (int)hkv, p.hs) : f.kv_block_bytes;
   f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.v_head = off; off += up256(f.v_block_bytes * p.ring * n_cols);
@@ -633,13 +633,14 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
         for (int n = 0; n < hp.n; ++n) {
           const size_t row_off = (size_t)hp.first[n] * hkv * p->hs * es;
           kp[n] = (const char*)kb[hp.block[n]] + row_off;
-          vp[n] = (const char*)vb[hp.block[n]] + row_off;
+          // (transposed tiles: a piece begins hp.first / 64 tiles into every head's run of tiles)
+          vp[n] = (const char*)vb[hp.block[n]] + (f.v_transposed ? (size_t)(hp.first[n] / 64) * p->hs * 64 * es : row_off);
           pd[n] = piece_of(kds[hp.block[n]], hp.first[n], hp.last[n]);
           lk[n] = (int)(hp.last[n] - hp.first[n]);
           o_ptrs[n] = (float*)(ws + f.o_parts + (size_t)n * f.part_o_bytes);
           l_ptrs[n] = (float*)(ws + f.lse_parts + (size_t)n * f.part_lse_bytes);
         }
-        const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy};
+        const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy, f.v_transposed};
         st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, hp.n, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq,
                                       hkv, p->hs, scale, 1, qd, stream, &seq, &mixed);
         if (st != USP_OK) return st;

@@ -106,7 +106,9 @@ int launch_layout_a2a_vt(const usp_problem& p, int heads, const void* src, void*
 // causal mask, the first ones otherwise) are cut so; the other query tiles are whole items of the same launch that walk
 // all blocks and write their finished rows (bf16, through `seq` when given) to mixed->o and mixed->lse.  The partials
 // then hold the rows of the cut tiles only, to be merged over that row range.
-struct MixedLaunch { void* o; float* lse; int n_split_tiles; };
+// v_transposed: the V pointers are pieces of blocks in key-tile-transposed layout (each begins at a tile of 64 keys of
+// its block; Lk, the batch stride in rows, then also gives the number of tiles per head of a whole block).
+struct MixedLaunch { void* o; float* lse; int n_split_tiles; bool v_transposed; };
 int launch_attn_fwd_partials(const void* q, const void* const* k_blocks, const void* const* v_blocks,
                              const usp_posdesc* kpos_blocks, const int* lk_blocks, int n_blocks, float* const* o_parts,
                              float* const* lse_parts, int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs,
