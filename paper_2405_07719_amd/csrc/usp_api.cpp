@@ -452,8 +452,7 @@ int heavy_tiles(const usp_problem& p, int r) {
   };
   // A cut has to pay for itself: 3 % by this model when the pieces are the halves of one block, where the model's
   // choice was the measured optimum at every length tried; 8 % when they are ring blocks of unequal visible parts,
-  // where it promises 5 % more than is measured (the uncut launch's long tail runs on few CUs at a higher clock, and
-  // the cut launch reads V as rows, not as transposed tiles).
+  // where it promises 5 % more than is measured (the uncut launch's long tail runs on few CUs at a higher clock).
   const double need = p.ring == 1 ? 0.97 : 0.92;
   const double uncut_us = launch_time(0);
   int best = 0;
