@@ -347,27 +347,29 @@ int key_splits(const usp_problem& p) {
   return s * p.ring > 1 ? (int)s : 0;
 }
 
-// Between the two regimes (more than one work item per CU, yet the heaviest item longer than a CU's fair share: a
-// causal rank of four heads with 18000 ... 28000 queries) only the heaviest query tiles are cut: the LAST `tiles` query
-// tiles of the rank run as one item per piece of the keys (the two halves of the one block when R = 1, else the R ring
-// blocks), with fp32 partial results that are merged afterwards; the other tiles stay whole items of the same launch
-// (launch_attn_fwd_partials with MixedLaunch).  How many tiles, if any, is decided by playing the launch through on
-// the host: the kernel's own dealing (the first items given one per workgroup, the rest drawn in order by whoever is
-// free), 8 us per item, 1.85 us per tile of 64 keys, 3 us each time a whole item moves on to another piece, and the
-// merge of the cut rows at 5 TB/s + 10 us.  Host arithmetic only; the same for every Ulysses column of a ring row.
+// Short of full grids (fewer than two work items per CU under a causal mask, the heaviest item longer than a CU's
+// fair share) only the heaviest query tiles may be cut: the LAST `tiles` query tiles of the rank run as one item per
+// piece of the keys (2 to 4 equal pieces of the one block when R = 1, else the R ring blocks), with fp32 partial results
+// that are merged afterwards; the other tiles stay whole items of the same launch (launch_attn_fwd_partials with
+// MixedLaunch).  How many tiles and pieces, if any, is decided by playing the launch through on the host: the kernel's
+// own dealing (the first items given one per workgroup, the rest drawn in order by whoever is free), 8 us per item,
+// 1.85 us per tile of 64 keys, 3 us each time a whole item moves on to another piece, and the merge of the cut rows at
+// 5 TB/s + 10 us.  Host arithmetic only; the same for every Ulysses column of a ring row.
 constexpr int kMaxHeavyPieces = USP_MAX_RING_BLOCKS;
 struct HeavyPieces { int n; int64_t first[kMaxHeavyPieces], last[kMaxHeavyPieces]; int block[kMaxHeavyPieces]; };
+struct HeavyChoice { int tiles, pieces; };   // tiles == 0: nothing is cut this way
 
-// The pieces of ring rank r's keys, in the order its ring loop visits them: piece j = keys [first, last) of the block
-// of ring step block[j].
-HeavyPieces heavy_pieces(const usp_problem& p) {
+// The pieces of a ring rank's keys, in the order its ring loop visits them: piece j = keys [first, last) of the block
+// of ring step block[j].  R = 1: `pieces` equal parts of the one block (multiples of 64 keys); R > 1: the blocks.
+HeavyPieces heavy_pieces(const usp_problem& p, int pieces) {
   HeavyPieces hp;
   const int64_t Lq = p.L / p.ring;
   if (p.ring == 1) {
-    const int64_t cut = ((Lq / 2) + 63) / 64 * 64;
-    hp.n = 2;
-    hp.first[0] = 0; hp.last[0] = cut; hp.block[0] = 0;
-    hp.first[1] = cut; hp.last[1] = Lq; hp.block[1] = 0;
+    const int64_t piece = ((Lq + pieces - 1) / pieces + 63) / 64 * 64;
+    hp.n = 0;
+    for (int64_t a0 = 0; a0 < Lq; a0 += piece, ++hp.n) {
+      hp.first[hp.n] = a0; hp.last[hp.n] = std::min(Lq, a0 + piece); hp.block[hp.n] = 0;
+    }
   } else {
     hp.n = p.ring;
     for (int i = 0; i < p.ring; ++i) { hp.first[i] = 0; hp.last[i] = Lq; hp.block[i] = i; }
@@ -382,35 +384,19 @@ usp_posdesc piece_of(const usp_posdesc& d, int64_t a, int64_t b) {
   return usp_posdesc{d.start0 + a, n0, d.start1, (b - a) - n0};
 }
 
-// Number of query tiles of ring rank r to cut (0: none, leave the launch to key_splits()).
-int heavy_tiles(const usp_problem& p, int r) {
-  if (!ring_in_one_launch(p) || !p.causal) return 0;
+// What ring rank r cuts ({0, 0}: nothing, the launch is key_splits()' business).
+HeavyChoice heavy_choice(const usp_problem& p, int r) {
+  const HeavyChoice none = {0, 0};
+  if (!ring_in_one_launch(p) || !p.causal) return none;
   const int64_t Lq = p.L / p.ring;
   const int T = (int)((Lq + 255) / 256), n = (p.hc / p.ulysses) * p.bs;
   const int64_t items = (int64_t)T * n;
-  if (items <= kPlanCUs || items > 2 * kPlanCUs || Lq < 4096) return 0;
-  const HeavyPieces hp = heavy_pieces(p);
-  usp_posdesc qd, pd[kMaxHeavyPieces];
+  if (items > 2 * kPlanCUs || Lq < 4096 || T < 8) return none;
+  if (p.ring > 1 && items <= kPlanCUs) return none;   // short ring ranks: every tile per block, as key_splits() has it
+  usp_posdesc qd;
   ring_block_desc(p, r, &qd);
-  for (int j = 0; j < hp.n; ++j) {
-    usp_posdesc kd;
-    ring_block_desc(p, ((r - hp.block[j]) % p.ring + p.ring) % p.ring, &kd);
-    pd[j] = piece_of(kd, hp.first[j], hp.last[j]);
-  }
   const double kItem = 8.0, kTile = 1.85, kCross = 3.0;
   auto pos_of = [&](int64_t i) { return i < qd.len0 ? qd.start0 + i : qd.start1 + (i - qd.len0); };
-  // 64-key tiles of piece j that query tile i walks: under kpos <= qpos the visible keys of each run are a prefix of it
-  std::vector<double> tiles((size_t)T * hp.n);
-  for (int i = 0; i < T; ++i) {
-    const int64_t a = (int64_t)i * 256, b = std::min<int64_t>(Lq, a + 256);
-    int64_t qmax = std::max(pos_of(a), pos_of(b - 1));
-    if (a < qd.len0 && b > qd.len0) qmax = std::max({qmax, pos_of(qd.len0 - 1), pos_of(qd.len0)});
-    for (int j = 0; j < hp.n; ++j) {
-      const int64_t c0 = std::clamp<int64_t>(qmax - pd[j].start0 + 1, 0, pd[j].len0);
-      const int64_t c1 = std::clamp<int64_t>(qmax - pd[j].start1 + 1, 0, pd[j].len1);
-      tiles[(size_t)i * hp.n + j] = (double)((c0 + 63) / 64 + (c1 + 63) / 64);
-    }
-  }
   auto play = [&](const std::vector<double>& w) {
     std::vector<double> free_at;   // a min-heap of the workgroups' finish times
     free_at.reserve(kPlanCUs);
@@ -426,7 +412,23 @@ int heavy_tiles(const usp_problem& p, int r) {
     for (double t : free_at) end = std::max(end, t);
     return end;
   };
-  auto launch_time = [&](int k) {   // the last k query tiles cut (k = T: every tile, k = 0: none)
+  // time of the launch with the last k query tiles cut into the pieces hp (k = T: every tile, k = 0: none)
+  auto launch_time = [&](const HeavyPieces& hp, int k) {
+    // 64-key tiles of piece j that query tile i walks: under kpos <= qpos the visible keys of each run are a prefix of it
+    std::vector<double> tiles((size_t)T * hp.n);
+    for (int j = 0; j < hp.n; ++j) {
+      usp_posdesc kd;
+      ring_block_desc(p, ((r - hp.block[j]) % p.ring + p.ring) % p.ring, &kd);
+      const usp_posdesc pd = piece_of(kd, hp.first[j], hp.last[j]);
+      for (int i = 0; i < T; ++i) {
+        const int64_t a = (int64_t)i * 256, b = std::min<int64_t>(Lq, a + 256);
+        int64_t qmax = std::max(pos_of(a), pos_of(b - 1));
+        if (a < qd.len0 && b > qd.len0) qmax = std::max({qmax, pos_of(qd.len0 - 1), pos_of(qd.len0)});
+        const int64_t c0 = std::clamp<int64_t>(qmax - pd.start0 + 1, 0, pd.len0);
+        const int64_t c1 = std::clamp<int64_t>(qmax - pd.start1 + 1, 0, pd.len1);
+        tiles[(size_t)i * hp.n + j] = (double)((c0 + 63) / 64 + (c1 + 63) / 64);
+      }
+    }
     std::vector<double> w;
     w.reserve((size_t)items + (size_t)k * n * hp.n);
     for (int t = 0; t < k; ++t)
@@ -450,27 +452,38 @@ int heavy_tiles(const usp_problem& p, int r) {
     }
     return us;
   };
-  // A cut has to pay for itself: 3 % by this model when the pieces are the halves of one block, where the model's
-  // choice was the measured optimum at every length tried; 8 % when they are ring blocks of unequal visible parts,
-  // where it promises 5 % more than is measured (the uncut launch's long tail runs on few CUs at a higher clock).
-  const double need = p.ring == 1 ? 0.97 : 0.92;
-  const double uncut_us = launch_time(0);
-  int best = 0;
-  double best_us = uncut_us;
-  for (int eighths = 1; eighths <= 8; ++eighths) {
-    const int k = std::max(1, T * eighths / 8);
-    const double us = launch_time(k);
-    if (us < best_us) { best = k; best_us = us; }
+  // what the launch costs as key_splits() has it: whole, or every tile in so many pieces per block
+  const int splits = key_splits(p);
+  const double as_is_us = splits > 0 ? launch_time(heavy_pieces(p, splits), T) : launch_time(heavy_pieces(p, 2), 0);
+  // A cut has to pay for itself: 3 % by this model when the pieces are parts of one block and the launch was whole,
+  // where the model's choice was the measured optimum at every length tried; 8 % when they are ring blocks of unequal
+  // visible parts, where it promises 5 % more than is measured (the uncut launch's long tail runs on few CUs at a
+  // higher clock); 5 % against a launch that already cuts every tile.
+  const double need = p.ring > 1 ? 0.92 : splits > 0 ? 0.95 : 0.97;
+  HeavyChoice best = none;
+  double best_us = as_is_us;
+  for (int pieces = 2; pieces <= (p.ring == 1 ? 4 : 2); ++pieces) {   // (R > 1: the blocks, one pass)
+    if (p.ring == 1 && Lq / pieces < 1024) break;
+    const HeavyPieces hp = heavy_pieces(p, pieces);
+    for (int eighths = 1; eighths < 8; ++eighths) {
+      const int k = std::max(1, T * eighths / 8);
+      const double us = launch_time(hp, k);
+      if (us < best_us) { best = HeavyChoice{k, hp.n}; best_us = us; }
+    }
   }
-  if (best_us >= need * uncut_us) return 0;
-  return best == T ? 0 : best;   // cutting everything is key_splits()' case
+  if (best_us >= need * as_is_us) return none;
+  return best;
 }
 
-// Whether any ring rank of the problem cuts tiles: then V is staged as rows and the workspace holds the partials.
-bool heavy_any(const usp_problem& p) {
-  for (int r = 0; r < p.ring; ++r)
-    if (heavy_tiles(p, r) > 0) return true;
-  return false;
+// The most pieces any ring rank of the problem cuts its heaviest tiles into (0: no rank does): the workspace holds as
+// many partial results.
+int heavy_max_pieces(const usp_problem& p) {
+  int m = 0;
+  for (int r = 0; r < p.ring; ++r) {
+    const HeavyChoice c = heavy_choice(p, r);
+    if (c.tiles > 0) m = std::max(m, c.pieces);
+  }
+  return m;
 }
 
 // allow_heavy = false: as if no rank cut its heaviest tiles (the entry point without a workspace of its own falls back
@@ -489,7 +502,7 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols, bool allow_heavy = true) {
   const size_t qo = ring_in_one_launch(p) ? 0 : qb;
   f.q_head = off; off += qo;
   f.o_head = off; off += qo;
-  const bool heavy = allow_heavy && heavy_any(p);
+  const int heavy = allow_heavy ? heavy_max_pieces(p) : 0;
   const int splits = key_splits(p);
   // The one-launch ring loop and the launch that cuts only the heaviest tiles (not the launch that cuts every tile,
   // whose fp32 instance reads V rows) take V in key-tile-transposed layout: tiles of 64 keys, the last one padded.
@@ -498,7 +511,7 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols, bool allow_heavy = true) {
   f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
   f.v_head = off; off += up256(f.v_block_bytes * p.ring * n_cols);
   size_t parts = splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
-  if (heavy) parts = std::max<size_t>(parts, heavy_pieces(p).n);
+  parts = std::max<size_t>(parts, (size_t)heavy);
   f.o_parts = off; off += f.part_o_bytes * parts;
   f.lse_parts = off; off += f.part_lse_bytes * parts;
   f.total = off;
@@ -617,12 +630,12 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
       // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
       const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
       const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * es;
-      const int heavy = allow_heavy ? heavy_tiles(*p, r) : 0;
-      if (heavy > 0) {
+      const HeavyChoice heavy = allow_heavy ? heavy_choice(*p, r) : HeavyChoice{0, 0};
+      if (heavy.tiles > 0) {
         // Medium length: the last `heavy` query tiles as one item per piece of the keys (the halves of the one block, or
         // the ring blocks), with partial results; every other tile a whole item of the same launch that writes its
         // finished rows itself.  Then the merge of the cut rows, straight to the sequence-layout shards.
-        const HeavyPieces hp = heavy_pieces(*p);
+        const HeavyPieces hp = heavy_pieces(*p, heavy.pieces);
         const void* kp[kMaxHeavyPieces];
         const void* vp[kMaxHeavyPieces];
         usp_posdesc pd[kMaxHeavyPieces];
@@ -639,11 +652,11 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
           o_ptrs[n] = (float*)(ws + f.o_parts + (size_t)n * f.part_o_bytes);
           l_ptrs[n] = (float*)(ws + f.lse_parts + (size_t)n * f.part_lse_bytes);
         }
-        const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy, f.v_transposed};
+        const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy.tiles, f.v_transposed};
         st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, hp.n, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq,
                                       hkv, p->hs, scale, 1, qd, stream, &seq, &mixed);
         if (st != USP_OK) return st;
-        const int64_t row0 = ((Lq + 255) / 256 - heavy) * 256;
+        const int64_t row0 = ((Lq + 255) / 256 - heavy.tiles) * 256;
         st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, hp.n, (char*)o + group_off, lse_rank,
                               p->bs, Lq, hq, p->hs, USP_FP32, p->dtype, stream, &seq, row0);
         if (st != USP_OK) return st;
