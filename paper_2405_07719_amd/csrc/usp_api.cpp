@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <functional>
+#include <mutex>
 #include <string.h>
 #include <vector>
 
@@ -384,8 +385,9 @@ usp_posdesc piece_of(const usp_posdesc& d, int64_t a, int64_t b) {
   return usp_posdesc{d.start0 + a, n0, d.start1, (b - a) - n0};
 }
 
-// What ring rank r cuts ({0, 0}: nothing, the launch is key_splits()' business).
-HeavyChoice heavy_choice(const usp_problem& p, int r) {
+// What ring rank r cuts ({0, 0}: nothing, the launch is key_splits()' business).  (Worked out once per problem:
+// heavy_choice() below keeps the answers.)
+HeavyChoice work_out_heavy_choice(const usp_problem& p, int r) {
   const HeavyChoice none = {0, 0};
   if (!ring_in_one_launch(p) || !p.causal) return none;
   const int64_t Lq = p.L / p.ring;
@@ -473,6 +475,26 @@ HeavyChoice heavy_choice(const usp_problem& p, int r) {
   }
   if (best_us >= need * as_is_us) return none;
   return best;
+}
+
+// Playing a launch through takes the host 0.1-0.3 ms per ring rank, as long as a short launch itself: the answers
+// for the last problems seen are kept (every ring rank's, worked out at the first question about the problem).
+HeavyChoice heavy_choice(const usp_problem& p, int r) {
+  struct Entry { usp_problem p; std::vector<HeavyChoice> per_rank; };
+  static std::mutex mu;
+  static std::vector<Entry> seen;
+  auto same = [](const usp_problem& a, const usp_problem& b) {
+    return a.bs == b.bs && a.L == b.L && a.hc == b.hc && a.hk == b.hk && a.hs == b.hs && a.ulysses == b.ulysses &&
+           a.ring == b.ring && a.causal == b.causal && a.split == b.split && a.dtype == b.dtype;   // (the scale plays no part)
+  };
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : seen)
+    if (same(e.p, p)) return e.per_rank[r];
+  if (seen.size() >= 64) seen.erase(seen.begin());
+  Entry e{p, {}};
+  for (int rr = 0; rr < p.ring; ++rr) e.per_rank.push_back(work_out_heavy_choice(p, rr));
+  seen.push_back(e);
+  return seen.back().per_rank[r];
 }
 
 // The most pieces any ring rank of the problem cuts its heaviest tiles into (0: no rank does): the workspace holds as
