@@ -132,3 +132,17 @@ def test_loading_the_binding_first_leaves_one_hip_runtime_in_the_process():
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
     assert out.returncode == 0, out.stderr[-500:]
     assert out.stdout.strip() == "1"
+
+
+def test_planning_a_known_problem_again_costs_the_host_next_to_nothing(usp):
+    """usp_attn_fwd plans at every call; for medium lengths that includes playing the launch through on the host
+    (a fraction of a millisecond), which is done once per problem and kept: repeated calls must not pay it again."""
+    import time
+    problems = [usp.problem(1, L, 32, 8, 128, 8, 1, True) for L in (20480, 24576, 32768)] + [usp.problem(1, 32768, 32, 8, 128, 1, 8, True)]
+    for p in problems:
+        usp.usp_attn_fwd_workspace_bytes(p, 1)
+    t0 = time.perf_counter()
+    for _ in range(200):
+        for p in problems:
+            usp.usp_attn_fwd_workspace_bytes(p, 1)
+    assert (time.perf_counter() - t0) / 800 < 50e-6
