@@ -206,7 +206,8 @@ void block_attn_fwd_mfma(const AttnArgs) {
     } else if constexpr (MIXED) {
       t += ap->n_split_tiles;
     }
-    const int qtile = a.causal ? a.n_qtiles - 1 - t : t;
+    // (a mixed launch counts its tiles from the last one down whatever the mask: its cut tiles are the last rows)
+    const int qtile = (a.causal || MIXED) ? a.n_qtiles - 1 - t : t;
     const int b = group / a.hkv, kvh = group % a.hkv;
     const int h = kvh * a.g + hg;
 

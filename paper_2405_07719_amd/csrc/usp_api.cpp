@@ -389,12 +389,15 @@ usp_posdesc piece_of(const usp_posdesc& d, int64_t a, int64_t b) {
 // heavy_choice() below keeps the answers.)
 HeavyChoice work_out_heavy_choice(const usp_problem& p, int r) {
   const HeavyChoice none = {0, 0};
-  if (!ring_in_one_launch(p) || !p.causal) return none;
+  if (!ring_in_one_launch(p)) return none;
   const int64_t Lq = p.L / p.ring;
   const int T = (int)((Lq + 255) / 256), n = (p.hc / p.ulysses) * p.bs;
   const int64_t items = (int64_t)T * n;
   if (items > 2 * kPlanCUs || Lq < 4096 || T < 8) return none;
   if (p.ring > 1 && items <= kPlanCUs) return none;   // short ring ranks: every tile per block, as key_splits() has it
+  // Without a mask all items weigh the same and what is lost is the last, partly filled round (320 items on 256 CUs
+  // take two rounds): the cut tiles' pieces then fill the first round and the whole items follow.
+  if (!p.causal && items <= kPlanCUs) return none;
   usp_posdesc qd;
   ring_block_desc(p, r, &qd);
   const double kItem = 8.0, kTile = 1.85, kCross = 3.0;
@@ -426,8 +429,8 @@ HeavyChoice work_out_heavy_choice(const usp_problem& p, int r) {
         const int64_t a = (int64_t)i * 256, b = std::min<int64_t>(Lq, a + 256);
         int64_t qmax = std::max(pos_of(a), pos_of(b - 1));
         if (a < qd.len0 && b > qd.len0) qmax = std::max({qmax, pos_of(qd.len0 - 1), pos_of(qd.len0)});
-        const int64_t c0 = std::clamp<int64_t>(qmax - pd.start0 + 1, 0, pd.len0);
-        const int64_t c1 = std::clamp<int64_t>(qmax - pd.start1 + 1, 0, pd.len1);
+        const int64_t c0 = p.causal ? std::clamp<int64_t>(qmax - pd.start0 + 1, 0, pd.len0) : pd.len0;
+        const int64_t c1 = p.causal ? std::clamp<int64_t>(qmax - pd.start1 + 1, 0, pd.len1) : pd.len1;
         tiles[(size_t)i * hp.n + j] = (double)((c0 + 63) / 64 + (c1 + 63) / 64);
       }
     }
@@ -676,7 +679,7 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
         }
         const MixedLaunch mixed = {(char*)o + group_off, lse_rank, heavy.tiles, f.v_transposed};
         st = launch_attn_fwd_partials((const char*)q + group_off, kp, vp, pd, lk, hp.n, o_ptrs, l_ptrs, p->bs, Lq, Lq, hq,
-                                      hkv, p->hs, scale, 1, qd, stream, &seq, &mixed);
+                                      hkv, p->hs, scale, p->causal ? 1 : 0, qd, stream, &seq, &mixed);
         if (st != USP_OK) return st;
         const int64_t row0 = ((Lq + 255) / 256 - heavy.tiles) * 256;
         st = launch_lse_merge((const void* const*)o_ptrs, (const float* const*)l_ptrs, hp.n, (char*)o + group_off, lse_rank,

@@ -102,8 +102,8 @@ int launch_layout_a2a_vt(const usp_problem& p, int heads, const void* src, void*
 // Key split: the same query rows against n_blocks blocks, every (query tile, head, batch, block) its own work item of
 // ONE launch, each block's result (fp32 O, LSE) in its own partial, to be merged by launch_lse_merge.  Block j holds
 // lk_blocks[j] <= Lk keys (all Lk when lk_blocks is null); Lk is the batch stride, in rows, of every block's tensors.
-// With `mixed`, only the n_split_tiles query tiles that come first in item order (the LAST tiles of the block under a
-// causal mask, the first ones otherwise) are cut so; the other query tiles are whole items of the same launch that walk
+// With `mixed`, only the LAST n_split_tiles query tiles of the block (first in item order, the heaviest under a causal
+// mask) are cut so; the other query tiles are whole items of the same launch that walk
 // all blocks and write their finished rows (bf16, through `seq` when given) to mixed->o and mixed->lse.  The partials
 // then hold the rows of the cut tiles only, to be merged over that row range.
 // v_transposed: the V pointers are pieces of blocks in key-tile-transposed layout (each begins at a tile of 64 keys of

@@ -192,6 +192,7 @@ def test_usp_fwd_causal_gqa_all_factorisations(usp, U, R, zigzag):
     ("heavy_tiles_cut_batch_of_two", 2, 4608, 8, 2, 128, 1, 1, True),      # 6 of 18 tiles cut
     ("heavy_tiles_cut_ring_of_two", 1, 9216, 16, 4, 128, 1, 2, True),      # the pieces are the two ring blocks
     ("heavy_tiles_cut_short_four_pieces", 1, 6144, 8, 2, 128, 2, 1, True), # fewer items than CUs: 18 of 24 tiles in 4 pieces
+    ("tiles_cut_noncausal_to_fill_the_last_round", 1, 5120, 16, 4, 128, 1, 1, False),   # 320 equal items on 256 CUs
 ])
 def test_usp_fwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
     prob = tl.Problem(300 + len(name), bs, L, hc, hk, hs, U, R, causal, True, tl.BF16)
