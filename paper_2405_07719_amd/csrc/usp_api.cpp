@@ -393,7 +393,7 @@ HeavyChoice work_out_heavy_choice(const usp_problem& p, int r) {
   const int64_t Lq = p.L / p.ring;
   const int T = (int)((Lq + 255) / 256), n = (p.hc / p.ulysses) * p.bs;
   const int64_t items = (int64_t)T * n;
-  if (items > 2 * kPlanCUs || Lq < 4096 || T < 8) return none;
+  if (items > 4 * kPlanCUs || Lq < 4096 || T < 8) return none;
   if (p.ring > 1 && items <= kPlanCUs) return none;   // short ring ranks: every tile per block, as key_splits() has it
   // Without a mask all items weigh the same and what is lost is the last, partly filled round (320 items on 256 CUs
   // take two rounds): the cut tiles' pieces then fill the first round and the whole items follow.
@@ -470,8 +470,9 @@ HeavyChoice work_out_heavy_choice(const usp_problem& p, int r) {
   for (int pieces = 2; pieces <= (p.ring == 1 ? 4 : 2); ++pieces) {   // (R > 1: the blocks, one pass)
     if (p.ring == 1 && Lq / pieces < 1024) break;
     const HeavyPieces hp = heavy_pieces(p, pieces);
-    for (int eighths = 1; eighths < 8; ++eighths) {
-      const int k = std::max(1, T * eighths / 8);
+    for (int part = 1; part < 32; ++part) {   // k in steps of T / 32
+      const int k = std::max(1, T * part / 32);
+      if (part > 1 && k == std::max(1, T * (part - 1) / 32)) continue;
       const double us = launch_time(hp, k);
       if (us < best_us) { best = HeavyChoice{k, hp.n}; best_us = us; }
     }

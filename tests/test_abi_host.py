@@ -95,8 +95,11 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     # two, which takes K and V as rows (5 MiB each) + 2 fp32 partial O (40 MiB each) + 2 partial LSE (320 KiB each) ...
     medium = usp.problem(1, 20480, 32, 8, 128, 8, 1, True)
     assert usp.usp_attn_fwd_workspace_bytes(medium, 1) == 2 * 5 * 2**20 + 2 * 40 * 2**20 + 2 * 320 * 2**10
-    # ... a little longer and nothing is cut (K rows and transposed V tiles, 7 MiB each)
-    assert usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 28672, 32, 8, 128, 8, 1, True), 1) == 2 * 7 * 2**20
+    # ... longer still (448 items) a few tiles in three pieces (K rows and transposed V tiles of 7 MiB, 3 partials of
+    # 56 MiB + 448 KiB), and from two items per CU on nothing (K and V, 8 MiB each)
+    assert (usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 28672, 32, 8, 128, 8, 1, True), 1)
+            == 2 * 7 * 2**20 + 3 * (56 * 2**20 + 448 * 2**10))
+    assert usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 32768, 32, 8, 128, 8, 1, True), 1) == 2 * 8 * 2**20
     # without the causal mask the 320 items weigh the same and the second, quarter-filled round is what is lost:
     # some tiles in three pieces fill the first round instead (three partials)
     assert (usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 20480, 32, 8, 128, 8, 1, False), 1)
