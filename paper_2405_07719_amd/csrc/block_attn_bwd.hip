@@ -999,7 +999,7 @@ int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64
 // per CU likewise into slices of their query tiles (at least 16 tiles of 32 rows), and up to eight per CU into two
 // slices when an item walks several heads (long items, few copies); one head per item and two or more items per CU
 // are left alone (config 2: 8 copies of dK/dV instead of 4 cost 1 %).
-BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_blocks, bool cut_items) {
+BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_blocks, bool cut_items, bool equal_items) {
   BwdCut c;
   const int g = hq / hkv;
   const int64_t unsplit = ((Lk + 255) / 256) * hkv * bs * n_blocks;
@@ -1020,6 +1020,23 @@ BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_block
       c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>({4, (2 * kPlanCUs + dkdv_items - 1) / dkdv_items, query_tiles / 16}));
     else if (dkdv_items < 8 * kPlanCUs && c.heads_per_wg > 1)
       c.q_splits = (int)std::max<int64_t>(1, std::min<int64_t>(2, query_tiles / 16));
+    if (equal_items) {
+      // Without a mask every item of a kernel weighs the same and the time is rounds of kPlanCUs items: s slices make
+      // ceil(items x s / CUs) rounds of 1/s each (320 items: 2, 1.5, 1.33, 1.25 for 1 ... 4 slices).  The fewest slices
+      // within 3 % of the best, each further slice charged 2 % for its copy of the output (measured, one rank of four
+      // heads: L = 12288 1.22 -> 1.06 ms with 4 + 4 slices instead of 2 + 2, L = 20480 2.95 -> 2.73, L = 28672 5.39 -> 5.20).
+      auto slices = [](int64_t items, int64_t max_slices) {
+        int best = 1;
+        double best_t = 1e30;
+        for (int s = 1; s <= max_slices; ++s) {
+          const double t = (double)((items * s + kPlanCUs - 1) / kPlanCUs) / s * (1.0 + 0.02 * (s - 1));
+          if (t < 0.97 * best_t) { best = s; best_t = t; }
+        }
+        return best;
+      };
+      c.k_splits = slices(dq_items, std::max<int64_t>(1, std::min<int64_t>(4, key_tiles / 32)));
+      c.q_splits = slices(dkdv_items, std::max<int64_t>(1, std::min<int64_t>(4, query_tiles / 16)));
+    }
   }
   return c;
 }
@@ -1032,7 +1049,7 @@ int launch_ring_attn_bwd(const void* q, const void* const* k_blocks, const void*
                          hipStream_t stream, const BwdCopies* copies) {
   if (n_blocks < 1 || n_blocks > kMaxBlocks) return USP_ERR_UNSUPPORTED;
   // without room for copies: items are not cut, and heads that are split over workgroups meet through atomic adds
-  const BwdCut cut = copies ? copies->cut : plan_bwd_cut(bs, Lq, Lk, hq, hkv, n_blocks, false);
+  const BwdCut cut = copies ? copies->cut : plan_bwd_cut(bs, Lq, Lk, hq, hkv, n_blocks, false, false);
   BwdArgs a;
   a.k_splits = cut.k_splits;
   a.q_splits = cut.q_splits;

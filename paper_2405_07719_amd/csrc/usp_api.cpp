@@ -865,7 +865,7 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   const size_t qb = up256(q_elems * es);
   f.kv_block_bytes = kv_elems * es;   // exact: blocks are packed back to back
   // every launch pair of this problem is cut the same way (that of its largest launch: up to 16 blocks)
-  f.copies.cut = plan_bwd_cut(p.bs, (int64_t)Lq, (int64_t)Lq, (int)hq, (int)hkv, std::min(p.ring, USP_MAX_RING_BLOCKS), true);
+  f.copies.cut = plan_bwd_cut(p.bs, (int64_t)Lq, (int64_t)Lq, (int)hq, (int)hkv, std::min(p.ring, USP_MAX_RING_BLOCKS), true, !p.causal);
   f.copies.dq_stride = q_elems;
   f.copies.dkdv_stride = kv_elems;
   f.dkdv_copies = (int)(hq / hkv) / f.copies.cut.heads_per_wg * f.copies.cut.q_splits;
@@ -1055,7 +1055,7 @@ struct RingBwdWs {
 
 RingBwdWs plan_ring_bwd_ws(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int hs, int n_blocks) {
   RingBwdWs w;
-  w.copies.cut = plan_bwd_cut(bs, Lq, Lk, hq, hkv, n_blocks, true);
+  w.copies.cut = plan_bwd_cut(bs, Lq, Lk, hq, hkv, n_blocks, true, false);
   w.copies.dq_stride = (size_t)bs * Lq * hq * hs;
   w.copies.dkdv_stride = (size_t)bs * Lk * hkv * hs;
   w.dkdv_copies = (hq / hkv) / w.copies.cut.heads_per_wg * w.copies.cut.q_splits;

@@ -123,7 +123,8 @@ int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64
 // How a backward launch pair divides its work (plan_bwd_cut): query heads of a KV group walked by one dK/dV
 // workgroup, slices of a dQ item's key tiles, slices of a dK/dV item's query tiles.
 struct BwdCut { int heads_per_wg, k_splits, q_splits; };
-BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_blocks, bool cut_items);
+// equal_items: no causal mask (usp_attn_bwd knows; the per-call entry points, whose workspace query does not, say false).
+BwdCut plan_bwd_cut(int bs, int64_t Lq, int64_t Lk, int hq, int hkv, int n_blocks, bool cut_items, bool equal_items);
 // Room for copies of the outputs, one per slice: dq holds cut.k_splits copies dq_stride elements apart, every block's
 // dk and dv hold (hq / hkv / cut.heads_per_wg) * cut.q_splits copies dkdv_stride elements apart; every copy is
 // written (or added to, as the accumulate flags say) in full, nothing is atomic; launch_bwd_convert adds them up.
