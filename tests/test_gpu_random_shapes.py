@@ -197,3 +197,36 @@ def test_usp_fwd_bwd_random_problems(usp, seed):
         for rank in range(prob.N):
             pos = orc.zigzag_positions(L, R, U, rank // U, rank % U, zigzag)
             assert tl.max_abs(gg[rank], ref[:, pos]) <= 5e-2, (what, name, rank)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_usp_fwd_random_medium_problems_sampled_rows(usp, seed):
+    """One rank of a randomly drawn problem of 64 ... 1024 work items (query tiles x heads x batch), causal or not,
+    lengths that are no multiple of the tile sizes: where usp_attn_fwd cuts some or all query tiles into pieces of the
+    keys (partial results, merged) or leaves the launch whole.  Sampled rows against the oracle's plain attention."""
+    rng = np.random.default_rng(9000 + seed)
+    while True:
+        U = int(rng.choice([1, 2, 4, 8]))
+        R = int(rng.choice([1, 1, 1, 2, 4]))
+        hk = U * int(rng.choice([1, 2]))
+        hc = hk * int(rng.choice([1, 2, 4]))
+        hs = int(rng.choice([64, 128]))
+        bs = int(rng.choice([1, 1, 2]))
+        causal = bool(rng.random() < 0.6)
+        tiles = max(8, int(rng.integers(64, 1024)) // (hc // U * bs))
+        L = (tiles * 256 - int(rng.choice([0, 0, 64, 200]))) * R
+        if L % (2 * U * R) == 0 and L <= 70000 and L * hc * bs <= 3_000_000:
+            break
+    rank = int(rng.integers(0, U * R))
+    case = tl.OneRankCase(usp, 9000 + seed, bs, L, hc, hk, hs, U, R, rank)
+    case.p = usp.problem(bs, L, hc, hk, hs, U, R, causal, usp.USP_SPLIT_ZIGZAG, usp.USP_BF16)
+    case.forward()
+    rows = case.sample_rows(rng, 48)
+    pos, allpos = case.block_pos[rows], np.arange(L)
+    ref_o, ref_l = orc.attention_rows(case.values(inputs.TENSOR_Q, pos, case.q_heads), pos,
+                                      case.values(inputs.TENSOR_K, allpos, case.kv_heads),
+                                      case.values(inputs.TENSOR_V, allpos, case.kv_heads), causal)
+    got_o = case.seq_rows(case.o, rows, slice(case.u * case.hq, (case.u + 1) * case.hq))
+    got_l = case.lse[case.rank].cpu().double().numpy()[:, :, rows]
+    assert tl.max_abs(got_l, ref_l) <= 1e-3
+    assert tl.max_abs(got_o, ref_o) <= 2e-2
