@@ -931,23 +931,37 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* dst, size_t n4) {
   if (i < n4) dst[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
+// Where the converted tensor goes when that is not the dense [bs, rows, heads, hs] it comes from but the sequence-layout
+// shards of the rank's Ulysses group ([U][bs][rows_per_shard][seq_heads][hs], dst = the group's first shard, the
+// rank's heads from head0 on): Algorithm 1's reverse all-to-all rides on the conversion's stores.  rows_per_shard = 0: dense.
+struct ConvertSeq { int rows_per_shard = 0, seq_heads = 0, head0 = 0, heads = 0, hs4 = 0, bs = 0; int64_t rows = 0; };
+
 // fp32 accumulator -> bf16 / fp32 output, 4 elements per lane; blockIdx.y picks one of two tensors of the same size
 // (dK and dV go through one launch)
 template <typename OutT>
 __global__ __launch_bounds__(256) void bwd_convert_kernel(const float* src0, OutT* dst0, const float* src1, OutT* dst1,
-                                                          size_t n4, int n_copies, size_t copy_stride4, int add_to_dst) {
+                                                          size_t n4, int n_copies, size_t copy_stride4, int add_to_dst,
+                                                          ConvertSeq cs) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
   const float* src = blockIdx.y ? src1 : src0;
   OutT* dst = blockIdx.y ? dst1 : dst0;
   f32x4 v = __builtin_nontemporal_load((const f32x4*)src + i);
   for (int c = 1; c < n_copies; ++c) v += __builtin_nontemporal_load((const f32x4*)src + c * copy_stride4 + i);
+  size_t o = i;   // in groups of four elements
+  if (cs.rows_per_shard) {
+    const size_t e4 = i % cs.hs4, rh = i / cs.hs4;
+    const size_t h = rh % cs.heads, br = rh / cs.heads;
+    const size_t row = br % cs.rows, b = br / cs.rows;
+    const size_t shard = row / cs.rows_per_shard, sr = row - shard * cs.rows_per_shard;
+    o = (((shard * cs.bs + b) * cs.rows_per_shard + sr) * cs.seq_heads + cs.head0 + h) * cs.hs4 + e4;
+  }
   if constexpr (sizeof(OutT) == 4) {
-    if (add_to_dst) v += *((const f32x4*)dst + i);
-    __builtin_nontemporal_store(v, (f32x4*)dst + i);
+    if (add_to_dst) v += *((const f32x4*)dst + o);
+    __builtin_nontemporal_store(v, (f32x4*)dst + o);
   } else {
     u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-    __builtin_nontemporal_store(pk, (u32x2*)dst + i);
+    __builtin_nontemporal_store(pk, (u32x2*)dst + o);
   }
 }
 
@@ -1148,6 +1162,19 @@ int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hip
 
 int launch_bwd_convert2(const float* src0, void* dst0, const float* src1, void* dst1, size_t n, int out_dtype,
                         hipStream_t stream, int n_copies, size_t copy_stride, int add_to_dst) {
+  return launch_bwd_convert_seq(src0, dst0, src1, dst1, n, out_dtype, stream, n_copies, copy_stride, add_to_dst, nullptr,
+                                0, 0, 0, 0);
+}
+
+int launch_bwd_convert_seq(const float* src0, void* dst0, const float* src1, void* dst1, size_t n, int out_dtype,
+                           hipStream_t stream, int n_copies, size_t copy_stride, int add_to_dst, const SeqLayoutIO* seq,
+                           int bs, int64_t rows, int heads, int hs) {
+  ConvertSeq cs;
+  if (seq) {
+    if ((size_t)bs * rows * heads * hs != n || hs % 4) return USP_ERR_UNSUPPORTED;
+    cs.rows_per_shard = seq->rows_per_shard; cs.seq_heads = seq->heads; cs.head0 = seq->head0;
+    cs.heads = heads; cs.hs4 = hs / 4; cs.bs = bs; cs.rows = rows;
+  }
   if (add_to_dst && out_dtype != USP_FP32) return USP_ERR_UNSUPPORTED;
   const size_t n4 = n / 4;
   const size_t grid = (n4 + 255) / 256;
@@ -1155,10 +1182,10 @@ int launch_bwd_convert2(const float* src0, void* dst0, const float* src1, void* 
   const dim3 g((unsigned)grid, src1 ? 2u : 1u);
   if (out_dtype == USP_FP32)
     hipLaunchKernelGGL((bwd_convert_kernel<float>), g, dim3(256), 0, stream, src0, (float*)dst0, src1, (float*)dst1, n4,
-                       n_copies, copy_stride / 4, add_to_dst);
+                       n_copies, copy_stride / 4, add_to_dst, cs);
   else
     hipLaunchKernelGGL((bwd_convert_kernel<__bf16>), g, dim3(256), 0, stream, src0, (__bf16*)dst0, src1, (__bf16*)dst1,
-                       n4, n_copies, copy_stride / 4, 0);
+                       n4, n_copies, copy_stride / 4, 0, cs);
   return launch_status();
 }
 

@@ -977,12 +977,15 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
                                 p->causal ? 1 : 0, qd, i0 > 0 ? 1 : 0, acc, stream, &f.copies);
       if (st != USP_OK) return st;
     }
-    // dQ of this rank: convert into the (now free) q_head region and send it back to the sequence layout
-    st = launch_bwd_convert((const float*)(ws + f.dq_acc), ws + f.q_head, q_elems, p->dtype, stream,
-                            f.copies.cut.k_splits, f.copies.dq_stride);
-    if (st != USP_OK) return st;
-    st = launch_layout_a2a(*p, p->hc, USP_HEAD_TO_SEQ, ws + f.q_head, dq, rank, rank + 1, rank, stream);
-    if (st != USP_OK) return st;
+    // dQ of this rank: the copies summed, converted and written straight to the sequence-layout shards of its Ulysses
+    // group (the reverse all-to-all rides on the conversion's stores)
+    {
+      const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
+      const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * dtype_size(p->dtype);
+      st = launch_bwd_convert_seq((const float*)(ws + f.dq_acc), (char*)dq + group_off, nullptr, nullptr, q_elems, p->dtype,
+                                  stream, f.copies.cut.k_splits, f.copies.dq_stride, 0, &seq, p->bs, Lq, hq, p->hs);
+      if (st != USP_OK) return st;
+    }
   }
 
   // dK, dV of every block the range touched: all ring rows of the columns whose ranks were run.  A range that
@@ -993,15 +996,12 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
       const int rank = r * U + u;
       const size_t sl = slot(r, u);
       if (!touched[sl]) continue;
-      char* kdst = ws + f.k_head + sl * f.kv_block_bytes;
-      char* vdst = ws + f.v_head + sl * f.kv_block_bytes;
-      st = launch_bwd_convert2((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), kdst,
-                               (const float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), vdst, kv_elems, p->dtype, stream,
-                               f.dkdv_copies, f.copies.dkdv_stride);
-      if (st != USP_OK) return st;
-      const void* heads_kv[2] = {kdst, vdst};
-      void* seqs_kv[2] = {dk, dv};
-      st = launch_layout_a2a_multi(*p, p->hk, USP_HEAD_TO_SEQ, 2, heads_kv, seqs_kv, rank, rank + 1, rank, stream);
+      // the copies summed, converted and written straight to the block's sequence-layout shards
+      const SeqLayoutIO seq = {(int)(p->L / N), p->hk, u * hkv};
+      const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hk * p->hs * dtype_size(p->dtype);
+      st = launch_bwd_convert_seq((const float*)(ws + f.dk_acc + sl * f.kv_acc_bytes), (char*)dk + group_off,
+                                  (const float*)(ws + f.dv_acc + sl * f.kv_acc_bytes), (char*)dv + group_off, kv_elems,
+                                  p->dtype, stream, f.dkdv_copies, f.copies.dkdv_stride, 0, &seq, p->bs, Lq, hkv, p->hs);
       if (st != USP_OK) return st;
     }
   return USP_OK;

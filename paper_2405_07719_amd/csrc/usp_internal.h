@@ -152,5 +152,11 @@ int launch_bwd_convert(const float* src, void* dst, size_t n, int out_dtype, hip
 // The same for two tensors of the same size and copy layout in one launch (src1 == nullptr: one tensor).
 int launch_bwd_convert2(const float* src0, void* dst0, const float* src1, void* dst1, size_t n, int out_dtype,
                         hipStream_t stream, int n_copies = 1, size_t copy_stride = 0, int add_to_dst = 0);
+// The same with the result written to the sequence-layout shards of the rank's Ulysses group (seq; dst0 / dst1 = the
+// group's first shard) instead of the dense [bs, rows, heads, hs] tensor the sources are: the reverse all-to-all of
+// Algorithm 1 rides on the conversion's stores.  seq = null: dense, as above.
+int launch_bwd_convert_seq(const float* src0, void* dst0, const float* src1, void* dst1, size_t n, int out_dtype,
+                           hipStream_t stream, int n_copies, size_t copy_stride, int add_to_dst, const SeqLayoutIO* seq,
+                           int bs, int64_t rows, int heads, int hs);
 
 }  // namespace usp
