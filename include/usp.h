@@ -286,10 +286,10 @@ int usp_ring_attn_bwd_ws(const void* q, const void* const* k_blocks, const void*
  * [rank_begin, rank_end); bf16 problems only.
  *   q, k, v, o, d_o: seq layout (o as usp_attn_fwd wrote it); lse: [N][bs][hc/U][L/R] from usp_attn_fwd;
  *   dq, dk, dv: seq layout outputs in the problem dtype.
- * Per rank: all-to-all of Q, O, dO -> delta -> R block backwards (dQ accumulated over the ring steps in
- * fp32; the dK/dV contribution of step i is added to block (r-i) mod R's fp32 accumulator, the buffer that
- * would travel the ring with the block) -> all-to-all of dQ.  After the last rank the dK/dV accumulators
- * are converted and all-to-all'ed back.
+ * Per rank: all-to-all of Q and dO -> delta (O and dO read at their places in the shards) -> R block backwards (dQ
+ * accumulated over the ring steps in fp32; the dK/dV contribution of step i is added to block (r-i) mod R's fp32
+ * accumulator, the buffer that would travel the ring with the block) -> dQ converted and scattered back to the
+ * shards.  After the last rank the dK/dV accumulators are converted and scattered back likewise.
  * dq is complete for the ranks in range (each fills its head slice of its Ulysses group's shards).
  * dk/dv: for every Ulysses column u that has a rank (r,u) in range, the column's head slice of ALL N shards is
  * OVERWRITTEN with the sum of the contributions of the column's ranks in range; the head slices of columns

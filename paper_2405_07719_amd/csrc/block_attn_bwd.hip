@@ -147,17 +147,25 @@ __device__ inline void pack_b_operand(const float (&x)[16], bf16x8& lo, bf16x8& 
 // -------------------------------------------------------------------------------------------------
 // D_i = sum_e dO_ie * O_ie   (rows of [bs,L,h,hs] tensors -> [bs,h,L] fp32)
 // -------------------------------------------------------------------------------------------------
+// seq_n > 0: o and d_o are not dense [bs, L, h, hs] tensors but the sequence-layout shards of the rank's Ulysses group
+// ([U][bs][seq_n][seq_heads][hs], the rank's h heads from seq_head0 on): row i of the rank lies in shard i / seq_n.
 template <int HS>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* o, const __bf16* d_o, float* delta, int bs,
-                                                        int L, int h) {
+                                                        int L, int h, int seq_n, int seq_heads, int seq_head0) {
   constexpr int TPR = HS / 8;   // lanes per row, 8 elements each
   const int64_t rows = (int64_t)bs * L * h;
   const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / TPR;
   const int part = threadIdx.x % TPR;
   float acc = 0.f;
   if (row < rows) {
-    const bf16x8 a = *(const bf16x8*)(o + row * HS + part * 8);
-    const bf16x8 b = *(const bf16x8*)(d_o + row * HS + part * 8);
+    int64_t at = row;   // the row's place in o and d_o, in rows of HS elements
+    if (seq_n) {
+      const int64_t hh = row % h, i = (row / h) % L, b = row / ((int64_t)h * L);
+      const int64_t shard = i / seq_n, sr = i - shard * seq_n;
+      at = ((shard * bs + b) * seq_n + sr) * seq_heads + seq_head0 + hh;
+    }
+    const bf16x8 a = *(const bf16x8*)(o + at * HS + part * 8);
+    const bf16x8 b = *(const bf16x8*)(d_o + at * HS + part * 8);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
   }
@@ -989,17 +997,18 @@ int launch_dq_ds(const BwdArgs& a, int64_t grid, hipStream_t stream) {
 }  // namespace
 
 int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
-                     hipStream_t stream) {
+                     hipStream_t stream, const SeqLayoutIO* seq) {
+  const int seq_n = seq ? seq->rows_per_shard : 0, seq_heads = seq ? seq->heads : 0, seq_head0 = seq ? seq->head0 : 0;
   const int64_t rows = (int64_t)bs * L * h;
   const int tpr = hs / 8;
   const int64_t grid = (rows * tpr + 255) / 256;
   if (grid > 0x7fffffffll) return USP_ERR_UNSUPPORTED;
   if (hs == 128)
     hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)grid), dim3(256), 0, stream, (const __bf16*)o,
-                       (const __bf16*)d_o, delta, bs, (int)L, h);
+                       (const __bf16*)d_o, delta, bs, (int)L, h, seq_n, seq_heads, seq_head0);
   else
     hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)grid), dim3(256), 0, stream, (const __bf16*)o,
-                       (const __bf16*)d_o, delta, bs, (int)L, h);
+                       (const __bf16*)d_o, delta, bs, (int)L, h, seq_n, seq_heads, seq_head0);
   return launch_status();
 }
 

@@ -840,8 +840,8 @@ extern "C" int usp_block_attn_bwd(const void* q, const void* k, const void* v, c
 
 // ---------------------------------------------------------------------------------------------
 // Algorithm 1 backward.  Workspace plan:
-//   q_head, o_head, do_head : one rank's Q, O, dO in head layout (reused rank after rank); q_head later
-//                             holds the rank's converted dQ before its all-to-all;
+//   q_head, do_head         : one rank's Q and dO in head layout (reused rank after rank); O is read once, for D_i,
+//                             straight from the sequence-layout shards;
 //   delta                   : one rank's D_i;
 //   k_head, v_head          : as in the forward; later hold the converted dK / dV blocks;
 //   dq_acc                  : one rank's fp32 dQ;  dk_acc, dv_acc : fp32, one per K/V block.
@@ -849,7 +849,7 @@ extern "C" int usp_block_attn_bwd(const void* q, const void* k, const void* v, c
 namespace {
 
 struct BwdPlan {
-  size_t q_head, o_head, do_head, delta, k_head, v_head, dq_acc, dk_acc, dv_acc, total;
+  size_t q_head, do_head, delta, k_head, v_head, dq_acc, dk_acc, dv_acc, total;
   size_t kv_block_bytes, kv_acc_bytes;   // kv_acc_bytes: ALL copies of one block's dk (or dv) accumulator
   BwdCopies copies;                      // how the launch pairs are cut, and the copies of dq / dk / dv they fill
   int dkdv_copies;
@@ -873,7 +873,6 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   const size_t blocks = (size_t)p.ring * n_cols;
   size_t off = 0;
   f.q_head = off; off += qb;
-  f.o_head = off; off += qb;
   f.do_head = off; off += qb;
   f.delta = off; off += up256((size_t)p.bs * hq * Lq * sizeof(float));
   f.k_head = off; off += up256(f.kv_block_bytes * blocks);
@@ -937,15 +936,20 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
 
   for (int rank = rank_begin; rank < rank_end; ++rank) {
     const int r = rank / U, u = rank % U;
-    {   // Q, O and dO of this rank to head layout: one geometry, one launch
-      const void* srcs[3] = {q, o, d_o};
-      void* dsts[3] = {ws + f.q_head, ws + f.o_head, ws + f.do_head};
-      st = launch_layout_a2a_multi(*p, p->hc, USP_SEQ_TO_HEAD, 3, srcs, dsts, rank, rank + 1, rank, stream);
+    {   // Q and dO of this rank to head layout: one geometry, one launch
+      const void* srcs[2] = {q, d_o};
+      void* dsts[2] = {ws + f.q_head, ws + f.do_head};
+      st = launch_layout_a2a_multi(*p, p->hc, USP_SEQ_TO_HEAD, 2, srcs, dsts, rank, rank + 1, rank, stream);
       if (st != USP_OK) return st;
     }
+    // delta reads O (and dO) once: straight from the sequence-layout shards of the rank's Ulysses group, no copy of O
     float* delta = (float*)(ws + f.delta);
-    st = launch_bwd_delta(ws + f.o_head, ws + f.do_head, delta, p->bs, Lq, hq, p->hs, stream);
-    if (st != USP_OK) return st;
+    {
+      const SeqLayoutIO seq = {(int)(p->L / N), p->hc, u * hq};
+      const size_t group_off = (size_t)r * U * p->bs * (p->L / N) * p->hc * p->hs * dtype_size(p->dtype);
+      st = launch_bwd_delta((const char*)o + group_off, (const char*)d_o + group_off, delta, p->bs, Lq, hq, p->hs, stream, &seq);
+      if (st != USP_OK) return st;
+    }
     usp_posdesc qd;
     usp_local_positions(p, r, u, nullptr, &qd);
     const float* lse_rank = lse + (size_t)rank * p->bs * hq * Lq;

@@ -118,8 +118,9 @@ int launch_block_attn_fwd(const void* q, const void* k, const void* v, void* o, 
                           int64_t Lk, int hq, int hkv, int hs, float scale, int causal, const usp_posdesc& qpos,
                           const usp_posdesc& kpos, int in_dtype, int o_dtype, hipStream_t stream);
 
+// seq: o and d_o are the sequence-layout shards of the rank's Ulysses group (their first shard), not dense tensors.
 int launch_bwd_delta(const void* o, const void* d_o, float* delta, int bs, int64_t L, int h, int hs,
-                     hipStream_t stream);
+                     hipStream_t stream, const SeqLayoutIO* seq = nullptr);
 // How a backward launch pair divides its work (plan_bwd_cut): query heads of a KV group walked by one dK/dV
 // workgroup, slices of a dQ item's key tiles, slices of a dK/dV item's query tiles.
 struct BwdCut { int heads_per_wg, k_splits, q_splits; };

@@ -104,12 +104,13 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     # some tiles in three pieces fill the first round instead (three partials)
     assert (usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 20480, 32, 8, 128, 8, 1, False), 1)
             == 2 * 5 * 2**20 + 3 * 40 * 2**20 + 3 * 320 * 2**10)
-    # backward: Q, O, dO in head layout (32 MiB each), delta (0.5), K and V (8 each), fp32 dQ (64) and one fp32 copy of
-    # dK and of dV (16 MiB each) per query head of the group: the four heads run as separate work items
-    assert usp.usp_attn_bwd_workspace_bytes(p, 1) == (3 * 32 + 2 * 8 + 64 + 2 * 4 * 16) * 2**20 + 2**19
+    # backward: Q and dO in head layout (32 MiB each; O is only read for delta, straight from the shards), delta (0.5),
+    # K and V (8 each), fp32 dQ (64) and one fp32 copy of dK and of dV (16 MiB each) per query head of the group: the
+    # four heads run as separate work items
+    assert usp.usp_attn_bwd_workspace_bytes(p, 1) == (2 * 32 + 2 * 8 + 64 + 2 * 4 * 16) * 2**20 + 2**19
     # the short sequence: 4 slices of the dQ items (4 copies of 16 MiB), 4 head splits x 4 query slices of dK/dV
     # (16 copies of 4 MiB each)
-    assert usp.usp_attn_bwd_workspace_bytes(short, 1) == (3 * 8 + 2 * 2 + 4 * 16 + 2 * 16 * 4) * 2**20 + 2**17
+    assert usp.usp_attn_bwd_workspace_bytes(short, 1) == (2 * 8 + 2 * 2 + 4 * 16 + 2 * 16 * 4) * 2**20 + 2**17
     # with room for dS (bf16, one 32 x 32 block per 2 KiB, both lengths rounded up to 256): 4 heads x 32768^2 x 2 bytes more
     assert usp.usp_attn_bwd_workspace_bytes_with_ds(p, 1) - usp.usp_attn_bwd_workspace_bytes(p, 1) == 4 * 32768**2 * 2
     assert usp.usp_attn_bwd_workspace_bytes_with_ds(short, 1) - usp.usp_attn_bwd_workspace_bytes(short, 1) == 4 * 8192**2 * 2
