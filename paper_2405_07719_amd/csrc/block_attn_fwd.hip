@@ -262,6 +262,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
     PosDesc32 kpos = {0, 0, 0, 0};
     TileRanges tr = {0, 0, 0, 0};
     int na = 0, nt = 0;
+    int free_a = 0, free_b0 = 0, free_b1 = 0;   // walk positions [0, free_a) and [free_b0, free_b1): tiles this wave need not mask
     auto tile_of = [&](int it) { return it < na ? tr.a0 + it : tr.b0 + (it - na); };
 
     f32x16 oacc[NQB][DB];
@@ -388,10 +389,9 @@ void block_attn_fwd_mfma(const AttnArgs) {
       const bool has2 = STEADY || it + 2 < nt;
       const int key0 = tile_of(it) * KT;
 
-      // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave
-      const int key1 = min(Lk_b, key0 + KT);
-      bool need_mask = key0 + KT > Lk_b;
-      if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
+      // ---- mask (wave-uniform decision): ragged key tail, or a key of the tile may exceed a query of the wave;
+      //      the tiles that need none come in two runs of the walk, worked out once per block
+      const bool need_mask = !(it < free_a || (it >= free_b0 && it < free_b1));
       if (need_mask) {
         int qp[NQB];   // the lane's query position: derived here, where it is rarely needed, rather than kept in a register
 #pragma unroll
@@ -519,6 +519,22 @@ void block_attn_fwd_mfma(const AttnArgs) {
       na = tr.a1 - tr.a0;
       nt = na + (tr.b1 - tr.b0);
       if (nt == 0) continue;         // nothing of this block is visible to the query tile (workgroup-uniform)
+      {
+        // Tiles that need no mask: full tiles that lie wholly in one ascending run of the key positions and whose
+        // last key no row of this wave precedes.  In walk order they form a run at the start of each visible range.
+        const int full = Lk_b / KT;
+        int fa = full, tb0 = 0, tb1 = 0;
+        if (a.causal && wave_live) {
+          int64_t c0 = (int64_t)wave_qmin - kpos.start0 + 1; c0 = c0 < 0 ? 0 : (c0 > kpos.len0 ? kpos.len0 : c0);
+          int64_t c1 = (int64_t)wave_qmin - kpos.start1 + 1; c1 = c1 < 0 ? 0 : (c1 > kpos.len1 ? kpos.len1 : c1);
+          fa = (int)(c0 / KT);
+          tb0 = (int)(((int64_t)kpos.len0 + KT - 1) / KT);
+          tb1 = (int)(((int64_t)kpos.len0 + c1) / KT);
+        }
+        free_a = min(min(fa, full), na);
+        free_b0 = na + max(tb0, tr.b0) - tr.b0;
+        free_b1 = na + min(min(tb1, full), tr.b1) - tr.b0;
+      }
       kg = (const char*)ap->k[blk] + kv_head_off;
       vg = (const char*)ap->v[blk] + (VT ? vt_head_off : kv_head_off);
 
