@@ -318,14 +318,15 @@ void block_attn_fwd_mfma(const AttnArgs) {
     uint32_t st_off[CPT];
 #pragma unroll
     for (int c = 0; c < CPT; ++c) st_off[c] = (uint32_t)(st_row + c * ROWS_PER_PASS) * row_bytes + st_col * 16;
-    auto fetch = [&](const char* base, int it, u32x4* reg) {
-      const int key0 = tile_of(it) * KT;
-      const char* tb = base + (size_t)key0 * row_bytes;
-      const int rows = min(Lk_b - key0, KT);
-      const __amdgpu_buffer_rsrc_t tile = __builtin_amdgcn_make_buffer_rsrc(
-          (void*)tb, 0, (rows - 1) * (int)row_bytes + HS * 2, kRawBufferFlags);
+    // (`tile` is the tile's number in the block, not its place in the walk; the extent is one of two values that
+    // are worked out once per block: a full tile's, or that of the block's ragged last tile)
+    int full_tiles = 0, full_extent = 0, ragged_extent = 0;
+    auto fetch = [&](const char* base, int tile, u32x4* reg) {
+      const char* tb = base + (uint64_t)((uint32_t)tile * KT) * row_bytes;
+      const __amdgpu_buffer_rsrc_t tile_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)tb, 0, tile < full_tiles ? full_extent : ragged_extent, kRawBufferFlags);
 #pragma unroll
-      for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile, (int)st_off[c], 0, 0);
+      for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile_rsrc, (int)st_off[c], 0, 0);
     };
     auto stash = [&](char* buf, int stride, const u32x4* reg) {
 #pragma unroll
@@ -333,11 +334,11 @@ void block_attn_fwd_mfma(const AttnArgs) {
     };
     // transposed V tiles: 16 KiB (8 KiB at head size 64) contiguous in global memory, chunk c of the tile goes to
     // row c / 8 (a head dim), 16 B column c % 8 of the LDS tile
-    auto fetch_vt = [&](const char* base, int it, u32x4* reg) {
-      const char* tb = base + (size_t)tile_of(it) * VT_TILE_BYTES;
-      const __amdgpu_buffer_rsrc_t tile = __builtin_amdgcn_make_buffer_rsrc((void*)tb, 0, VT_TILE_BYTES, kRawBufferFlags);
+    auto fetch_vt = [&](const char* base, int tile, u32x4* reg) {
+      const char* tb = base + (uint64_t)(uint32_t)tile * VT_TILE_BYTES;
+      const __amdgpu_buffer_rsrc_t tile_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)tb, 0, VT_TILE_BYTES, kRawBufferFlags);
 #pragma unroll
-      for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile, (tid + c * NT) * 16, 0, 0);
+      for (int c = 0; c < CPT; ++c) reg[c] = __builtin_amdgcn_raw_buffer_load_b128(tile_rsrc, (tid + c * NT) * 16, 0, 0);
     };
     auto stash_vt = [&](char* buf, const u32x4* reg) {
 #pragma unroll
@@ -346,8 +347,8 @@ void block_attn_fwd_mfma(const AttnArgs) {
         *(u32x4*)(buf + (ch >> 3) * VSTR + (ch & 7) * 16) = reg[c];
       }
     };
-    auto fetch_v = [&](const char* base, int it, u32x4* reg) {
-      if constexpr (VT) fetch_vt(base, it, reg); else fetch(base, it, reg);
+    auto fetch_v = [&](const char* base, int tile, u32x4* reg) {
+      if constexpr (VT) fetch_vt(base, tile, reg); else fetch(base, tile, reg);
     };
     auto stash_v = [&](char* buf, const u32x4* reg) {
       if constexpr (VT) stash_vt(buf, reg); else stash(buf, VSTR, reg);
@@ -379,6 +380,7 @@ void block_attn_fwd_mfma(const AttnArgs) {
 
     // One pipeline step on tile `it` whose scores are in s_cur.  Unless LAST, the scores of tile it+1
     // are produced into s_next while the softmax of s_cur runs.
+    int v_tile = 0;   // number of the V tile the next step prefetches (workgroup-uniform)
     const int grp = lane >> 4, j16 = lane & 15;
     const int v_lane_off = (4 * hl + (j16 >> 2)) * VSTR + (16 * (grp & 1) + 4 * (j16 & 3)) * 2;
     auto step = [&](auto steady_tag, int it, f32x16 (&s_cur)[NQB][KB], f32x16 (&s_next)[NQB][KB]) {
@@ -446,8 +448,11 @@ void block_attn_fwd_mfma(const AttnArgs) {
       for (int qb = 0; qb < NQB; ++qb) mc[qb] = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb] * a.scale_log2;
 
       // ---- global prefetch: K two tiles ahead, V one tile ahead
-      if (has2) fetch(kg, it + 2, kreg);
-      if (has1) fetch_v(vg, it + 1, vreg);
+      //      (the V tile wanted now is the K tile of the step before: its number is carried over)
+      const int k_tile = tile_of(it + 2);
+      if (has2) fetch(kg, k_tile, kreg);
+      if (has1) fetch_v(vg, v_tile, vreg);
+      v_tile = k_tile;
       // keep the loads up here: left alone, the scheduler sinks them to just before the LDS stores below to
       // save registers, and every step then waits out a full global-memory latency
       __builtin_amdgcn_sched_barrier(0);
@@ -540,12 +545,16 @@ void block_attn_fwd_mfma(const AttnArgs) {
 
       // ---- prologue: K(0), V(0), K(1) to LDS; scores of tile 0.  (Every step ends on a barrier, so the previous
       //      block's last reads of these buffers are over.)
-      fetch(kg, 0, kreg);
-      fetch_v(vg, 0, vreg);
+      full_tiles = Lk_b / KT;
+      full_extent = (KT - 1) * (int)row_bytes + HS * 2;
+      ragged_extent = (Lk_b - full_tiles * KT - 1) * (int)row_bytes + HS * 2;   // (not used when there is no ragged tile)
+      fetch(kg, tile_of(0), kreg);
+      fetch_v(vg, tile_of(0), vreg);
       stash(kbuf, KSTR, kreg);
       stash_v(vbuf, vreg);
+      v_tile = tile_of(1);
       if (nt > 1) {
-        fetch(kg, 1, kreg);
+        fetch(kg, tile_of(1), kreg);
         stash(kbuf + KBYTES, KSTR, kreg);
       }
       __syncthreads();
