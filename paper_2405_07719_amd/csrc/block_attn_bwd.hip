@@ -312,6 +312,24 @@ void bwd_dq_kernel(const BwdArgs) {
     nt = na + (tr.b1 - tr.b0);
     const int it0 = (int)((int64_t)nt * kslice / k_splits), it1 = (int)((int64_t)nt * (kslice + 1) / k_splits);
     if (it1 == it0) continue;                // workgroup-uniform
+    // Tiles this wave need not mask: full tiles that lie wholly in one ascending run of the key positions and whose
+    // last key none of the wave's rows precedes.  In walk order they are [0, free_a) and [free_b0, free_b1), worked
+    // out here once per block; the decision per tile is then two comparisons.
+    int free_a, free_b0, free_b1;
+    {
+      const int full = a.Lk / KT;
+      int fa = full, tb0 = 0, tb1 = 0;
+      if (a.causal && wave_live) {
+        int64_t c0 = (int64_t)wave_qmin - kpos.start0 + 1; c0 = c0 < 0 ? 0 : (c0 > kpos.len0 ? kpos.len0 : c0);
+        int64_t c1 = (int64_t)wave_qmin - kpos.start1 + 1; c1 = c1 < 0 ? 0 : (c1 > kpos.len1 ? kpos.len1 : c1);
+        fa = (int)(c0 / KT);
+        tb0 = (int)(((int64_t)kpos.len0 + KT - 1) / KT);
+        tb1 = (int)(((int64_t)kpos.len0 + c1) / KT);
+      }
+      free_a = min(min(fa, full), na);
+      free_b0 = na + max(tb0, tr.b0) - tr.b0;
+      free_b1 = na + min(min(tb1, full), tr.b1) - tr.b0;
+    }
     kg = (const char*)ap->k[blk] + kv_head_off;
     vg = (const char*)ap->v[blk] + kv_head_off;
     fetch(it0);
@@ -337,9 +355,7 @@ void bwd_dq_kernel(const BwdArgs) {
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dp, 0, 0, 0);
       }
 
-      const int key1 = min(a.Lk, key0 + KT);
-      bool need_mask = key0 + KT > a.Lk;
-      if (a.causal && wave_live) need_mask = need_mask || (pos_max(kpos, key0, key1) > wave_qmin);
+      const bool need_mask = !(it < free_a || (it >= free_b0 && it < free_b1));
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], a.scale_log2, -l2));
       if (need_mask) {     // wave-uniform and rare: tiles on the causal boundary or the ragged tail
@@ -692,6 +708,27 @@ void bwd_dkdv_kernel(const BwdArgs) {
     auto tile_of = [&](int it) { const int j = nt - 1 - it; return j < na ? tr.a0 + j : tr.b0 + (j - na); };
     const bool wave_live = wave_key0 < a.Lk;
     const int wave_kmax = (a.causal && wave_live) ? pos_max(kpos, wave_key0, min(a.Lk, wave_key0 + 32)) : 0;
+    // Query tiles this wave need not mask: full tiles that lie wholly in one ascending run of the query positions
+    // and whose first row none of the wave's keys follows (and only if the wave's 32 keys all exist).  As places
+    // j in the visible ranges (tile_of(it) is place nt - 1 - it) they are [free_a0, free_a1) and [free_b0, free_b1),
+    // worked out here once per work item; the decision per tile is then a few comparisons.
+    int free_a0 = 0, free_a1 = 0, free_b0 = 0, free_b1 = 0;
+    if (wave_live && wave_key0 + 32 <= a.Lk) {
+      const int full = a.Lq / QT;
+      int ta0 = 0, ta1 = full, tb0 = 0, tb1 = 0;   // as tile numbers
+      if (a.causal) {
+        int64_t g0 = (int64_t)wave_kmax - a.qpos.start0; g0 = g0 < 0 ? 0 : (g0 > a.qpos.len0 ? a.qpos.len0 : g0);
+        int64_t g1 = (int64_t)wave_kmax - a.qpos.start1; g1 = g1 < 0 ? 0 : (g1 > a.qpos.len1 ? a.qpos.len1 : g1);
+        ta0 = (int)((g0 + QT - 1) / QT);
+        ta1 = min(full, a.qpos.len0 / QT);
+        tb0 = (int)(((int64_t)a.qpos.len0 + g1 + QT - 1) / QT);
+        tb1 = min(full, (int)(((int64_t)a.qpos.len0 + a.qpos.len1) / QT));
+      }
+      free_a0 = max(ta0, tr.a0) - tr.a0;
+      free_a1 = min(ta1, tr.a1) - tr.a0;
+      free_b0 = na + max(max(tb0, ta1), tr.b0) - tr.b0;
+      free_b1 = na + min(tb1, tr.b1) - tr.b0;
+    }
 
     const int st_row = tid / CPR, st_col = tid % CPR;
     const bool stager = st_row < QT;
@@ -818,9 +855,8 @@ void bwd_dkdv_kernel(const BwdArgs) {
       // this lane: key column l32; register i <-> query row 8 (i/4) + 4 hl + (i%4) of the tile.
       // P and dS overwrite s and dp in place; the mask (rare: tiles on the causal boundary or ragged) sits
       // behind a wave-uniform branch.
-      const int q1 = min(a.Lq, q0 + QT);
-      bool need_mask = q0 + QT > a.Lq || wave_key0 + 32 > a.Lk;
-      if (a.causal && wave_live) need_mask = need_mask || (wave_kmax > pos_min(a.qpos, q0, q1));
+      const int jq = nt - 1 - it;   // the tile's place in the visible ranges
+      const bool need_mask = !((jq >= free_a0 && jq < free_a1) || (jq >= free_b0 && jq < free_b1));
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(s[i] * a.scale_log2);
       if (need_mask) {
