@@ -55,7 +55,24 @@ def _tensors(seed, bs, Lq, Lk, hq, hkv, hs, nb):
 @pytest.mark.parametrize("seed", range(24))
 def test_ring_fwd_random_shapes(usp, seed):
     rng = np.random.default_rng(1000 + seed)
-    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = _draw(rng, usp, 700)
+    _check_ring_fwd(usp, seed, _draw(rng, usp, 700))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_ring_fwd_random_shapes_of_many_tiles(usp, seed):
+    """The same with blocks of up to 24 key tiles: long runs of tiles that need no mask between the unaligned
+    boundaries of the position runs, where the kernels decide per tile from runs worked out once per block."""
+    rng = np.random.default_rng(7000 + seed)
+    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = _draw(rng, usp, 1500)
+    Lq, Lk = max(Lq, 300), max(Lk, 700)
+    span = int(1.3 * max(Lq, Lk)) + 10    # queries and keys share a narrow range of positions: boundaries everywhere
+    qd = _random_desc(rng, usp, Lq, span)
+    kds = [_random_desc(rng, usp, Lk, span) for _ in range(nb)]
+    _check_ring_fwd(usp, 300 + seed, (1, Lq, Lk, hq, hkv, hs, min(nb, 3), True, qd, kds[:min(nb, 3)]))
+
+
+def _check_ring_fwd(usp, seed, drawn):
+    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = drawn
     qs, qv, ks, kv, vs, vv = _tensors(seed, bs, Lq, Lk, hq, hkv, hs, nb)
     qpos = np.array(qd.positions()) if causal else np.arange(Lq)
     kpos = np.concatenate([np.array(d.positions()) for d in kds]) if causal else np.arange(nb * Lk)
@@ -77,9 +94,28 @@ def test_ring_fwd_random_shapes(usp, seed):
 @pytest.mark.parametrize("seed", range(12))
 def test_ring_bwd_random_shapes(usp, seed):
     rng = np.random.default_rng(5000 + seed)
-    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = _draw(rng, usp, 400)
-    qs, qv, ks, kv, vs, vv = _tensors(100 + seed, bs, Lq, Lk, hq, hkv, hs, nb)
-    gs, gv = tl.gen(100 + seed, inputs.TENSOR_DO, bs, np.arange(Lq), np.arange(hq), hs, tl.BF16)
+    _check_ring_bwd(usp, 100 + seed, _draw(rng, usp, 400))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_ring_bwd_random_shapes_of_many_tiles(usp, seed):
+    """Blocks of 16 ... 31 key tiles and 8 ... 31 query tiles of 32 (causal, one or two blocks): the backward
+    kernels' runs of tiles that need no mask, between unaligned run boundaries.  Keys and queries of similar
+    number, so that the gradients stay of the magnitude the 5e-2 tolerance is meant for."""
+    rng = np.random.default_rng(9000 + seed)
+    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = _draw(rng, usp, 1000)
+    Lq, Lk = int(rng.integers(256, 1000)), int(rng.integers(512, 1000))
+    nb = min(nb, 2)
+    span = int(1.3 * max(Lq, Lk)) + 10    # queries and keys share a narrow range of positions: boundaries everywhere
+    qd = _random_desc(rng, usp, Lq, span)
+    kds = [_random_desc(rng, usp, Lk, span) for _ in range(nb)]
+    _check_ring_bwd(usp, 400 + seed, (1, Lq, Lk, hq, hkv, hs, nb, True, qd, kds), scale_tolerance=True)
+
+
+def _check_ring_bwd(usp, seed, drawn, scale_tolerance=False):
+    bs, Lq, Lk, hq, hkv, hs, nb, causal, qd, kds = drawn
+    qs, qv, ks, kv, vs, vv = _tensors(seed, bs, Lq, Lk, hq, hkv, hs, nb)
+    gs, gv = tl.gen(seed, inputs.TENSOR_DO, bs, np.arange(Lq), np.arange(hq), hs, tl.BF16)
     qpos = np.array(qd.positions()) if causal else np.arange(Lq)
     kpos = np.concatenate([np.array(d.positions()) for d in kds]) if causal else np.arange(nb * Lk)
     ref_dq, ref_dk, ref_dv = orc.attention_backward(qv, kv, vv, gv, causal, None, qpos, kpos)
@@ -103,7 +139,12 @@ def test_ring_bwd_random_shapes(usp, seed):
     got_dv = np.concatenate([tl.to_f64(x) for x in dv], axis=1)
     for name, got, ref in (("dq", tl.to_f64(dq), ref_dq), ("dk", got_dk, ref_dk), ("dv", got_dv, ref_dv)):
         assert not np.isnan(got).any(), name
-        assert tl.max_abs(got, ref) <= 5e-2, name
+        # 5e-2 is the bound for gradients of the usual magnitude (a few units).  Random descriptors can leave hundreds of
+        # queries with a handful of visible keys, whose dK / dV then reach 20-40: rounding P and dS to bf16 (2^-9
+        # relative, what the kernels' matrix products take) alone moves such sums by more than 5e-2, so where asked
+        # the bound grows with the reference's magnitude beyond 8.
+        tol = 5e-2 * max(1.0, float(np.abs(ref).max()) / 8.0) if scale_tolerance else 5e-2
+        assert tl.max_abs(got, ref) <= tol, name
 
 
 @pytest.mark.parametrize("gain", [8.0, 0.015625])
