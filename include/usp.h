@@ -213,7 +213,12 @@ int usp_ring_attn_fwd_partials(const void* q, const void* const* k_blocks, const
  * the merge covers their rows; the workspace query knows.
  *   q, o: seq layout with hc heads; k, v: seq layout with hk heads (ALL N shards must be
  *   present: the ring reads the other ring ranks' K/V where hardware would receive them);
- *   lse: [N][bs][hc/U][L/R] float, written for the ranks in range. */
+ *   lse: [N][bs][hc/U][L/R] float, written for the ranks in range.
+ * With Ulysses degree 1 the all-to-alls are the identity (a block in head layout is its shard as it stands): K, and
+ * V unless re-tiling it pays, are read where the caller holds them, not copied.
+ * The workspace query returns 0 for an invalid problem or n_ranks < 1, and also for a plan that needs none (a
+ * ring-only bf16 problem whose ring loop is one launch): usp_attn_fwd then accepts any workspace pointer, NULL
+ * included; usp_validate tells the two apart. */
 size_t usp_attn_fwd_workspace_bytes(const usp_problem* p, int n_ranks);
 int usp_attn_fwd(const usp_problem* p, const void* q, const void* k, const void* v, void* o, float* lse,
                  int rank_begin, int rank_end, void* workspace, size_t workspace_bytes, void* stream);

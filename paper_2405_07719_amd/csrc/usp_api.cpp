@@ -305,6 +305,9 @@ struct FwdPlan {
   size_t kv_block_bytes, v_block_bytes, part_o_bytes, part_lse_bytes;
   int n_cols;
   bool v_transposed;   // V blocks are staged in key-tile-transposed layout (the one-launch ring loop reads them so)
+  // Ulysses degree 1: a K/V block in head layout IS its sequence-layout shard.  K is then never staged; V only when it
+  // is wanted in transposed tiles and re-tiling it costs less than the tiles save.
+  bool k_in_place, v_in_place;
 };
 
 // Ulysses columns touched by ranks [rb, re): all U when the range spans more than one ring row.
@@ -532,10 +535,24 @@ FwdPlan plan_fwd(const usp_problem& p, int n_cols, bool allow_heavy = true) {
   const int splits = key_splits(p);
   // The one-launch ring loop and the launch that cuts only the heaviest tiles (not the launch that cuts every tile,
   // whose fp32 instance reads V rows) take V in key-tile-transposed layout: tiles of 64 keys, the last one padded.
+  // With Ulysses degree 1 the all-to-all of Algorithm 1 is the identity: block s in head layout, [bs][L/R][hk][hs], is
+  // shard s as it stands, and the kernels read K where it is.  V too, as rows, unless re-tiling it (the only copy
+  // left: all R blocks read and written at about 5 TB/s, one launch of about 6 us) costs less than the transposed
+  // tiles save (1.3 % of the attention time, taken as visible pairs x 4 hs flop at 1.1 PFLOP/s).  Measured, one
+  // ring-only rank of L = 32768, ring 8: 8 KV heads 1.014 -> 0.970 ms with both in place (0.987 estimated with V
+  // re-tiled); one KV head 0.954 -> 0.960 ms with both in place, hence V re-tiled there.
+  f.k_in_place = p.ulysses == 1;
   f.v_transposed = ring_in_one_launch(p) && splits == 0;
+  if (f.k_in_place && f.v_transposed) {
+    const double pairs = (double)p.bs * hq * (double)Lq * (double)p.L * (p.causal ? 0.5 : 1.0);
+    const double attention_us = pairs * 4.0 * p.hs / 1.1e9;
+    const double retile_us = 2.0 * (double)p.bs * p.L * hkv * p.hs * es / 5e6 + 6.0;
+    if (retile_us > 0.013 * attention_us) f.v_transposed = false;
+  }
+  f.v_in_place = f.k_in_place && !f.v_transposed;
   f.v_block_bytes = f.v_transposed ? vt_block_bytes(p.bs, (int64_t)Lq, (int)hkv, p.hs) : f.kv_block_bytes;
-  f.k_head = off; off += up256(f.kv_block_bytes * p.ring * n_cols);
-  f.v_head = off; off += up256(f.v_block_bytes * p.ring * n_cols);
+  f.k_head = off; off += f.k_in_place ? 0 : up256(f.kv_block_bytes * p.ring * n_cols);
+  f.v_head = off; off += f.v_in_place ? 0 : up256(f.v_block_bytes * p.ring * n_cols);
   size_t parts = splits > 0 ? (size_t)splits * p.ring : (p.ring > 1 && !ring_in_one_launch(p)) ? p.ring : 0;
   parts = std::max<size_t>(parts, (size_t)heavy);
   f.o_parts = off; off += f.part_o_bytes * parts;
@@ -613,8 +630,8 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
   int c0, c1;
   column_range(*p, rank_begin, rank_end, &c0, &c1);
   const FwdPlan f = plan_fwd(*p, c1 - c0, allow_heavy);
-  if (!workspace || workspace_bytes < f.total) return USP_ERR_WORKSPACE;
-  if ((uintptr_t)workspace & 255) return USP_ERR_WORKSPACE;
+  // (a plan that needs no workspace at all, as a ring-only problem in one launch, takes any pointer, null included)
+  if (f.total > 0 && (!workspace || workspace_bytes < f.total || ((uintptr_t)workspace & 255))) return USP_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   char* ws = (char*)workspace;
   const size_t es = dtype_size(p->dtype);
@@ -626,9 +643,17 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
   // Steps 3-4 of Algorithm 1 for every K/V block the ranks in range will visit.  The workspace slot of
   // block (r, u) is r * n_cols + (u - c0): with all U columns that is the rank order (one launch per
   // tensor); with one column the ranks r * U + u are a stride-U sequence (again one launch per tensor).
-  st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream,
-                       f.v_transposed ? f.v_block_bytes : 0);
-  if (st != USP_OK) return st;
+  const char* const k_blocks = f.k_in_place ? (const char*)k : ws + f.k_head;   // block slot 0 of K, of V
+  const char* const v_blocks = f.v_in_place ? (const char*)v : ws + f.v_head;
+  if (!f.k_in_place) {
+    st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream,
+                         f.v_transposed ? f.v_block_bytes : 0);
+    if (st != USP_OK) return st;
+  } else if (!f.v_in_place) {
+    // Ulysses degree 1, V wanted in transposed tiles: all R blocks in one launch, slot = ring row
+    st = launch_layout_a2a_vt(*p, p->hk, v, ws + f.v_head, 0, R, -1, stream);
+    if (st != USP_OK) return st;
+  }
 
   for (int rank = rank_begin; rank < rank_end; ++rank) {
     const int r = rank / U, u = rank % U;
@@ -649,8 +674,8 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
         const int s = ((r - i) % R + R) % R;
         usp_local_positions(p, s, u, nullptr, &kds[i]);
         const size_t slot = (size_t)s * (c1 - c0) + (u - c0);
-        kb[i] = ws + f.k_head + slot * f.kv_block_bytes;
-        vb[i] = ws + f.v_head + slot * f.v_block_bytes;
+        kb[i] = k_blocks + slot * f.kv_block_bytes;
+        vb[i] = v_blocks + slot * f.v_block_bytes;
       }
       // Steps 2 and 6 for Q and O ride on the kernel's own accesses: it reads each Q row once and writes each O
       // row once, so it does that straight from / to the sequence-layout shards of the Ulysses group.
@@ -736,7 +761,7 @@ int attn_fwd_impl(const usp_problem* p, const void* q, const void* k, const void
       const size_t slot = ((size_t)s * (c1 - c0) + (u - c0)) * f.kv_block_bytes;
       void* o_dst = R > 1 ? (void*)(ws + f.o_parts + (size_t)i * f.part_o_bytes) : (void*)(ws + f.o_head);
       float* l_dst = R > 1 ? (float*)(ws + f.lse_parts + (size_t)i * f.part_lse_bytes) : lse_rank;
-      st = launch_block_attn_fwd(ws + f.q_head, ws + f.k_head + slot, ws + f.v_head + slot, o_dst, l_dst, p->bs, Lq,
+      st = launch_block_attn_fwd(ws + f.q_head, k_blocks + slot, v_blocks + slot, o_dst, l_dst, p->bs, Lq,
                                  Lq, hq, hkv, p->hs, scale, p->causal ? 1 : 0, qd, kd, p->dtype,
                                  R > 1 ? USP_FP32 : p->dtype, stream);
       if (st != USP_OK) return st;
@@ -842,6 +867,8 @@ extern "C" int usp_block_attn_bwd(const void* q, const void* k, const void* v, c
 // Algorithm 1 backward.  Workspace plan:
 //   q_head, do_head         : one rank's Q and dO in head layout (reused rank after rank); O is read once, for D_i,
 //                             straight from the sequence-layout shards;
+//   (with Ulysses degree 1 a rank's Q, dO and every K/V block in head layout ARE the sequence-layout shards: these
+//   four regions are empty and the kernels read the caller's tensors where they are)
 //   delta                   : one rank's D_i;
 //   k_head, v_head          : as in the forward; later hold the converted dK / dV blocks;
 //   dq_acc                  : one rank's fp32 dQ;  dk_acc, dv_acc : fp32, one per K/V block.
@@ -872,11 +899,12 @@ BwdPlan plan_bwd(const usp_problem& p, int n_cols) {
   f.kv_acc_bytes = up256(kv_elems * sizeof(float) * f.dkdv_copies);
   const size_t blocks = (size_t)p.ring * n_cols;
   size_t off = 0;
-  f.q_head = off; off += qb;
-  f.do_head = off; off += qb;
+  const bool in_place = p.ulysses == 1;
+  f.q_head = off; off += in_place ? 0 : qb;
+  f.do_head = off; off += in_place ? 0 : qb;
   f.delta = off; off += up256((size_t)p.bs * hq * Lq * sizeof(float));
-  f.k_head = off; off += up256(f.kv_block_bytes * blocks);
-  f.v_head = off; off += up256(f.kv_block_bytes * blocks);
+  f.k_head = off; off += in_place ? 0 : up256(f.kv_block_bytes * blocks);
+  f.v_head = off; off += in_place ? 0 : up256(f.kv_block_bytes * blocks);
   f.dq_acc = off; off += up256(q_elems * sizeof(float) * f.copies.cut.k_splits);
   f.dk_acc = off; off += f.kv_acc_bytes * blocks;
   f.dv_acc = off; off += f.kv_acc_bytes * blocks;
@@ -927,8 +955,14 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
   const size_t q_elems = (size_t)p->bs * Lq * hq * p->hs, kv_elems = (size_t)p->bs * Lq * hkv * p->hs;
   auto slot = [&](int r, int u) { return (size_t)r * n_cols + (u - c0); };
 
-  st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream);
-  if (st != USP_OK) return st;
+  // Ulysses degree 1: the all-to-alls are the identity, a rank's Q / dO and every K/V block are shards as they stand
+  const bool in_place = U == 1;
+  const char* const k_blocks = in_place ? (const char*)k : ws + f.k_head;   // block slot 0 of K, of V
+  const char* const v_blocks = in_place ? (const char*)v : ws + f.v_head;
+  if (!in_place) {
+    st = stage_kv_blocks(*p, k, v, ws + f.k_head, ws + f.v_head, f.kv_block_bytes, c0, c1, stream);
+    if (st != USP_OK) return st;
+  }
 
   // first contribution to a K/V block overwrites its accumulator, later ones add
   bool touched[USP_MAX_MERGE_PARTS] = {false};
@@ -936,11 +970,15 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
 
   for (int rank = rank_begin; rank < rank_end; ++rank) {
     const int r = rank / U, u = rank % U;
-    {   // Q and dO of this rank to head layout: one geometry, one launch
+    const char* q_rank = (const char*)q + (size_t)rank * q_elems * dtype_size(p->dtype);      // used when in place
+    const char* do_rank = (const char*)d_o + (size_t)rank * q_elems * dtype_size(p->dtype);
+    if (!in_place) {   // Q and dO of this rank to head layout: one geometry, one launch
       const void* srcs[2] = {q, d_o};
       void* dsts[2] = {ws + f.q_head, ws + f.do_head};
       st = launch_layout_a2a_multi(*p, p->hc, USP_SEQ_TO_HEAD, 2, srcs, dsts, rank, rank + 1, rank, stream);
       if (st != USP_OK) return st;
+      q_rank = ws + f.q_head;
+      do_rank = ws + f.do_head;
     }
     // delta reads O (and dO) once: straight from the sequence-layout shards of the rank's Ulysses group, no copy of O
     float* delta = (float*)(ws + f.delta);
@@ -969,14 +1007,14 @@ extern "C" int usp_attn_bwd(const usp_problem* p, const void* q, const void* k, 
         const int s = ((r - (i0 + j)) % R + R) % R;
         usp_local_positions(p, s, u, nullptr, &kds[j]);
         const size_t sl = slot(s, u);
-        kb[j] = ws + f.k_head + sl * f.kv_block_bytes;
-        vb[j] = ws + f.v_head + sl * f.kv_block_bytes;
+        kb[j] = k_blocks + sl * f.kv_block_bytes;
+        vb[j] = v_blocks + sl * f.kv_block_bytes;
         dkb[j] = (float*)(ws + f.dk_acc + sl * f.kv_acc_bytes);
         dvb[j] = (float*)(ws + f.dv_acc + sl * f.kv_acc_bytes);
         acc[j] = touched[sl] ? 1 : 0;
         touched[sl] = true;
       }
-      st = launch_ring_attn_bwd(ws + f.q_head, kb, vb, kds, nb, ws + f.do_head, lse_rank, delta,
+      st = launch_ring_attn_bwd(q_rank, kb, vb, kds, nb, do_rank, lse_rank, delta,
                                 (float*)(ws + f.dq_acc), dkb, dvb, p->bs, Lq, Lq, hq, hkv, p->hs, scale,
                                 p->causal ? 1 : 0, qd, i0 > 0 ? 1 : 0, acc, stream, &f.copies);
       if (st != USP_OK) return st;

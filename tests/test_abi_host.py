@@ -77,15 +77,19 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     assert usp.usp_attn_fwd_workspace_bytes(p, 8) > one
     ring = usp.problem(1, 32768, 32, 8, 128, 1, 8, True)
     w = usp.usp_attn_fwd_workspace_bytes(ring, 1)
-    # bf16, R <= 16: the ring loop is one launch, so only the 8 K and 8 V blocks (8 MiB each)
-    assert w == 2 * 8 * 8 * 2**20
-    # fp32 data runs one launch per ring step: + 8 fp32 partial O and 8 partial LSE (elements are 4 bytes now)
+    # bf16, R <= 16: the ring loop is one launch, and with Ulysses degree 1 the all-to-alls are the identity: a K/V block
+    # in head layout is its shard as it stands, nothing is staged, no workspace at all
+    assert w == 0
+    # ... with Ulysses 2 x ring 4 the 4 K and 4 V blocks of a column are staged (16384 keys x 4 heads: 16 MiB each)
+    assert usp.usp_attn_fwd_workspace_bytes(usp.problem(1, 65536, 32, 8, 128, 2, 4, True), 1) == 2 * 4 * 16 * 2**20
+    # fp32 data runs one launch per ring step: Q and O in head layout (64 MiB each, elements are 4 bytes now; K/V in place),
+    # 8 fp32 partial O and 8 partial LSE
     ring32 = usp.problem(1, 32768, 32, 8, 128, 1, 8, True, usp.USP_SPLIT_ZIGZAG, usp.USP_FP32)
     w32 = usp.usp_attn_fwd_workspace_bytes(ring32, 1)
-    assert w32 == 2 * 64 * 2**20 + 2 * 8 * 16 * 2**20 + 8 * 64 * 2**20 + 8 * 2**19
+    assert w32 == 2 * 64 * 2**20 + 8 * 64 * 2**20 + 8 * 2**19
     # more ring ranks than one launch takes blocks: partials again
     long_ring = usp.problem(1, 32768, 32, 8, 128, 1, 32, True)
-    assert usp.usp_attn_fwd_workspace_bytes(long_ring, 1) == 2 * 8 * 2**20 + 2 * 2 * 32 * 2**20 + 32 * 16 * 2**20 + 32 * 2**17
+    assert usp.usp_attn_fwd_workspace_bytes(long_ring, 1) == 2 * 8 * 2**20 + 32 * 16 * 2**20 + 32 * 2**17
     # a short sequence (128 work items for 256 CUs): each block is cut into 3 pieces that run side by side,
     # + 3 fp32 partial O (16 MiB each) and 3 partial LSE (128 KiB each)
     short = usp.problem(1, 8192, 32, 8, 128, 8, 1, True)
@@ -114,6 +118,9 @@ def test_workspace_query_is_host_only_and_scales_with_the_problem(usp):
     # with room for dS (bf16, one 32 x 32 block per 2 KiB, both lengths rounded up to 256): 4 heads x 32768^2 x 2 bytes more
     assert usp.usp_attn_bwd_workspace_bytes_with_ds(p, 1) - usp.usp_attn_bwd_workspace_bytes(p, 1) == 4 * 32768**2 * 2
     assert usp.usp_attn_bwd_workspace_bytes_with_ds(short, 1) - usp.usp_attn_bwd_workspace_bytes(short, 1) == 4 * 8192**2 * 2
+    # the ring-only rank needs no head-layout copies at all: delta (0.5 MiB), fp32 dQ (64 MiB), and for each of the 8
+    # blocks fp32 dK and dV (4096 keys x 8 heads: 16 MiB) in two copies
+    assert usp.usp_attn_bwd_workspace_bytes(ring, 1) == 2**19 + (64 + 8 * 2 * 2 * 16) * 2**20
     # one rank of the ring: 32 heads, 8 blocks of 4096 keys for its 4096 queries
     assert (usp.usp_attn_bwd_workspace_bytes_with_ds(ring, 1) - usp.usp_attn_bwd_workspace_bytes(ring, 1)
             == 32 * 8 * 4096**2 * 2)
