@@ -182,8 +182,16 @@ class Workload:
             usp.usp_layout_a2a(pb, hkv, usp.USP_SEQ_TO_HEAD_VT, vb_, t, 0, 1)
             vt_blocks.append(t)
 
+        # ... unless the step reads V where it lies: with Ulysses degree 1 a block in head layout is its shard, and
+        # the library re-tiles V only when that pays (then its workspace holds the R re-tiled blocks)
+        v_in_place = U == 1 and usp.usp_attn_fwd_workspace_bytes(p, 1) < sum(t.numel() * 2 for t in vt_blocks)
+
         def attn_only():
-            usp.usp_ring_attn_fwd_vt(qh, k_blocks, vt_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, causal, qd)
+            if v_in_place:
+                usp.usp_ring_attn_fwd(qh, k_blocks, v_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, causal, qd,
+                                      usp.USP_BF16, usp.USP_BF16)
+            else:
+                usp.usp_ring_attn_fwd_vt(qh, k_blocks, vt_blocks, kds, o_ring, l_ring, bs, Lq, Lq, hq, hkv, hs, 0.0, causal, qd)
 
         for _ in range(warmup):
             attn_only()
