@@ -202,6 +202,16 @@ def test_usp_fwd_other_model_shapes(usp, name, bs, L, hc, hk, hs, U, R, causal):
         assert tl.max_abs(o[rank], ref_o[rank]) <= to, rank
 
 
+def test_usp_fwd_fp32_ring_only(usp):
+    """fp32 data, Ulysses degree 1: one launch per ring step on K/V blocks read in place (a block in head layout is its
+    shard), fp32 partials, merge."""
+    prob = tl.Problem(1001, 2, 512, 4, 2, 64, 1, 4, True, True, tl.FP32)
+    o, lse = _run_usp_fwd(usp, prob)
+    ref_o, to = _check_against_reference(prob, o, lse)
+    for rank in range(prob.N):
+        assert tl.max_abs(o[rank], ref_o[rank]) <= to, rank
+
+
 def test_usp_fwd_single_rank_range_and_batch(usp):
     prob = tl.Problem(78, 2, 1024, 8, 4, 128, 2, 2, True, True, tl.BF16)
     o, lse = _run_usp_fwd(usp, prob, 3, 4)                      # rank (r=1, u=1) only

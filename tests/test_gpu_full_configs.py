@@ -65,6 +65,16 @@ def test_full_size_forward_one_rank(usp, name, L, U, R, rank, samples):
             assert np.array_equal(o0[0, 0, h], v0[0, 0, h // g])
 
 
+def test_full_size_forward_mqa_ring_rank(usp):
+    """One KV head, ring only (Ulysses cannot split it): with Ulysses degree 1 K is read where the caller holds it,
+    and at this size V is still re-tiled into transposed tiles first (one head: cheap) - the mixed case."""
+    case = tl.OneRankCase(usp, 1234, 1, 32768, 32, 1, 128, 1, 8, 3)
+    assert 0 < usp.usp_attn_fwd_workspace_bytes(case.p, 1) == 8 * 2**20     # the 8 re-tiled V blocks, nothing else
+    case.forward()
+    _check_forward_rows(case, case.sample_rows(np.random.default_rng(4), 128))
+    assert torch.isfinite(case.lse[case.rank]).all()
+
+
 def _bwd_workspace(usp, p, keep_ds):
     """Backward workspace for one rank, every byte 0xFF (NaN as bf16 and fp32); with keep_ds of the size at which
     usp_attn_bwd keeps dS between its two kernels."""
